@@ -1,0 +1,152 @@
+/*
+ * fq.h -- C ABI of the fine-grained weight-only quantisation library for MI355X (gfx950).
+ *
+ * The library implements the hot path of "FineQuant: Unlocking Efficiency with
+ * Fine-Grained Weight-Only Quantization for LLMs": a linear abs-max symmetric
+ * quantiser with one half-precision scale per block of g consecutive rows of a
+ * column, and the fused dequantise-and-multiply product C = A . dequant(W).
+ *
+ * Conventions (all entry points):
+ *   - plain C, no exceptions; every int-returning call returns an fq_status.
+ *   - every buffer is CALLER-OWNED DEVICE memory unless the comment says "host";
+ *     the library neither allocates, frees nor retains any of them.
+ *   - matrices are row-major; the weight matrix is W[K, N] so that y = x . W and
+ *     a "column" is an output channel (section 4.1, "Quantization Method").
+ *   - device pointers must be 16-byte aligned.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Calls are asynchronous on that stream unless stated otherwise.
+ *   - arguments are validated on the host before anything is launched, so
+ *     invalid calls never touch the GPU.
+ */
+#ifndef FQ_H_
+#define FQ_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum fq_status {
+    FQ_OK = 0,
+    FQ_ERR_INVALID_ARG = 1, /* null pointer, negative size, bad enum, group size not dividing K */
+    FQ_ERR_UNSUPPORTED = 2, /* valid in principle, but outside what the kernels handle (see each call) */
+    FQ_ERR_WORKSPACE = 3,   /* workspace missing or smaller than fq_gemm_workspace_bytes() */
+    FQ_ERR_HIP = 4          /* a HIP runtime call failed (launch error, wrong device, ...) */
+} fq_status;
+
+typedef enum fq_dtype {
+    FQ_F16 = 0, /* IEEE binary16 activations and output */
+    FQ_BF16 = 1 /* bfloat16 activations and output */
+} fq_dtype;
+
+/* Shape limits shared by every call:
+ *   bits        4 or 8
+ *   N           multiple of 16
+ *   K           multiple of 128 (bits = 4) or 64 (bits = 8)
+ *   group_size  0 or K (one scale per column), or a multiple of 32 that divides K
+ *               (the paper plans "any power of 2 group size greater than 16",
+ *               section 5; multiples of 32 cover that from 32 up).
+ */
+
+/* Size in bytes of the packed code buffer: K*N*bits/8 (no padding).  0 on invalid arguments. */
+size_t fq_codes_bytes(int64_t K, int64_t N, int bits);
+
+/* Size in bytes of the scale matrix [K/g, N] of binary16 values.  0 on invalid arguments. */
+size_t fq_scales_bytes(int64_t K, int64_t N, int group_size);
+
+/* Bytes of scratch fq_gemm needs for this problem (split-K partial sums; may be 0).
+ * The value is an upper bound that depends only on the arguments. */
+size_t fq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits, int group_size);
+
+/* Same for fq_gemm_grouped, with total_rows = offsets[E]. */
+size_t fq_gemm_grouped_workspace_bytes(int64_t total_rows, int E, int64_t N, int64_t K, int bits,
+                                       int group_size);
+
+/*
+ * fq_quantize -- Appendix A ("Linear quantization with absolute maximum") applied per
+ * block of `group_size` consecutive rows of each column (section 4.1, "Quantization
+ * Method"), scales stored in half precision (Appendix B).
+ *
+ *   m = max |w| over the block;  s = smallest binary16 value with (2^bits - 1) * s >= 2 m;
+ *   q = clamp(round_half_even(w / s), -(2^(bits-1) - 1), +(2^(bits-1) - 1)), the quotient
+ *   taken in IEEE binary32;  an all-zero block gives s = 0, q = 0.
+ *
+ *   W_f16      in   [K, N] binary16, row-major, finite values
+ *   codes      out  fq_codes_bytes() bytes; opaque tiled layout consumed by fq_gemm / fq_unpack
+ *   scales_f16 out  [K/g, N] binary16, row-major
+ * Errors: FQ_ERR_INVALID_ARG (null pointers, bad bits, g not dividing K),
+ *         FQ_ERR_UNSUPPORTED (shape limits above), FQ_ERR_HIP.
+ */
+int fq_quantize(const void* W_f16, int64_t K, int64_t N, int bits, int group_size, void* codes,
+                void* scales_f16, void* stream);
+
+/*
+ * fq_unpack -- inverse of the packing step: writes the logical signed codes q[K, N]
+ * (int8, row-major) held in a packed buffer.  Used for parity checks and debugging.
+ */
+int fq_unpack(const void* codes, int64_t K, int64_t N, int bits, int8_t* q, void* stream);
+
+/*
+ * fq_choose_group -- the adaptive fine-grained heuristic of section 3.3: start from
+ * g_start (0 = one group per column), and while the halved size is an integer >= g_min,
+ * halve it if for ANY group the smaller abs-max of its two halves is below
+ * (1 - alpha) times the group's abs-max (comparison in binary32); stop at the first
+ * size for which no group changes that much.  One group size per matrix.
+ *
+ *   g_out  out  HOST pointer; receives the chosen group size.
+ * The call enqueues its kernels on `stream`, then SYNCHRONISES that stream to read
+ * the result back.  `workspace` is device scratch of at least
+ * fq_choose_group_workspace_bytes(K, N, g_start, g_min) bytes.
+ * The returned size is not checked against fq_gemm's limits (it may be odd multiples
+ * of small numbers when K has odd factors); callers pass g_start / g_min accordingly.
+ */
+size_t fq_choose_group_workspace_bytes(int64_t K, int64_t N, int g_start, int g_min);
+int fq_choose_group(const void* W_f16, int64_t K, int64_t N, int g_start, int g_min, float alpha,
+                    int* g_out, void* workspace, size_t workspace_bytes, void* stream);
+
+/*
+ * fq_gemm -- the fused dequantise-and-multiply product of section 4.1 ("GPU kernel
+ * implementations"):  C[m, n] = sum_k A[m, k] * (q[k, n] * s[k / g, n]),
+ * accumulated in binary32, written in the activation's data type.
+ *
+ *   A           in   [M, K] row-major, act_dtype
+ *   codes       in   packed codes written by fq_quantize for the same (K, N, bits)
+ *   scales_f16  in   [K/g, N] binary16
+ *   C           out  [M, N] row-major, act_dtype
+ *   workspace        device scratch, >= fq_gemm_workspace_bytes(M, N, K, bits, group_size)
+ *                    bytes (may be NULL when that is 0)
+ * M = 0 is a valid no-op.  Deterministic: the same inputs give the same bits.
+ * Errors: as fq_quantize, plus FQ_ERR_WORKSPACE.
+ */
+int fq_gemm(const void* A, int act_dtype, int64_t M, int64_t N, int64_t K, const void* codes,
+            const void* scales_f16, int bits, int group_size, void* C, void* workspace,
+            size_t workspace_bytes, void* stream);
+
+/*
+ * fq_gemm_grouped -- the same product for the expert FFNs of a mixture-of-experts
+ * layer (section 4.3): rows offsets[e] .. offsets[e+1]-1 of A (tokens sorted by
+ * expert) are multiplied by expert e's matrix.  Experts without rows are skipped
+ * and their weights are not read.
+ *
+ *   offsets_host  in  HOST array [E+1], non-decreasing, offsets[0] = 0
+ *   codes         in  E packed matrices back to back (fq_codes_bytes() apart)
+ *   scales_f16    in  E scale matrices back to back (fq_scales_bytes() apart)
+ *   A, C              [offsets[E], K] and [offsets[E], N]
+ * E <= 256.
+ */
+int fq_gemm_grouped(const void* A, int act_dtype, const int32_t* offsets_host, int E, int64_t N,
+                    int64_t K, const void* codes, const void* scales_f16, int bits, int group_size,
+                    void* C, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Human-readable name of a status code (static string, never NULL). */
+const char* fq_status_string(int status);
+
+/* Library version, "major.minor". */
+const char* fq_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* FQ_H_ */

@@ -1,0 +1,167 @@
+// C ABI of libfq: argument validation on the host, then dispatch to the launchers.
+// Every check happens before the first HIP call, so invalid calls never touch the GPU.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "fq_internal.h"
+#include "fq_layout.h"
+
+namespace {
+
+bool bits_ok(int bits) { return bits == 4 || bits == 8; }
+
+// Returns FQ_OK and the effective group size in *g_eff, or an error status.
+int check_shape(int64_t K, int64_t N, int bits, int group_size, int* g_eff) {
+    if (!bits_ok(bits) || K <= 0 || N <= 0 || group_size < 0) return FQ_ERR_INVALID_ARG;
+    const int64_t g = (group_size == 0) ? K : (int64_t)group_size;
+    if (g > K || K % g != 0) return FQ_ERR_INVALID_ARG;
+    if (K > (int64_t)1 << 24 || N > (int64_t)1 << 24) return FQ_ERR_UNSUPPORTED;
+    if (N % FQ_NTILE != 0 || K % fq_kblk(bits) != 0) return FQ_ERR_UNSUPPORTED;
+    if (g % 32 != 0) return FQ_ERR_UNSUPPORTED;
+    if (K / g > 65535) return FQ_ERR_UNSUPPORTED;
+    if (g_eff) *g_eff = (int)g;
+    return FQ_OK;
+}
+
+int halving_levels(int64_t g_top, int g_min) {
+    int levels = 0;
+    int64_t g = g_top;
+    while (g % 2 == 0 && g / 2 >= g_min) {
+        g /= 2;
+        ++levels;
+    }
+    return levels;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t fq_codes_bytes(int64_t K, int64_t N, int bits) {
+    if (!bits_ok(bits) || K <= 0 || N <= 0) return 0;
+    return (size_t)(K * N * bits / 8);
+}
+
+size_t fq_scales_bytes(int64_t K, int64_t N, int group_size) {
+    if (K <= 0 || N <= 0 || group_size < 0) return 0;
+    const int64_t g = group_size == 0 ? K : group_size;
+    if (g > K || K % g != 0) return 0;
+    return (size_t)((K / g) * N * 2);
+}
+
+size_t fq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits, int group_size) {
+    int g = 0;
+    if (M <= 0 || check_shape(K, N, bits, group_size, &g) != FQ_OK) return 0;
+    const fq_gemm_plan plan = fq_plan_gemm(M, N, K, bits, g);
+    return plan.splits > 1 ? (size_t)plan.splits * (size_t)M * (size_t)N * sizeof(float) : 0;
+}
+
+size_t fq_gemm_grouped_workspace_bytes(int64_t total_rows, int E, int64_t N, int64_t K, int bits,
+                                       int group_size) {
+    (void)total_rows; (void)E; (void)N; (void)K; (void)bits; (void)group_size;
+    return 0;
+}
+
+int fq_quantize(const void* W_f16, int64_t K, int64_t N, int bits, int group_size, void* codes,
+                void* scales_f16, void* stream) {
+    if (!W_f16 || !codes || !scales_f16) return FQ_ERR_INVALID_ARG;
+    int g = 0;
+    const int st = check_shape(K, N, bits, group_size, &g);
+    if (st != FQ_OK) return st;
+    return fq_launch_quantize(W_f16, K, N, bits, g, codes, scales_f16, (hipStream_t)stream);
+}
+
+int fq_unpack(const void* codes, int64_t K, int64_t N, int bits, int8_t* q, void* stream) {
+    if (!codes || !q) return FQ_ERR_INVALID_ARG;
+    const int st = check_shape(K, N, bits, 0, nullptr);
+    if (st != FQ_OK) return st;
+    return fq_launch_unpack(codes, K, N, bits, q, (hipStream_t)stream);
+}
+
+size_t fq_choose_group_workspace_bytes(int64_t K, int64_t N, int g_start, int g_min) {
+    if (K <= 0 || N <= 0 || g_start < 0 || g_min <= 0) return 0;
+    const int64_t g_top = g_start == 0 ? K : g_start;
+    if (g_top > K || K % g_top != 0) return 0;
+    const int levels = halving_levels(g_top, g_min);
+    const int64_t f = g_top >> levels;
+    return (size_t)(256 + (K / f) * N * 2);
+}
+
+int fq_choose_group(const void* W_f16, int64_t K, int64_t N, int g_start, int g_min, float alpha,
+                    int* g_out, void* workspace, size_t workspace_bytes, void* stream) {
+    if (!W_f16 || !g_out || K <= 0 || N <= 0 || g_start < 0 || g_min <= 0) return FQ_ERR_INVALID_ARG;
+    if (!(alpha >= 0.0f && alpha <= 1.0f)) return FQ_ERR_INVALID_ARG;
+    const int64_t g_top = g_start == 0 ? K : g_start;
+    if (g_top > K || K % g_top != 0) return FQ_ERR_INVALID_ARG;
+    if (N % 2 != 0 || K > (int64_t)1 << 24 || N > (int64_t)1 << 24) return FQ_ERR_UNSUPPORTED;
+    const int levels = halving_levels(g_top, g_min);
+    if (levels == 0) {
+        *g_out = (int)g_top;
+        return FQ_OK;
+    }
+    const int64_t f = g_top >> levels;
+    if (levels > 24 || K / f > 65535 || K / g_top > 65535) return FQ_ERR_UNSUPPORTED;
+    if (!workspace || workspace_bytes < fq_choose_group_workspace_bytes(K, N, g_start, g_min))
+        return FQ_ERR_WORKSPACE;
+    int flags[64];
+    const int st = fq_launch_choose_group(W_f16, K, N, (int)g_top, levels, alpha, flags, workspace,
+                                          (hipStream_t)stream);
+    if (st != FQ_OK) return st;
+    int64_t g = g_top;
+    for (int d = 0; d < levels; ++d) {
+        if (!flags[d]) break;
+        g /= 2;
+    }
+    *g_out = (int)g;
+    return FQ_OK;
+}
+
+int fq_gemm(const void* A, int act_dtype, int64_t M, int64_t N, int64_t K, const void* codes,
+            const void* scales_f16, int bits, int group_size, void* C, void* workspace,
+            size_t workspace_bytes, void* stream) {
+    if (M < 0 || (act_dtype != FQ_F16 && act_dtype != FQ_BF16)) return FQ_ERR_INVALID_ARG;
+    int g = 0;
+    const int st = check_shape(K, N, bits, group_size, &g);
+    if (st != FQ_OK) return st;
+    if (M == 0) return FQ_OK;
+    if (!A || !codes || !scales_f16 || !C) return FQ_ERR_INVALID_ARG;
+    if (M > (int64_t)1 << 24) return FQ_ERR_UNSUPPORTED;
+    const size_t need = fq_gemm_workspace_bytes(M, N, K, bits, group_size);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return FQ_ERR_WORKSPACE;
+    return fq_launch_gemm(A, act_dtype, M, N, K, codes, scales_f16, bits, g, C, workspace,
+                          (hipStream_t)stream);
+}
+
+int fq_gemm_grouped(const void* A, int act_dtype, const int32_t* offsets_host, int E, int64_t N,
+                    int64_t K, const void* codes, const void* scales_f16, int bits, int group_size,
+                    void* C, void* workspace, size_t workspace_bytes, void* stream) {
+    (void)workspace; (void)workspace_bytes;
+    if (!offsets_host || E < 0 || (act_dtype != FQ_F16 && act_dtype != FQ_BF16)) return FQ_ERR_INVALID_ARG;
+    if (E > 256) return FQ_ERR_UNSUPPORTED;
+    int g = 0;
+    const int st = check_shape(K, N, bits, group_size, &g);
+    if (st != FQ_OK) return st;
+    if (E == 0) return FQ_OK;
+    if (offsets_host[0] != 0) return FQ_ERR_INVALID_ARG;
+    for (int e = 0; e < E; ++e)
+        if (offsets_host[e + 1] < offsets_host[e]) return FQ_ERR_INVALID_ARG;
+    if (offsets_host[E] == 0) return FQ_OK;
+    if (!A || !codes || !scales_f16 || !C) return FQ_ERR_INVALID_ARG;
+    return fq_launch_gemm_grouped(A, act_dtype, offsets_host, E, N, K, codes, scales_f16, bits, g, C,
+                                  (hipStream_t)stream);
+}
+
+const char* fq_status_string(int status) {
+    switch (status) {
+        case FQ_OK: return "FQ_OK";
+        case FQ_ERR_INVALID_ARG: return "FQ_ERR_INVALID_ARG";
+        case FQ_ERR_UNSUPPORTED: return "FQ_ERR_UNSUPPORTED";
+        case FQ_ERR_WORKSPACE: return "FQ_ERR_WORKSPACE";
+        case FQ_ERR_HIP: return "FQ_ERR_HIP";
+        default: return "FQ_ERR_UNKNOWN";
+    }
+}
+
+const char* fq_version(void) { return "0.1"; }
+
+}  // extern "C"

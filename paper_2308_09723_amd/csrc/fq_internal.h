@@ -1,0 +1,32 @@
+// Internal launcher declarations shared by the translation units of libfq.
+#ifndef FQ_INTERNAL_H_
+#define FQ_INTERNAL_H_
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/fq.h"
+
+// quantiser side
+int fq_launch_quantize(const void* W, int64_t K, int64_t N, int bits, int g, void* codes, void* scales,
+                       hipStream_t stream);
+int fq_launch_unpack(const void* codes, int64_t K, int64_t N, int bits, int8_t* q, hipStream_t stream);
+int fq_launch_choose_group(const void* W, int64_t K, int64_t N, int g_top, int levels, float alpha,
+                           int* flags_host, void* workspace, hipStream_t stream);
+
+// product side
+struct fq_gemm_plan {
+    int kind;      // 0 = skinny (M <= 16), 1 = tiled
+    int mt;        // row tiles of 16 per block (tiled kernel)
+    int splits;    // split-K factor (>= 1)
+    int kb_per_split;
+};
+fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g);
+int fq_launch_gemm(const void* A, int act, int64_t M, int64_t N, int64_t K, const void* codes,
+                   const void* scales, int bits, int g, void* C, void* workspace, hipStream_t stream);
+int fq_launch_gemm_grouped(const void* A, int act, const int32_t* offsets, int E, int64_t N, int64_t K,
+                           const void* codes, const void* scales, int bits, int g, void* C,
+                           hipStream_t stream);
+
+#endif  // FQ_INTERNAL_H_

@@ -1,0 +1,265 @@
+// Quantiser, packer, unpacker and group-size heuristic kernels (gfx950).
+//
+// Appendix A: s = 2 max|w| / (2^b - 1), q = int(w / s); section 4.1: one scale per block
+// of g consecutive rows of a column; Appendix B: scales stored in half precision.
+// Rounding choices (scale rounded up to binary16, quotient in binary32, ties to even,
+// clamp) are stated in fq.h.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "fq_internal.h"
+#include "fq_layout.h"
+
+namespace {
+
+__device__ inline float half_bits_to_float(uint16_t b) {
+    return __half2float(__ushort_as_half(b));
+}
+
+// ---------------------------------------------------------------------------------
+// Scales: abs-max over each block of g rows, then the smallest binary16 s with
+// L * s >= 2 m.  Block = 64 x 4 threads: x covers 128 columns (two per thread), the four
+// y-slices split the block's rows and are combined through LDS.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void fq_scales_kernel(const uint16_t* __restrict__ W, int64_t K,
+                                                        int64_t N, int g, float L,
+                                                        uint16_t* __restrict__ scales) {
+    __shared__ uint32_t red[4][64];
+    const int tx = threadIdx.x, ty = threadIdx.y;
+    const int64_t n = ((int64_t)blockIdx.x * 64 + tx) * 2;
+    const int64_t grp = blockIdx.y;
+    uint32_t m0 = 0, m1 = 0;
+    if (n < N) {
+        const uint16_t* base = W + (grp * g) * N + n;
+        for (int r = ty; r < g; r += 4) {
+            const uint32_t v = *reinterpret_cast<const uint32_t*>(base + (int64_t)r * N);
+            const uint32_t a0 = v & 0x7fffu, a1 = (v >> 16) & 0x7fffu;
+            m0 = a0 > m0 ? a0 : m0;
+            m1 = a1 > m1 ? a1 : m1;
+        }
+    }
+    red[ty][tx] = m0 | (m1 << 16);
+    __syncthreads();
+    if (ty == 0 && n < N) {
+        uint32_t out = 0;
+        for (int c = 0; c < 2; ++c) {
+            uint32_t m = 0;
+            for (int y = 0; y < 4; ++y) {
+                const uint32_t v = (red[y][tx] >> (16 * c)) & 0xffffu;
+                m = v > m ? v : m;
+            }
+            const float two_m = 2.0f * half_bits_to_float((uint16_t)m);
+            const float t32 = __fdiv_rn(two_m, L);
+            uint32_t tb = __half_as_ushort(__float2half_rn(t32));
+            if (L * half_bits_to_float((uint16_t)tb) < two_m) tb += 1;   // next binary16 up
+            out |= tb << (16 * c);
+        }
+        *reinterpret_cast<uint32_t*>(scales + grp * N + n) = out;
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Encode + pack.  One wavefront produces one tile record set (16 columns x KBLK rows =
+// 1 KiB): lane (j, nl) walks the rows it owns, divides, rounds, clamps and assembles its
+// 16 bytes, which are stored with one 16-byte write per lane.
+// ---------------------------------------------------------------------------------
+__device__ inline int encode_one(uint16_t wbits, float s, int qmax) {
+    if (s == 0.0f) return 0;
+    const float r = rintf(__fdiv_rn(half_bits_to_float(wbits), s));
+    const float c = fminf(fmaxf(r, (float)-qmax), (float)qmax);
+    return (int)c;
+}
+
+template <int BITS>
+__global__ __launch_bounds__(256) void fq_encode_kernel(const uint16_t* __restrict__ W, int64_t K,
+                                                        int64_t N, int g,
+                                                        const uint16_t* __restrict__ scales,
+                                                        uint4* __restrict__ codes) {
+    constexpr int KBLK = BITS == 4 ? 128 : 64;
+    constexpr int STEPS = KBLK / FQ_KSTEP;
+    constexpr int QMAX = BITS == 4 ? 7 : 127;
+    const int lane = threadIdx.x & 63;
+    const int wave = threadIdx.x >> 6;
+    const int64_t ntiles = N / FQ_NTILE;
+    const int64_t ntile = (int64_t)blockIdx.x * 4 + wave;   // four neighbouring column tiles per block
+    const int64_t kb = blockIdx.y;
+    if (ntile >= ntiles) return;
+    const int nl = lane & 15, j = lane >> 4;
+    const int64_t n = ntile * FQ_NTILE + nl;
+    uint32_t rec[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+    for (int t = 0; t < STEPS; ++t) {
+        const int64_t k0 = kb * KBLK + t * FQ_KSTEP + j * 8;
+        const float s = half_bits_to_float(scales[(k0 / g) * N + n]);   // 8 rows share a group (g % 32 == 0)
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int q = encode_one(W[(k0 + e) * N + n], s, QMAX);
+            if (BITS == 4) {
+                rec[t] |= (uint32_t)(q + 8) << (4 * fq_nibble_slot(e));
+            } else {
+                rec[2 * t + (e >> 2)] |= (uint32_t)(q + 128) << (8 * (e & 3));
+            }
+        }
+    }
+    codes[(ntile * (K / KBLK) + kb) * 64 + lane] = make_uint4(rec[0], rec[1], rec[2], rec[3]);
+}
+
+// ---------------------------------------------------------------------------------
+// Unpack: one thread per logical element, writes are coalesced along N.
+// ---------------------------------------------------------------------------------
+template <int BITS>
+__global__ __launch_bounds__(256) void fq_unpack_kernel(const uint32_t* __restrict__ codes, int64_t K,
+                                                        int64_t N, int8_t* __restrict__ q) {
+    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    for (int64_t k = blockIdx.y; k < K; k += gridDim.y) {
+        const fq_pos p = fq_locate(k, n, K, BITS);
+        int v;
+        if (BITS == 4) {
+            const uint32_t w = codes[p.rec * 4 + p.t];
+            v = (int)((w >> (4 * fq_nibble_slot(p.e))) & 0xfu) - 8;
+        } else {
+            const uint32_t w = codes[p.rec * 4 + 2 * p.t + (p.e >> 2)];
+            v = (int)((w >> (8 * (p.e & 3))) & 0xffu) - 128;
+        }
+        q[k * N + n] = (int8_t)v;
+    }
+}
+
+// ---------------------------------------------------------------------------------
+// Heuristic (section 3.3).  Pass 1: abs-max of the finest blocks (f rows) -> fine[K/f, N]
+// as binary16 bit patterns.  Pass 2: one thread per (column, coarsest group) folds the
+// fine values pairwise, level by level, and sets flag[level] when the smaller child is
+// below thr * parent.  The host then walks the flags from the coarsest level down.
+// ---------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void fq_fine_absmax_kernel(const uint16_t* __restrict__ W, int64_t N,
+                                                             int f, uint16_t* __restrict__ fine) {
+    __shared__ uint32_t red[4][64];
+    const int tx = threadIdx.x, ty = threadIdx.y;
+    const int64_t n = ((int64_t)blockIdx.x * 64 + tx) * 2;
+    const int64_t blk = blockIdx.y;
+    uint32_t m0 = 0, m1 = 0;
+    if (n < N) {
+        const uint16_t* base = W + (blk * f) * N + n;
+        for (int r = ty; r < f; r += 4) {
+            const uint32_t v = *reinterpret_cast<const uint32_t*>(base + (int64_t)r * N);
+            const uint32_t a0 = v & 0x7fffu, a1 = (v >> 16) & 0x7fffu;
+            m0 = a0 > m0 ? a0 : m0;
+            m1 = a1 > m1 ? a1 : m1;
+        }
+    }
+    red[ty][tx] = m0 | (m1 << 16);
+    __syncthreads();
+    if (ty == 0 && n < N) {
+        uint32_t a = 0, b = 0;
+        for (int y = 0; y < 4; ++y) {
+            const uint32_t v = red[y][tx];
+            a = (v & 0xffffu) > a ? (v & 0xffffu) : a;
+            b = (v >> 16) > b ? (v >> 16) : b;
+        }
+        *reinterpret_cast<uint32_t*>(fine + blk * N + n) = a | (b << 16);
+    }
+}
+
+// levels = number of halvings covered; a top group spans 2^levels fine blocks.
+// flag[l] (l = 0 is the coarsest transition g_start -> g_start/2) is set to 1 when any
+// parent at that level has min(child) < thr * parent.
+__global__ __launch_bounds__(256) void fq_halving_flags_kernel(const uint16_t* __restrict__ fine,
+                                                               int64_t N, int64_t tops, int levels,
+                                                               float thr, int* __restrict__ flags) {
+    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t top = blockIdx.y;
+    if (n >= N || top >= tops) return;
+    const int64_t span = (int64_t)1 << levels;
+    const uint16_t* col = fine + (top * span) * N + n;
+    // Bottom-up fold with an explicit stack-free scheme: at level d (d = levels-1 is the
+    // finest transition) parents are pairs of nodes of size 2^(levels-1-d) fine blocks.
+    // Values are recomputed per level from the fine array; the total work per thread is
+    // span * levels reads, which is small (span <= a few hundred).
+    for (int d = 0; d < levels; ++d) {
+        const int64_t child = span >> (d + 1);     // fine blocks per child at this level
+        bool hit = false;
+        for (int64_t p = 0; p < span; p += 2 * child) {
+            uint32_t c0 = 0, c1 = 0;
+            for (int64_t i = 0; i < child; ++i) {
+                const uint32_t a = col[(p + i) * N];
+                const uint32_t b = col[(p + child + i) * N];
+                c0 = a > c0 ? a : c0;
+                c1 = b > c1 ? b : c1;
+            }
+            const float lo = half_bits_to_float((uint16_t)(c0 < c1 ? c0 : c1));
+            const float hi = half_bits_to_float((uint16_t)(c0 < c1 ? c1 : c0));
+            const float bound = __fmul_rn(thr, hi);
+            hit = hit || (lo < bound);
+        }
+        if (hit) atomicOr(&flags[d], 1);
+    }
+}
+
+__global__ void fq_zero_ints_kernel(int* p, int n) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+}  // namespace
+
+// ----------------------------------------------------------------------------- launchers
+int fq_launch_quantize(const void* W, int64_t K, int64_t N, int bits, int g, void* codes, void* scales,
+                       hipStream_t stream) {
+    const float L = (float)((1 << bits) - 1);
+    {
+        dim3 block(64, 4);
+        dim3 grid((unsigned)((N + 127) / 128), (unsigned)(K / g));
+        hipLaunchKernelGGL(fq_scales_kernel, grid, block, 0, stream, (const uint16_t*)W, K, N, g, L,
+                           (uint16_t*)scales);
+    }
+    {
+        const int kblk = fq_kblk(bits);
+        dim3 block(256);
+        dim3 grid((unsigned)((N / FQ_NTILE + 3) / 4), (unsigned)(K / kblk));
+        if (bits == 4)
+            hipLaunchKernelGGL(fq_encode_kernel<4>, grid, block, 0, stream, (const uint16_t*)W, K, N, g,
+                               (const uint16_t*)scales, (uint4*)codes);
+        else
+            hipLaunchKernelGGL(fq_encode_kernel<8>, grid, block, 0, stream, (const uint16_t*)W, K, N, g,
+                               (const uint16_t*)scales, (uint4*)codes);
+    }
+    return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;
+}
+
+int fq_launch_unpack(const void* codes, int64_t K, int64_t N, int bits, int8_t* q, hipStream_t stream) {
+    dim3 block(256);
+    dim3 grid((unsigned)((N + 255) / 256), (unsigned)(K < 16384 ? K : 16384));
+    if (bits == 4)
+        hipLaunchKernelGGL(fq_unpack_kernel<4>, grid, block, 0, stream, (const uint32_t*)codes, K, N, q);
+    else
+        hipLaunchKernelGGL(fq_unpack_kernel<8>, grid, block, 0, stream, (const uint32_t*)codes, K, N, q);
+    return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;
+}
+
+int fq_launch_choose_group(const void* W, int64_t K, int64_t N, int g_top, int levels, float alpha,
+                           int* flags_host, void* workspace, hipStream_t stream) {
+    // workspace: [flags: 64 ints][fine: (K / f) * N binary16]
+    int* flags = (int*)workspace;
+    uint16_t* fine = (uint16_t*)((char*)workspace + 256);
+    const int f = g_top >> levels;
+    hipLaunchKernelGGL(fq_zero_ints_kernel, dim3(1), dim3(64), 0, stream, flags, 64);
+    {
+        dim3 block(64, 4);
+        dim3 grid((unsigned)((N + 127) / 128), (unsigned)(K / f));
+        hipLaunchKernelGGL(fq_fine_absmax_kernel, grid, block, 0, stream, (const uint16_t*)W, N, f, fine);
+    }
+    {
+        const float thr = 1.0f - alpha;
+        dim3 block(256);
+        dim3 grid((unsigned)((N + 255) / 256), (unsigned)(K / g_top));
+        hipLaunchKernelGGL(fq_halving_flags_kernel, grid, block, 0, stream, (const uint16_t*)fine, N,
+                           K / g_top, levels, thr, flags);
+    }
+    if (hipGetLastError() != hipSuccess) return FQ_ERR_HIP;
+    if (hipMemcpyAsync(flags_host, flags, sizeof(int) * 64, hipMemcpyDeviceToHost, stream) != hipSuccess)
+        return FQ_ERR_HIP;
+    if (hipStreamSynchronize(stream) != hipSuccess) return FQ_ERR_HIP;
+    return FQ_OK;
+}

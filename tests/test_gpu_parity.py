@@ -1,0 +1,244 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle on the same seeded inputs.
+
+Codes and scales must match bit for bit; products must satisfy
+max|C - C_ref| <= 4e-3 max|C_ref| (fp16) / 1.6e-2 max|C_ref| (bf16).
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_2308_09723_amd import workloads
+
+from gpu_util import (TOL, assert_gemm_close, assert_quantizer_parity, from_dev_act, gpu_quantize, round_to_act,
+                      to_dev_act, torch_mod)
+
+pytestmark = pytest.mark.gpu
+
+
+def _fq():
+    from paper_2308_09723_amd import fq
+    return fq
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------ quantiser
+@pytest.mark.parametrize("bits,g", [(8, 0), (4, 128)])
+def test_quantize_config1(bits, g):
+    _say(f"quantize config1 bits={bits} g={g}")
+    _, W = workloads.config1(0)
+    assert_quantizer_parity(W, bits, g)
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("K,N,g", [(384, 80, 32), (512, 272, 64), (768, 48, 96), (1024, 16, 0), (256, 1040, 256)])
+def test_quantize_ragged_shapes_and_outliers(bits, K, N, g):
+    _say(f"quantize ragged bits={bits} K={K} N={N} g={g}")
+    W = workloads.weights_gaussian(K, N, seed=K + N + bits, outlier_prob=0.01)
+    assert_quantizer_parity(W, bits, g)
+    Wh = workloads.weights_heavy_tail(K, N, seed=K + N + bits + 1, col_prob=0.05)
+    assert_quantizer_parity(Wh, bits, g)
+
+
+@pytest.mark.parametrize("bits", [4, 8])
+def test_quantize_edge_values(bits):
+    _say(f"quantize edge values bits={bits}")
+    K, N, g = 256, 32, 64
+    W = workloads.weights_gaussian(K, N, seed=99)
+    W[:, 0] = 0                                   # all-zero column
+    W[:64, 1] = 0                                 # one all-zero group
+    W[:, 2] = np.float16(6e-8)                    # smallest subnormal everywhere
+    W[64:128, 3] = np.float16(6e-8)
+    W[70, 3] = np.float16(-1.2e-7)
+    W[0, 4] = np.float16(65504.0)
+    W[1, 4] = np.float16(-65504.0)
+    W[:, 5] = np.float16(6.1e-5)                  # smallest normal
+    # exact ties: with max 7.5 (int4) / 127.5 (int8) the scale is exactly 1
+    top = 7.5 if bits == 4 else 127.5
+    W[:64, 6] = np.float16(0.5)
+    W[0, 6] = np.float16(top)
+    W[1, 6] = np.float16(1.5)
+    W[2, 6] = np.float16(2.5)
+    W[3, 6] = np.float16(-3.5)
+    W[4, 6] = np.float16(-top)
+    _, _, q_ref, s_ref = assert_quantizer_parity(W, bits, g)
+    assert s_ref[0, 6] == np.float16(1.0) and q_ref[1, 6] == 2 and q_ref[2, 6] == 2 and q_ref[3, 6] == -4
+
+
+def test_quantize_exhaustive_quotient_window():
+    """Every (numerator, scale) pair of a dense window goes through the GPU divide/round path."""
+    _say("quantize exhaustive window")
+    s_vals = np.arange(0x2C00, 0x3000, 8, dtype=np.uint16).view(np.float16)      # 128 scales in [2^-4, 2^-3)
+    K = 2048
+    N = len(s_vals)
+    all16 = np.arange(0x1000, 0x3C00, dtype=np.uint16).view(np.float16)          # positive halves up to 1.0
+    W = np.empty((K, N), dtype=np.float16)
+    rng = np.random.default_rng(5)
+    for j, sj in enumerate(s_vals):
+        top = np.float16(float(sj) * 15 / 2.0)
+        cand = all16[all16 <= top]
+        col = rng.choice(cand, size=K, replace=True)
+        col[0] = top
+        sign = rng.integers(0, 2, size=K) * 2 - 1
+        W[:, j] = (col.astype(np.float32) * sign).astype(np.float16)
+    assert_quantizer_parity(W, 4, 0)
+
+
+# ------------------------------------------------------------------ product, oracle-sized cases
+def _gemm_case(M, K, N, dtype, bits, g, seed, heavy=False):
+    fq = _fq()
+    A = workloads.activations(M, K, dtype, seed)
+    if heavy:
+        W = workloads.weights_heavy_tail(K, N, seed + 1, col_prob=0.02)
+    else:
+        W = workloads.weights_gaussian(K, N, seed + 1, outlier_prob=1e-3)
+    codes, scales, q_ref, s_ref = assert_quantizer_parity(W, bits, g)
+    C_ref = oracle.gemm_ref(A, q_ref, s_ref)
+    Ad = to_dev_act(A, dtype)
+    C = from_dev_act(fq.gemm(Ad, codes, scales, bits, g), dtype)
+    rel = assert_gemm_close(C, C_ref, dtype, f"M={M} K={K} N={N} {dtype} int{bits} g={g}")
+    # determinism: a second call returns the same bits
+    C2 = from_dev_act(fq.gemm(Ad, codes, scales, bits, g), dtype)
+    assert np.array_equal(C, C2)
+    return rel
+
+
+def test_gemm_config1():
+    for bits, g in ((8, 0), (4, 128)):
+        _say(f"gemm config1 int{bits} g={g}")
+        fq = _fq()
+        A, W = workloads.config1(0)
+        codes, scales, q_ref, s_ref = assert_quantizer_parity(W, bits, g)
+        C = from_dev_act(fq.gemm(to_dev_act(A, "f16"), codes, scales, bits, g), "f16")
+        assert_gemm_close(C, oracle.gemm_ref(A, q_ref, s_ref), "f16", "config1")
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("bits,g", [(4, 32), (4, 64), (4, 128), (4, 256), (4, 0), (8, 32), (8, 64), (8, 128), (8, 0)])
+@pytest.mark.parametrize("M", [1, 5, 16])
+def test_gemm_small_m(dtype, bits, g, M):
+    _say(f"gemm small-M {dtype} int{bits} g={g} M={M}")
+    # 9 column tiles (ragged against the 4-tile wave groups), 6 k-blocks of 128
+    _gemm_case(M, 768, 144, dtype, bits, g, seed=1000 + M + bits + g)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("bits,g", [(4, 32), (4, 64), (4, 128), (4, 0), (8, 64), (8, 0)])
+@pytest.mark.parametrize("M", [17, 40, 130])
+def test_gemm_tiled(dtype, bits, g, M):
+    _say(f"gemm tiled {dtype} int{bits} g={g} M={M}")
+    _gemm_case(M, 768, 304, dtype, bits, g, seed=2000 + M + bits + g)
+
+
+@pytest.mark.parametrize("dtype,bits,g,M", [("f16", 4, 96, 8), ("bf16", 4, 192, 33), ("f16", 8, 96, 3), ("bf16", 8, 160, 70)])
+def test_gemm_group_sizes_that_are_not_powers_of_two(dtype, bits, g, M):
+    _say(f"gemm odd group {dtype} int{bits} g={g} M={M}")
+    K = 960 * 2 if g in (96, 160, 192) else 768           # 1920 = lcm-friendly: divisible by 96, 160, 192 and 128
+    _gemm_case(M, K, 64, dtype, bits, g, seed=3000 + g)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("bits", [4, 8])
+def test_gemm_heavy_tailed_weights(dtype, bits):
+    _say(f"gemm heavy tail {dtype} int{bits}")
+    for g in (32, 128, 0):
+        for M in (1, 16, 48):
+            _gemm_case(M, 1024, 224, dtype, bits, g, seed=4000 + M + g, heavy=True)
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+@pytest.mark.parametrize("bits,g", [(4, 32), (4, 128), (8, 0), (8, 32)])
+def test_gemm_one_hot_rows_return_the_dequantised_weights_exactly(dtype, bits, g):
+    """A = e_k: no accumulation error, so C must equal q*s rounded once to the output type.
+
+    Every k of two k-blocks is visited, which checks the packed layout element by element."""
+    _say(f"gemm one-hot {dtype} int{bits} g={g}")
+    fq = _fq()
+    K, N = 256, 48
+    W = workloads.weights_gaussian(K, N, seed=77 + bits, outlier_prob=0.01)
+    codes, scales, q_ref, s_ref = assert_quantizer_parity(W, bits, g)
+    gg = g or K
+    for k0 in range(0, K, 16):
+        A = np.zeros((16, K), dtype=np.float32)
+        for r in range(16):
+            A[r, k0 + r] = 1.0
+        A_in = A.astype(np.float16) if dtype == "f16" else A
+        C = from_dev_act(fq.gemm(to_dev_act(A_in, dtype), codes, scales, bits, g), dtype)
+        for r in range(16):
+            k = k0 + r
+            expect = round_to_act(q_ref[k].astype(np.float64) * s_ref[k // gg].astype(np.float64), dtype)
+            assert np.array_equal(C[r], expect), (k, dtype, bits, g)
+
+
+def test_gemm_rows_beyond_m_are_not_written():
+    _say("gemm guard rows")
+    fq = _fq()
+    torch = torch_mod()
+    K, N, M = 512, 128, 5
+    A = workloads.activations(M, K, "f16", 1)
+    W = workloads.weights_gaussian(K, N, 2)
+    codes, scales, q_ref, s_ref = assert_quantizer_parity(W, 4, 128)
+    for Mcase in (5, 21):
+        A = workloads.activations(Mcase, K, "f16", 1)
+        out = torch.full((Mcase + 3, N), 7.0, dtype=torch.float16, device="cuda")
+        fq.gemm(to_dev_act(A, "f16"), codes, scales, 4, 128, out=out[:Mcase])
+        host = out.cpu().numpy()
+        assert np.all(host[Mcase:] == 7.0)
+        assert_gemm_close(host[:Mcase].astype(np.float64), oracle.gemm_ref(A, q_ref, s_ref), "f16", "guard")
+
+
+# ------------------------------------------------------------------ heuristic
+def test_choose_group_matches_oracle():
+    fq = _fq()
+    torch = torch_mod()
+    cases = []
+    W = workloads.weights_gaussian(1024, 256, 11, outlier_prob=1e-3)
+    for alpha in (0.0, 0.3, 0.6, 0.75, 0.9, 0.97, 0.995, 1.0):
+        cases.append((W, 256, 64, alpha))
+        cases.append((W, 0, 32, alpha))
+    Wp = np.full((512, 64), 1.0, dtype=np.float16)
+    Wp[:64, 3] = 8.0
+    cases += [(Wp, 0, 16, 0.5), (Wp, 0, 16, 0.9), (Wp, 64, 16, 0.5)]
+    Wq = np.full((64, 32), 1.0, dtype=np.float16)
+    Wq[:32, 1] = 4.0
+    cases += [(Wq, 0, 32, 0.5), (Wq, 0, 32, 0.75), (Wq, 0, 32, 0.8)]
+    Wo = workloads.weights_gaussian(96 * 4, 32, 5)
+    cases += [(Wo, 96, 1, 0.0), (Wo, 0, 32, 0.0), (Wo, 0, 32, 0.4)]
+    for W_, gs, gm, alpha in cases:
+        _say(f"choose_group K={W_.shape[0]} N={W_.shape[1]} g_start={gs} g_min={gm} alpha={alpha}")
+        want = oracle.choose_group(W_, gs, gm, alpha)
+        got = fq.choose_group(torch.from_numpy(W_).cuda(), gs, gm, alpha)
+        assert got == want, (gs, gm, alpha, got, want)
+
+
+# ------------------------------------------------------------------ grouped (mixture of experts)
+@pytest.mark.parametrize("dtype,bits,g", [("f16", 4, 64), ("bf16", 4, 64), ("f16", 8, 0)])
+def test_grouped_gemm_small(dtype, bits, g):
+    _say(f"grouped small {dtype} int{bits} g={g}")
+    fq = _fq()
+    torch = torch_mod()
+    E, K, N = 6, 256, 96
+    rows = [70, 0, 1, 16, 130, 0]
+    offsets = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    A = workloads.activations(int(offsets[-1]), K, dtype, 8)
+    qs, ss, codes_l, scales_l = [], [], [], []
+    for e in range(E):
+        W = workloads.weights_gaussian(K, N, 50 + e, outlier_prob=1e-3)
+        c, s, q_ref, s_ref = assert_quantizer_parity(W, bits, g)
+        codes_l.append(c)
+        scales_l.append(s.reshape(-1))
+        qs.append(q_ref)
+        ss.append(s_ref)
+    codes = torch.cat(codes_l)
+    scales = torch.cat(scales_l)
+    out = torch.full((int(offsets[-1]), N), 3.0, dtype=torch.float16 if dtype == "f16" else torch.bfloat16, device="cuda")
+    fq.gemm_grouped(to_dev_act(A, dtype), offsets.tolist(), codes, scales, bits, g, N, out=out)
+    C = from_dev_act(out, dtype)
+    C_ref = oracle.gemm_ref_grouped(A, offsets, qs, ss)
+    assert_gemm_close(C, C_ref, dtype, "grouped")
+    for e in range(E):
+        if rows[e]:
+            sl = slice(offsets[e], offsets[e + 1])
+            assert_gemm_close(C[sl], C_ref[sl], dtype, f"expert {e}")

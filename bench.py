@@ -1,0 +1,237 @@
+#!/usr/bin/env python3
+"""Benchmark of the fused dequantise-and-multiply GEMM on one MI355X.
+
+Workload (benchmark configs[1]): the four weight matrices of an OPT-175B decoder layer
+(QKV 12288x36864, out-proj 12288x12288, FC1 12288x49152, FC2 49152x12288), int4 codes with one
+fp16 scale per 128 rows, fp16 activations, decode-sized M = 1 and M = 8.  One "step" is one
+pass over all eight products.  The metric is the weight-stream rate: bytes of packed codes and
+scales that the step must read, divided by the step time, with everything resident in HBM
+before the timed region.  Weights are synthetic (N(0, 0.02) with 0.1 % of entries x20) and are
+quantised on the GPU by fq_quantize before timing; the four matrices total 0.93 GB, far more
+than the 256 MB last-level cache, so consecutive products evict each other's weights.
+
+Prints ONE JSON line (see the keys below).  Usage: python bench.py [--gpus 1] [--steps K] [--warmup W]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published
+MFMA_PEAK_TFLOPS = 2500.0      # dense fp16 / bf16, published
+BITS = 4
+GROUP = 128
+DECODE_M = (1, 8)
+
+
+def make_weight(torch, K, N, seed):
+    """N(0, 0.02) with a Bernoulli(0.001) mask of entries multiplied by 20, as fp16 on the GPU."""
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(seed)
+    w = torch.randn((K, N), generator=gen, device="cuda", dtype=torch.float32) * 0.02
+    mask = torch.rand((K, N), generator=gen, device="cuda", dtype=torch.float32) < 1e-3
+    w = torch.where(mask, w * 20.0, w)
+    return w.to(torch.float16)
+
+
+def cpu_baseline(seconds_target=12.0):
+    """The CPU oracle timed on the host cores on a bounded sample of the same workload:
+    out-proj-shaped slab (K = 12288, 2048 columns), int4 g = 128, M = 1 and M = 8."""
+    import numpy as np
+
+    import oracle
+    from paper_2308_09723_amd import workloads
+
+    K, N = 12288, 2048
+    W = workloads.weights_gaussian(K, N, seed=7, outlier_prob=1e-3)
+    q, s = oracle.quantize(W, BITS, GROUP)          # not timed: quantisation is offline
+    acts = [workloads.activations(M, K, "f16", 11 + M) for M in DECODE_M]
+    wbytes = K * N * BITS // 8 + (K // GROUP) * N * 2
+    t0 = time.perf_counter()
+    passes = 0
+    while True:
+        for A in acts:
+            oracle.gemm_ref(A, q, s)
+        passes += 1
+        el = time.perf_counter() - t0
+        if el >= seconds_target or passes >= 2000:
+            break
+    rate = passes * len(acts) * wbytes / el / 1e12
+    return {
+        "value": rate,
+        "unit": "TB/s",
+        "cores": len(os.sched_getaffinity(0)),
+        "kind": "oracle",
+        "sample": f"K=12288 x N=2048 slab of the out-proj layer, int4 g=128, M in {list(DECODE_M)}, "
+                  f"{passes} passes in {el:.1f} s (fp64 dequantise + matmul; quantisation not timed)",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--large-m", action="store_true", help="also time the M >= 256 products (reported under 'extra')")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build targets one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    from paper_2308_09723_amd import fq, workloads
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    fq.load(build_if_missing=False)
+    torch.cuda.set_device(0)
+
+    layers = []
+    for i, (name, (K, N)) in enumerate(workloads.OPT175B_LAYERS.items()):
+        W = make_weight(torch, K, N, 100 + i)
+        codes, scales = fq.quantize(W, BITS, GROUP)
+        del W
+        layers.append((name, K, N, codes, scales))
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+
+    calls = []   # (name, M, A, codes, scales, C, workspace, weight_bytes, algorithmic_bytes)
+    for name, K, N, codes, scales in layers:
+        for M in DECODE_M:
+            gen = torch.Generator(device="cuda")
+            gen.manual_seed(1000 + M)
+            A = torch.randn((M, K), generator=gen, device="cuda", dtype=torch.float32).to(torch.float16)
+            C = torch.empty((M, N), device="cuda", dtype=torch.float16)
+            need = fq.gemm_workspace_bytes(M, N, K, BITS, GROUP)
+            ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+            wbytes = codes.numel() + scales.numel() * 2
+            abytes = wbytes + 2 * M * K + 2 * M * N
+            calls.append((name, M, A, codes, scales, C, ws, wbytes, abytes))
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def step(events=None):
+        for i, (name, M, A, codes, scales, C, ws, _, _) in enumerate(calls):
+            if events is not None:
+                events[i][0].record()
+            st = fq.gemm_raw(A.data_ptr(), fq.FQ_F16, M, C.shape[1], A.shape[1], codes.data_ptr(), scales.data_ptr(),
+                             BITS, GROUP, C.data_ptr(), ws.data_ptr(), ws.numel(), stream)
+            if st != fq.FQ_OK:
+                raise fq.FqError(st, "fq_gemm")
+            if events is not None:
+                events[i][1].record()
+
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    # timed region: exactly `steps` steps.  In every EVENT_STRIDE-th step HIP events (recorded on the
+    # launch stream) bracket each product; the other steps run back to back, because every event record
+    # is a command of its own and eight pairs per step would stretch the step by ~10 %.
+    EVENT_STRIDE = 8
+    ev = {k: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in calls]
+          for k in range(0, args.steps, EVENT_STRIDE)}
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for k in range(args.steps):
+        step(ev.get(k))
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+
+    ms_per_step = elapsed * 1e3 / args.steps
+    weight_bytes_step = sum(c[7] for c in calls)
+    value = weight_bytes_step / (elapsed / args.steps) / 1e12
+    # per-launch durations from the events
+    per_call_us = []
+    for i in range(len(calls)):
+        ts = [ev[k][i][0].elapsed_time(ev[k][i][1]) * 1e3 for k in ev]
+        per_call_us.append(sum(ts) / len(ts))
+    algo_bytes = sum(c[8] for c in calls)
+    kernel_us = sum(per_call_us)
+    achieved = algo_bytes / (kernel_us * 1e-6) / 1e9
+    per_layer = {f"{c[0]}_M{c[1]}": {"us": round(t, 2), "weight_TBps": round(c[7] / t / 1e6, 3),
+                                    "plan": fq.gemm_describe(c[1], c[5].shape[1], c[2].shape[1], BITS, GROUP)}
+                 for c, t in zip(calls, per_call_us)}
+
+    out = {
+        "metric": "W4A16 GEMM weight-stream rate, OPT-175B decode layers (M=1 and M=8)",
+        "value": round(value, 4),
+        "unit": "TB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f16",
+        "data": "synthetic",
+        "config": {
+            "workload": "BASELINE configs[1]: OPT-175B-shaped QKV/out-proj/FC1/FC2, fp16 activations M in {1, 8}, "
+                        "int4 weights, group_size 128, N(0,0.02) weights with 0.1% x20 outliers",
+            "products_per_step": len(calls),
+            "weight_bytes_per_step": weight_bytes_step,
+            "frac_of_hbm_peak": round(value * 1e3 / HBM_PEAK_GBS, 4),
+        },
+        "roofline": {
+            "bound": "hbm",
+            "achieved": round(achieved, 1),
+            "peak": HBM_PEAK_GBS,
+            "unit": "GB/s",
+            "frac": round(achieved / HBM_PEAK_GBS, 4),
+            "traffic": None,
+            "kernel": "fq_gemm_skinny_kernel (8 launches per step; sum of algorithmic bytes / sum of mean HIP-event durations)",
+            "algorithmic_bytes_per_step": algo_bytes,
+            "kernel_us_per_step": round(kernel_us, 2),
+        },
+        "per_product": per_layer,
+    }
+    if args.large_m:
+        out["extra"] = large_m_section(torch, fq, layers)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline()
+    print(json.dumps(out))
+
+
+def large_m_section(torch, fq, layers):
+    """Prefill-sized products on the same int4 weights (bf16 activations): TFLOP/s and fraction of MFMA peak."""
+    res = {}
+    stream = torch.cuda.current_stream().cuda_stream
+    for name, K, N, codes, scales in layers:
+        for M in (256, 2048):
+            A = torch.randn((M, K), device="cuda", dtype=torch.float32).to(torch.bfloat16)
+            C = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)
+            need = fq.gemm_workspace_bytes(M, N, K, BITS, GROUP)
+            ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+
+            def run():
+                st = fq.gemm_raw(A.data_ptr(), fq.FQ_BF16, M, N, K, codes.data_ptr(), scales.data_ptr(), BITS, GROUP,
+                                 C.data_ptr(), ws.data_ptr(), ws.numel(), stream)
+                if st != fq.FQ_OK:
+                    raise fq.FqError(st, "fq_gemm")
+            for _ in range(2):
+                run()
+            reps = 5
+            e0 = torch.cuda.Event(enable_timing=True)
+            e1 = torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(reps):
+                run()
+            e1.record()
+            torch.cuda.synchronize()
+            ms = e0.elapsed_time(e1) / reps
+            tflops = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+            res[f"{name}_M{M}"] = {"ms": round(ms, 4), "TFLOPs": round(tflops, 1),
+                                   "frac_of_mfma_peak": round(tflops / MFMA_PEAK_TFLOPS, 4),
+                                   "plan": fq.gemm_describe(M, N, K, BITS, GROUP)}
+    return res
+
+
+if __name__ == "__main__":
+    main()

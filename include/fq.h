@@ -140,6 +140,16 @@ int fq_gemm_grouped(const void* A, int act_dtype, const int32_t* offsets_host, i
                     int64_t K, const void* codes, const void* scales_f16, int bits, int group_size,
                     void* C, void* workspace, size_t workspace_bytes, void* stream);
 
+/*
+ * fq_gemm_describe -- writes a short text description of the kernel configuration fq_gemm
+ * would use for this problem (kernel family, tile shape, block shape, split-K factor) into
+ * buf (HOST memory, at most buf_bytes including the terminating 0).  For logs and benchmark
+ * reports; it launches nothing.  Returns FQ_OK, or the status fq_gemm would return for an
+ * invalid shape.
+ */
+int fq_gemm_describe(int64_t M, int64_t N, int64_t K, int bits, int group_size, char* buf,
+                     size_t buf_bytes);
+
 /* Human-readable name of a status code (static string, never NULL). */
 const char* fq_status_string(int status);
 

@@ -2,6 +2,7 @@
 // Every check happens before the first HIP call, so invalid calls never touch the GPU.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdio.h>
 
 #include "fq_internal.h"
 #include "fq_layout.h"
@@ -149,6 +150,26 @@ int fq_gemm_grouped(const void* A, int act_dtype, const int32_t* offsets_host, i
     if (!A || !codes || !scales_f16 || !C) return FQ_ERR_INVALID_ARG;
     return fq_launch_gemm_grouped(A, act_dtype, offsets_host, E, N, K, codes, scales_f16, bits, g, C,
                                   (hipStream_t)stream);
+}
+
+int fq_gemm_describe(int64_t M, int64_t N, int64_t K, int bits, int group_size, char* buf,
+                     size_t buf_bytes) {
+    if (!buf || buf_bytes == 0 || M < 0) return FQ_ERR_INVALID_ARG;
+    int g = 0;
+    const int st = check_shape(K, N, bits, group_size, &g);
+    if (st != FQ_OK) return st;
+    if (M == 0) {
+        snprintf(buf, buf_bytes, "empty");
+        return FQ_OK;
+    }
+    const fq_gemm_plan p = fq_plan_gemm(M, N, K, bits, g);
+    if (p.kind == 0)
+        snprintf(buf, buf_bytes, "small-m variant=%d gp=%d kw=%d au=%d waves=%d splits=%d", p.variant, p.gp,
+                 p.kw, p.au, p.waves, p.splits);
+    else
+        snprintf(buf, buf_bytes, "tiled mt=%d waves=%d splits=%d kb_per_split=%d", p.mt, p.waves, p.splits,
+                 p.kb_per_split);
+    return FQ_OK;
 }
 
 const char* fq_status_string(int status) {

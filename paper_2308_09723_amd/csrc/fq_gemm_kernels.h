@@ -1,0 +1,650 @@
+// Device code of the fused dequantise-and-multiply kernels (included by fq_gemm.hip).
+#ifndef FQ_GEMM_KERNELS_H_
+#define FQ_GEMM_KERNELS_H_
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "fq_internal.h"
+#include "fq_layout.h"
+
+namespace fqk {
+
+
+typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+
+template <typename T, typename F>
+__device__ inline T bitcast(const F& f) {
+    static_assert(sizeof(T) == sizeof(F), "size mismatch");
+    return __builtin_bit_cast(T, f);
+}
+
+template <int ACT>
+__device__ inline f32x4 mfma16x16x32(const u32x4& w, const u32x4& a, const f32x4& c) {
+    if constexpr (ACT == FQ_F16) {
+        return __builtin_amdgcn_mfma_f32_16x16x32_f16(bitcast<f16x8>(w), bitcast<f16x8>(a), c, 0, 0, 0);
+    } else {
+        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(bitcast<bf16x8>(w), bitcast<bf16x8>(a), c, 0, 0, 0);
+    }
+}
+
+// ------------------------------------------------------------------------------------------
+// Integer code -> matrix-core operand.  The result holds (q + OFFSET) exactly.
+//   fp16: the stored nibble/byte u is OR-ed into the mantissa of 1024.0 (0x6400), giving
+//         1024 + u (or 1024 + 16 u for the nibble that sits four bits higher), and one packed
+//         fp16 add / fma removes 1024 and the storage bias exactly:  OFFSET = 0.
+//   bf16: there is no packed bf16 arithmetic on gfx950, so the operand keeps a bias:
+//         4-bit: 0x4300 | u = 128 + u      -> OFFSET = 136 (= 128 + 8)
+//         8-bit: float(u) truncated to bf16 is exact for u <= 255 -> OFFSET = 128
+//         The bias is removed after the MFMA with the row sums of A over the same k-range,
+//         which an extra MFMA against an all-ones operand provides.
+// ------------------------------------------------------------------------------------------
+// (x & mask) | magic in one v_and_or_b32.  gfx9 VALU instructions can read only one
+// scalar/literal operand, so the magic constant is pinned in a vector register (the empty
+// asm hides its value from the constant folder); otherwise the compiler splits the
+// operation into v_and_b32 + v_or_b32.
+__device__ inline uint32_t vgpr_const(uint32_t c) {
+    asm volatile("" : "+v"(c));
+    return c;
+}
+__device__ inline uint32_t and_or(uint32_t x, uint32_t mask, uint32_t magic_v) { return (x & mask) | magic_v; }
+
+template <int ACT, int BITS>
+struct Dequant;
+
+template <>
+struct Dequant<FQ_F16, 4> {
+    static constexpr float OFFSET = 0.0f;
+    static __device__ inline uint32_t init() { return vgpr_const(0x64006400u); }
+    template <int T>
+    static __device__ inline u32x4 run(const u32x4& rec, uint32_t MAGIC) {
+        const uint32_t w = rec[T];
+        const uint32_t w8 = w >> 8;
+        const f16x2 lo0 = bitcast<f16x2>(and_or(w, 0x000f000fu, MAGIC));
+        const f16x2 hi0 = bitcast<f16x2>(and_or(w, 0x00f000f0u, MAGIC));
+        const f16x2 lo1 = bitcast<f16x2>(and_or(w8, 0x000f000fu, MAGIC));
+        const f16x2 hi1 = bitcast<f16x2>(and_or(w8, 0x00f000f0u, MAGIC));
+        const f16x2 sub = {(_Float16)1032.0f, (_Float16)1032.0f};
+        const f16x2 sc = {(_Float16)0.0625f, (_Float16)0.0625f};
+        const f16x2 off = {(_Float16)-72.0f, (_Float16)-72.0f};
+        u32x4 r;
+        r[0] = bitcast<uint32_t>(lo0 - sub);                                 // elements 0,1
+        r[1] = bitcast<uint32_t>(__builtin_elementwise_fma(hi0, sc, off));   // elements 2,3
+        r[2] = bitcast<uint32_t>(lo1 - sub);                                 // elements 4,5
+        r[3] = bitcast<uint32_t>(__builtin_elementwise_fma(hi1, sc, off));   // elements 6,7
+        return r;
+    }
+};
+
+template <>
+struct Dequant<FQ_F16, 8> {
+    static constexpr float OFFSET = 0.0f;
+    static __device__ inline uint32_t init() { return 0x64646464u; }
+    template <int T>
+    static __device__ inline u32x4 run(const u32x4& rec, uint32_t MAGIC) {
+        const uint32_t w0 = rec[2 * T], w1 = rec[2 * T + 1];
+        const f16x2 sub = {(_Float16)1152.0f, (_Float16)1152.0f};   // 1024 + 128
+        u32x4 r;
+        r[0] = bitcast<uint32_t>(bitcast<f16x2>(__builtin_amdgcn_perm(MAGIC, w0, 0x04010400u)) - sub);
+        r[1] = bitcast<uint32_t>(bitcast<f16x2>(__builtin_amdgcn_perm(MAGIC, w0, 0x04030402u)) - sub);
+        r[2] = bitcast<uint32_t>(bitcast<f16x2>(__builtin_amdgcn_perm(MAGIC, w1, 0x04010400u)) - sub);
+        r[3] = bitcast<uint32_t>(bitcast<f16x2>(__builtin_amdgcn_perm(MAGIC, w1, 0x04030402u)) - sub);
+        return r;
+    }
+};
+
+template <>
+struct Dequant<FQ_BF16, 4> {
+    static constexpr float OFFSET = 136.0f;
+    static __device__ inline uint32_t init() { return vgpr_const(0x43004300u); }
+    template <int T>
+    static __device__ inline u32x4 run(const u32x4& rec, uint32_t MAGIC) {
+        const uint32_t w = rec[T];
+        u32x4 r;
+        r[0] = and_or(w, 0x000f000fu, MAGIC);
+        r[1] = and_or(w >> 4, 0x000f000fu, MAGIC);
+        r[2] = and_or(w >> 8, 0x000f000fu, MAGIC);
+        r[3] = and_or(w >> 12, 0x000f000fu, MAGIC);
+        return r;
+    }
+};
+
+template <>
+struct Dequant<FQ_BF16, 8> {
+    static constexpr float OFFSET = 128.0f;
+    static __device__ inline uint32_t init() { return 0u; }
+    static __device__ inline uint32_t pair(uint32_t w, int lo_byte) {
+        const float f0 = (float)((w >> (8 * lo_byte)) & 0xffu);
+        const float f1 = (float)((w >> (8 * lo_byte + 8)) & 0xffu);
+        // upper halves of the two binary32 values (exact: at most 8 significant bits)
+        return __builtin_amdgcn_perm(bitcast<uint32_t>(f1), bitcast<uint32_t>(f0), 0x07060302u);
+    }
+    template <int T>
+    static __device__ inline u32x4 run(const u32x4& rec, uint32_t MAGIC) {
+        const uint32_t w0 = rec[2 * T], w1 = rec[2 * T + 1];
+        u32x4 r;
+        r[0] = pair(w0, 0);
+        r[1] = pair(w0, 2);
+        r[2] = pair(w1, 0);
+        r[3] = pair(w1, 2);
+        return r;
+    }
+};
+
+template <int ACT>
+__device__ inline u32x4 ones_operand() {
+    const uint32_t one2 = ACT == FQ_F16 ? 0x3c003c00u : 0x3f803f80u;
+    u32x4 r = {one2, one2, one2, one2};
+    return r;
+}
+
+__device__ inline f32x4 scales4(const uint16_t* p) {
+    // four consecutive binary16 scales -> binary32
+    const u32x2 v = *reinterpret_cast<const u32x2*>(p);
+    const f16x2 a = bitcast<f16x2>(v[0]);
+    const f16x2 b = bitcast<f16x2>(v[1]);
+    f32x4 r = {(float)a[0], (float)a[1], (float)b[0], (float)b[1]};
+    return r;
+}
+
+template <int ACT>
+__device__ inline u32x2 pack4(const f32x4& v) {
+    u32x2 r;
+    if constexpr (ACT == FQ_F16) {
+        const f16x2 a = {(_Float16)v[0], (_Float16)v[1]};
+        const f16x2 b = {(_Float16)v[2], (_Float16)v[3]};
+        r[0] = bitcast<uint32_t>(a);
+        r[1] = bitcast<uint32_t>(b);
+    } else {
+        typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+        const bf16x2 a = {(__bf16)v[0], (__bf16)v[1]};
+        const bf16x2 b = {(__bf16)v[2], (__bf16)v[3]};
+        r[0] = bitcast<uint32_t>(a);
+        r[1] = bitcast<uint32_t>(b);
+    }
+    return r;
+}
+
+// acc += s * (p - OFFSET * rowsum)
+template <int ACT, int BITS>
+__device__ inline void flush(f32x4& acc, const f32x4& p, const f32x4& s, float rowsum) {
+    constexpr float OFF = Dequant<ACT, BITS>::OFFSET;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float d = p[i];
+        if constexpr (OFF != 0.0f) d = __builtin_fmaf(-OFF, rowsum, d);
+        acc[i] = __builtin_fmaf(s[i], d, acc[i]);
+    }
+}
+
+// ==========================================================================================
+// Small-M kernel (M <= 16): the decode case, bound by the HBM read of the weights
+// (section 2.1, "Large weights with small activations").
+//
+// Block = GP column groups x KW k-workers (run-time values, GP * KW <= MAXW waves), one block
+// per compute unit and all blocks resident at once: a wave's loop is latency-bound, so a
+// second, partly filled round of blocks would cost as much as the first.  Wave (gi, kw) owns
+// NT column tiles and, in iteration `it`, k-block (sb * KW + kw) of super-block sb.
+//  - Weights and scales stream through a DEPTH-deep REGISTER ring per wave (NT KiB per stage);
+//    they never touch LDS.
+//  - The activation slice of a super-block (M rows x KW k-blocks) is fetched ONCE per block by
+//    a cooperative, coalesced load, DEPTH iterations ahead (two registers per lane in the same
+//    ring, so its age in the in-order memory queue equals that of the weights consumed with
+//    it), written to one of two LDS buffers and read back as MFMA fragments.  Fetching it per
+//    wave from L1/L2 instead costs four more vector loads per k-block and wave, and those, not
+//    HBM, were what limited the rate.
+//  - One barrier per iteration; the steady-state loop has no conditionals, so the memory
+//    counter waits only for the stage about to be consumed.
+//  - The KW partial results of a column group are added through LDS (fixed order); if the grid
+//    also splits K (grid_splits > 1) block sums go to a binary32 partial buffer.
+// PER_STEP = the scale changes inside a k-block (group size not a multiple of KBLK).
+// ==========================================================================================
+// AU = activation units (16 B) a lane fetches per super-block: M * KC <= AU * 64 * GP.
+template <int BITS, int NT, bool PER_STEP, int AU_>
+struct SkinnyStage {
+    static constexpr int STEPS = (BITS == 4 ? 128 : 64) / FQ_KSTEP;
+    static constexpr int SROWS = PER_STEP ? STEPS : 1;
+    static constexpr int AU = AU_;
+    u32x4 wq[NT];
+    u32x2 sc[SROWS][NT];
+    u32x4 areg[AU];
+};
+
+__device__ inline f32x4 scales4(const u32x2& v) {
+    const f16x2 a = bitcast<f16x2>(v[0]);
+    const f16x2 b = bitcast<f16x2>(v[1]);
+    f32x4 r = {(float)a[0], (float)a[1], (float)b[0], (float)b[1]};
+    return r;
+}
+
+// acc[nt] += (this wave's k-block of the stage) x (activation fragments af[0..STEPS))
+template <int ACT, int BITS, int NT, bool PER_STEP, int AU>
+__device__ inline void skinny_block(const SkinnyStage<BITS, NT, PER_STEP, AU>& sl,
+                                    const u32x4 (&af)[SkinnyStage<BITS, NT, PER_STEP, AU>::STEPS], uint32_t magic,
+                                    f32x4 (&acc)[NT]) {
+    constexpr int STEPS = SkinnyStage<BITS, NT, PER_STEP, AU>::STEPS;
+    constexpr float OFF = Dequant<ACT, BITS>::OFFSET;
+    const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+    if constexpr (!PER_STEP) {
+        f32x4 p[NT];
+        f32x4 psa = zero;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) p[nt] = zero;
+#pragma unroll
+        for (int t = 0; t < STEPS; ++t) {
+            const u32x4 a = af[t];
+            if constexpr (OFF != 0.0f) psa = mfma16x16x32<ACT>(ones_operand<ACT>(), a, psa);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                u32x4 w;
+                if (t == 0) w = Dequant<ACT, BITS>::template run<0>(sl.wq[nt], magic);
+                if (t == 1) w = Dequant<ACT, BITS>::template run<1>(sl.wq[nt], magic);
+                if (STEPS > 2 && t == 2) w = Dequant<ACT, BITS>::template run<2 % STEPS>(sl.wq[nt], magic);
+                if (STEPS > 2 && t == 3) w = Dequant<ACT, BITS>::template run<3 % STEPS>(sl.wq[nt], magic);
+                p[nt] = mfma16x16x32<ACT>(w, a, p[nt]);
+            }
+        }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) flush<ACT, BITS>(acc[nt], p[nt], scales4(sl.sc[0][nt]), psa[0]);
+    } else {
+#pragma unroll
+        for (int t = 0; t < STEPS; ++t) {
+            const u32x4 a = af[t];
+            f32x4 psa = zero;
+            if constexpr (OFF != 0.0f) psa = mfma16x16x32<ACT>(ones_operand<ACT>(), a, psa);
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                u32x4 w;
+                if (t == 0) w = Dequant<ACT, BITS>::template run<0>(sl.wq[nt], magic);
+                if (t == 1) w = Dequant<ACT, BITS>::template run<1>(sl.wq[nt], magic);
+                if (STEPS > 2 && t == 2) w = Dequant<ACT, BITS>::template run<2 % STEPS>(sl.wq[nt], magic);
+                if (STEPS > 2 && t == 3) w = Dequant<ACT, BITS>::template run<3 % STEPS>(sl.wq[nt], magic);
+                const f32x4 p = mfma16x16x32<ACT>(w, a, zero);
+                flush<ACT, BITS>(acc[nt], p, scales4(sl.sc[t % SkinnyStage<BITS, NT, PER_STEP, AU>::SROWS][nt]), psa[0]);
+            }
+        }
+    }
+}
+
+// LDS row pitch of the activation buffer in 16-byte units: 16 rows + 1 pad, so that both the
+// fragment reads (16 lanes = 16 rows of one unit column) and the staging writes (consecutive
+// lanes = consecutive unit columns of one row) spread over the banks.
+#define FQ_SK_PITCH 17
+
+template <int ACT, int BITS, int NT, int DEPTH, bool PER_STEP, int MAXW, int AU>
+__global__ __launch_bounds__(MAXW * 64) void fq_gemm_skinny_kernel(
+    const uint16_t* __restrict__ A, const u32x4* __restrict__ codes, const uint16_t* __restrict__ scales,
+    uint16_t* __restrict__ C, float* __restrict__ partial, int M, int N, int K, uint32_t g32,
+    uint32_t g32_recip, int gp, int kw_n, int grid_splits) {
+    constexpr int KBLK = BITS == 4 ? 128 : 64;
+    constexpr int STEPS = KBLK / FQ_KSTEP;
+    constexpr int KC = KBLK / 8;                    // 16-byte activation units per row and k-block
+    typedef SkinnyStage<BITS, NT, PER_STEP, AU> Stage;
+    extern __shared__ u32x4 lds[];   // two activation buffers [kw_n * KC][FQ_SK_PITCH]; later the reduction
+
+    const int tid = threadIdx.x;
+    const int nthreads = blockDim.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int gi = wave / kw_n;
+    const int kw = wave - gi * kw_n;
+    const int ntiles = N / FQ_NTILE;
+    const int ngroups = (ntiles + NT - 1) / NT;
+    const int bgroups = (ngroups + gp - 1) / gp;      // blocks per grid split
+    const int bx = blockIdx.x % bgroups;
+    const int gsplit = blockIdx.x / bgroups;          // < grid_splits
+    const int ng = bx * gp + gi;
+    const bool gvalid = ng < ngroups;
+    const int KB = K / KBLK;
+    const int SB = (KB + kw_n - 1) / kw_n;            // super-blocks of kw_n k-blocks
+    const int n_it = gsplit < SB ? (SB - gsplit + grid_splits - 1) / grid_splits : 0;   // block-uniform
+    const int64_t kb_stride = (int64_t)ntiles * 64;   // records between consecutive k-blocks of a tile
+    const int m = lane & 15, j = lane >> 4;
+    const bool mvalid = m < M;
+    const uint32_t magic = Dequant<ACT, BITS>::init();
+    const int abuf_units = kw_n * KC * FQ_SK_PITCH;
+
+    // Wave-uniform bases (scalar registers) plus one per-lane offset each.
+    const u32x4* wbase[NT];
+    const uint16_t* sbase[NT];
+    bool tvalid[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int tile = ng * NT + nt;
+        tvalid[nt] = gvalid && tile < ntiles;
+        const int tc = tvalid[nt] ? tile : 0;
+        wbase[nt] = codes + fq_rec(tc, 0, ntiles, 0);
+        sbase[nt] = scales + tc * FQ_NTILE;
+    }
+    const uint32_t s_off = (uint32_t)j * 4u;
+
+    // Cooperative activation fetch: unit u = tid + r * nthreads covers row u / upr, unit column
+    // u % upr of the super-block (upr = kw_n * KC units of 8 values per row).
+    const int upr = kw_n * KC;
+    int a_row[AU], a_col[AU];
+#pragma unroll
+    for (int r = 0; r < AU; ++r) {
+        const int u = tid + r * nthreads;
+        a_row[r] = u / upr;
+        a_col[r] = u - a_row[r] * upr;
+    }
+
+    f32x4 acc[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+
+    auto load_act = [&](u32x4 (&areg)[AU], int it) {
+        const int64_t k0 = (int64_t)(gsplit + it * grid_splits) * kw_n * KBLK;
+#pragma unroll
+        for (int r = 0; r < AU; ++r) {
+            int64_t k = k0 + a_col[r] * 8;
+            k = k < K ? k : K - 8;                       // past the end (tail super-block): never multiplied
+            areg[r] = a_row[r] < M ? *reinterpret_cast<const u32x4*>(A + (int64_t)a_row[r] * K + k) : zero4;
+        }
+    };
+    auto store_act = [&](const u32x4 (&areg)[AU], int buf) {
+#pragma unroll
+        for (int r = 0; r < AU; ++r)
+            if (a_row[r] < 16) lds[buf * abuf_units + a_col[r] * FQ_SK_PITCH + a_row[r]] = areg[r];
+    };
+    // stage `it`: this wave's weights and scales for iteration it, and the lane's share of the
+    // activations of iteration it + 1
+    auto load_stage = [&](Stage& sl, int it) {
+        int kb = (gsplit + it * grid_splits) * kw_n + kw;
+        kb = kb < KB ? kb : KB - 1;                      // tail super-block: idle workers re-read the last block
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) sl.wq[nt] = __builtin_nontemporal_load(wbase[nt] + (int64_t)kb * kb_stride + lane);
+#pragma unroll
+        for (int r = 0; r < Stage::SROWS; ++r) {
+            // scale row of 32-row step (kb * STEPS + r): an exact division by g / 32 done as a
+            // multiplication by its rounded-up reciprocal (valid while the step index < 2^32 / (g/32))
+            const uint32_t step = (uint32_t)kb * STEPS + (PER_STEP ? r : 0);
+            const uint32_t row = g32 == 1 ? step : __umulhi(step, g32_recip);
+            const int64_t srow = (int64_t)row * N;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                sl.sc[r][nt] = *reinterpret_cast<const u32x2*>(sbase[nt] + srow + s_off);
+        }
+        load_act(sl.areg, it + 1);
+    };
+    // one iteration: publish the next activations, read this iteration's fragments, multiply
+    auto iterate = [&](const Stage& sl, int it) {
+        store_act(sl.areg, (it + 1) & 1);
+        const int kb = (gsplit + it * grid_splits) * kw_n + kw;
+        u32x4 af[STEPS];
+        const u32x4* abuf = lds + (it & 1) * abuf_units + (kw * KC + j) * FQ_SK_PITCH + m;
+#pragma unroll
+        for (int t = 0; t < STEPS; ++t) af[t] = abuf[t * 4 * FQ_SK_PITCH];
+        if (gvalid && kb < KB) skinny_block<ACT, BITS, NT, PER_STEP, AU>(sl, af, magic, acc);
+    };
+
+    if (n_it > 0) {
+        {   // activations of iteration 0
+            u32x4 a0[AU];
+            load_act(a0, 0);
+            store_act(a0, 0);
+        }
+        Stage ring[DEPTH];
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d)
+            if (d < n_it) load_stage(ring[d], d);
+        __syncthreads();
+        int it = 0;
+        for (; it + 2 * DEPTH <= n_it; it += DEPTH) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                iterate(ring[d], it + d);
+                load_stage(ring[d], it + d + DEPTH);
+                __syncthreads();
+            }
+        }
+        // drain: at most 2 * DEPTH - 1 iterations are left, the first min(DEPTH, left) already loaded
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            if (it + d < n_it) {
+                iterate(ring[d], it + d);
+                if (it + d + DEPTH < n_it) load_stage(ring[d], it + d + DEPTH);
+                __syncthreads();
+            }
+        }
+#pragma unroll
+        for (int d = 0; d < DEPTH - 1; ++d) {
+            if (it + d + DEPTH < n_it) {
+                iterate(ring[d], it + d + DEPTH);
+                __syncthreads();
+            }
+        }
+    }
+
+    // combine the k-workers of each column group (fixed order: worker 1, 2, ... added to worker 0)
+    f32x4* red = reinterpret_cast<f32x4*>(lds);
+    if (kw > 0) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) red[(wave * NT + nt) * 64 + lane] = acc[nt];
+    }
+    __syncthreads();
+    if (kw != 0 || !mvalid) return;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        f32x4 v = acc[nt];
+        for (int w = 1; w < kw_n; ++w) {
+            const f32x4 o = red[((wave + w) * NT + nt) * 64 + lane];
+            v[0] += o[0]; v[1] += o[1]; v[2] += o[2]; v[3] += o[3];
+        }
+        if (!tvalid[nt]) continue;
+        const int64_t n = (int64_t)(ng * NT + nt) * FQ_NTILE + j * 4;
+        if (grid_splits == 1) {
+            *reinterpret_cast<u32x2*>(C + (int64_t)m * N + n) = pack4<ACT>(v);
+        } else {
+            *reinterpret_cast<f32x4*>(partial + ((int64_t)gsplit * M + m) * N + n) = v;
+        }
+    }
+}
+
+// Sum of split-K partials, fixed order, then conversion to the activation type.
+template <int ACT>
+__global__ __launch_bounds__(256) void fq_reduce_kernel(const float* __restrict__ partial, int splits,
+                                                        int64_t MN, uint16_t* __restrict__ C) {
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i >= MN) return;
+    f32x4 v = *reinterpret_cast<const f32x4*>(partial + i);
+    for (int s = 1; s < splits; ++s) {
+        const f32x4 o = *reinterpret_cast<const f32x4*>(partial + (int64_t)s * MN + i);
+        v[0] += o[0]; v[1] += o[1]; v[2] += o[2]; v[3] += o[3];
+    }
+    *reinterpret_cast<u32x2*>(C + i) = pack4<ACT>(v);
+}
+
+// ==========================================================================================
+// Tiled kernel (any M): the prefill / batched case (section 4.1: in compute-bound cases
+// the integer->float conversion, not the matrix-core math, is the bottleneck -- so each
+// weight record is converted exactly once per block and reused for all BM rows).
+//
+// Block = 4 waves.  All four share one activation tile (BM = 16 MT rows x KBLK) staged
+// through LDS with double buffering; wave w owns column tiles [4 bx + w) NT ... and converts
+// only its own weights, straight from its global-load registers.
+// LDS layout: 16-byte units (8 consecutive k of one row) at unit[kc * (BM + 1) + row];
+// a fragment read is 16 lanes x 16 contiguous bytes per lane group.
+// ==========================================================================================
+struct fq_group_items {
+    int count;
+    int32_t row0[256];
+    int16_t rows[256];
+    int16_t expert[256];
+};
+
+template <int ACT, int BITS, int MT, int NT, bool PER_STEP, bool GROUPED>
+__global__ __launch_bounds__(256) void fq_gemm_tile_kernel(
+    const uint16_t* __restrict__ A, const u32x4* __restrict__ codes, const uint16_t* __restrict__ scales,
+    uint16_t* __restrict__ C, float* __restrict__ partial, int M, int N, int K, int g, int kb_per_split,
+    int splits, int64_t codes_stride16, int64_t scales_stride, fq_group_items items) {
+    constexpr int KBLK = BITS == 4 ? 128 : 64;
+    constexpr int STEPS = KBLK / FQ_KSTEP;
+    constexpr int KC = KBLK / 8;             // 16-byte units per row and k-block
+    constexpr int BM = MT * 16;
+    constexpr int LDROW = BM + 1;
+    constexpr int UNITS = BM * KC;
+    constexpr int UPT = (UNITS + 255) / 256;  // units per thread
+    constexpr float OFF = Dequant<ACT, BITS>::OFFSET;
+    __shared__ u32x4 lds[2][KC * LDROW];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int ntiles = N / FQ_NTILE;
+    const int KB = K / KBLK;
+    const int split = blockIdx.z;
+    const int kb0 = split * kb_per_split;
+    const int kb1 = min(KB, kb0 + kb_per_split);
+    const int ml = lane & 15, j = lane >> 4;
+    const int64_t kb_stride = (int64_t)ntiles * 64;
+
+    int64_t row0;      // first row of this block in A / C
+    int rows;          // valid rows in this block
+    if constexpr (GROUPED) {
+        const int it = blockIdx.y;
+        row0 = items.row0[it];
+        rows = items.rows[it];
+        const int e = items.expert[it];
+        codes += (int64_t)e * codes_stride16;
+        scales += (int64_t)e * scales_stride;
+    } else {
+        row0 = (int64_t)blockIdx.y * BM;
+        rows = (int)min((int64_t)BM, (int64_t)M - row0);
+    }
+
+    const u32x4* wp[NT];
+    const uint16_t* sp[NT];
+    bool tvalid[NT];
+    const int tile0 = (blockIdx.x * 4 + wave) * NT;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int tile = tile0 + nt;
+        tvalid[nt] = tile < ntiles;
+        const int tc = tvalid[nt] ? tile : 0;
+        wp[nt] = codes + fq_rec(tc, 0, ntiles, lane);
+        sp[nt] = scales + tc * FQ_NTILE + j * 4;
+    }
+
+    // activation staging: unit u = tid + 256 r  ->  (row = u / KC, kc = u % KC)
+    const uint16_t* a_src[UPT];
+    int a_dst[UPT];
+    bool a_ok[UPT];
+#pragma unroll
+    for (int r = 0; r < UPT; ++r) {
+        const int u = tid + 256 * r;
+        const int row = u / KC, kc = u % KC;
+        a_ok[r] = (u < UNITS) && (row < rows);
+        a_src[r] = A + (row0 + (a_ok[r] ? row : 0)) * K + kc * 8;
+        a_dst[r] = (u < UNITS) ? kc * LDROW + row : -1;
+    }
+
+    f32x4 acc[MT][NT], p[MT][NT], psa[MT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        psa[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            p[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    }
+
+    const uint32_t magic = Dequant<ACT, BITS>::init();
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    u32x4 wq[NT], areg[UPT];
+    if (kb0 < kb1) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) wq[nt] = wp[nt][(int64_t)kb0 * kb_stride];
+#pragma unroll
+        for (int r = 0; r < UPT; ++r)
+            areg[r] = a_ok[r] ? *reinterpret_cast<const u32x4*>(a_src[r] + (int64_t)kb0 * KBLK) : zero4;
+    }
+    int buf = 0;
+    for (int kb = kb0; kb < kb1; ++kb) {
+#pragma unroll
+        for (int r = 0; r < UPT; ++r)
+            if (a_dst[r] >= 0) lds[buf][a_dst[r]] = areg[r];
+        __syncthreads();
+        // prefetch the next k-block into registers
+        u32x4 wq_n[NT];
+        const int kbn = kb + 1 < kb1 ? kb + 1 : kb;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) wq_n[nt] = wp[nt][(int64_t)kbn * kb_stride];
+#pragma unroll
+        for (int r = 0; r < UPT; ++r)
+            areg[r] = a_ok[r] ? *reinterpret_cast<const u32x4*>(a_src[r] + (int64_t)kbn * KBLK) : zero4;
+
+#pragma unroll
+        for (int t = 0; t < STEPS; ++t) {
+            u32x4 w[NT];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                if (t == 0) w[nt] = Dequant<ACT, BITS>::template run<0>(wq[nt], magic);
+                if (t == 1) w[nt] = Dequant<ACT, BITS>::template run<1>(wq[nt], magic);
+                if (STEPS > 2 && t == 2) w[nt] = Dequant<ACT, BITS>::template run<2 % STEPS>(wq[nt], magic);
+                if (STEPS > 2 && t == 3) w[nt] = Dequant<ACT, BITS>::template run<3 % STEPS>(wq[nt], magic);
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const u32x4 a = lds[buf][(t * 4 + j) * LDROW + mt * 16 + ml];
+                if constexpr (OFF != 0.0f) psa[mt] = mfma16x16x32<ACT>(ones_operand<ACT>(), a, psa[mt]);
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) p[mt][nt] = mfma16x16x32<ACT>(w[nt], a, p[mt][nt]);
+            }
+            bool do_flush;
+            int64_t srow;
+            if constexpr (PER_STEP) {
+                do_flush = true;
+                srow = (int64_t)((kb * KBLK + t * FQ_KSTEP) / g) * N;
+            } else {
+                const int kend = (kb + 1) * KBLK;
+                do_flush = (t == STEPS - 1) && (OFF != 0.0f || kend % g == 0 || kb == kb1 - 1);
+                srow = (int64_t)((kb * KBLK) / g) * N;
+            }
+            if (do_flush) {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const f32x4 s = scales4(sp[nt] + srow);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        flush<ACT, BITS>(acc[mt][nt], p[mt][nt], s, psa[mt][0]);
+                        p[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+                    }
+                }
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) psa[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
+            }
+        }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) wq[nt] = wq_n[nt];
+        buf ^= 1;
+    }
+
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int row = mt * 16 + ml;
+        if (row >= rows) continue;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            if (!tvalid[nt]) continue;
+            const int64_t n = (int64_t)(tile0 + nt) * FQ_NTILE + j * 4;
+            if (splits == 1) {
+                *reinterpret_cast<u32x2*>(C + (row0 + row) * N + n) = pack4<ACT>(acc[mt][nt]);
+            } else {
+                *reinterpret_cast<f32x4*>(partial + ((int64_t)split * M + row0 + row) * N + n) = acc[mt][nt];
+            }
+        }
+    }
+}
+
+
+}  // namespace fqk
+
+#endif  // FQ_GEMM_KERNELS_H_

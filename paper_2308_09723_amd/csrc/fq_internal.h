@@ -19,8 +19,12 @@ int fq_launch_choose_group(const void* W, int64_t K, int64_t N, int g_top, int l
 struct fq_gemm_plan {
     int kind;      // 0 = skinny (M <= 16), 1 = tiled
     int mt;        // row tiles of 16 per block (tiled kernel)
+    int waves;     // waves per block
+    int variant;   // small-M kernel: which compiled variant (NT, ring depth, register class)
+    int gp, kw;    // small-M kernel: column groups x k-workers per block
+    int au;        // small-M kernel: activation units a lane stages per super-block (1, 2 or 4)
     int splits;    // split-K factor (>= 1)
-    int kb_per_split;
+    int kb_per_split;   // k-blocks per grid split (tiled) or per wave (small-M)
 };
 fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g);
 int fq_launch_gemm(const void* A, int act, int64_t M, int64_t N, int64_t K, const void* codes,

@@ -6,9 +6,12 @@
 // 128-byte lines), and the 16 bytes a lane receives are exactly the values it feeds, as
 // they are, into v_mfma_f32_16x16x32 operands for one output column.
 //
-// Tile = 16 columns x KBLK rows, KBLK = 128 (4-bit) or 64 (8-bit), stored as
-//   codes[(ntile * (K / KBLK) + kblock) * 64 + lane] : 16 bytes
-// with lane = j * 16 + (n % 16), j in 0..3.  Inside a tile, row k (0 <= k < KBLK) is
+// Tile = 16 columns x KBLK rows, KBLK = 128 (4-bit) or 64 (8-bit), stored k-block-major:
+//   codes[(kblock * (N / 16) + ntile) * 64 + lane] : 16 bytes
+// with lane = j * 16 + (n % 16), j in 0..3.  All column tiles of one k-block are adjacent, so
+// the waves that work on neighbouring columns at the same time read one contiguous stripe
+// (like a plain streaming read), which keeps every HBM channel busy; a tile-major order
+// would put concurrently read KiB a multiple of 32 KiB apart for the usual K.  Inside a tile, row k (0 <= k < KBLK) is
 //   step t = k / 32, j = (k % 32) / 8, element e = k % 8
 // i.e. MFMA step t contracts rows [32 t, 32 t + 32) and lane group j supplies 8
 // consecutive rows of them.
@@ -35,7 +38,12 @@ struct fq_pos {
     int e;         // element 0..7 inside the step
 };
 
-__host__ __device__ inline fq_pos fq_locate(int64_t k, int64_t n, int64_t K, int bits) {
+// Index of the 16-byte record of (column tile, k-block, lane).
+__host__ __device__ inline int64_t fq_rec(int64_t ntile, int64_t kb, int64_t ntiles, int lane) {
+    return (kb * ntiles + ntile) * 64 + lane;
+}
+
+__host__ __device__ inline fq_pos fq_locate(int64_t k, int64_t n, int64_t N, int bits) {
     const int kblk = fq_kblk(bits);
     const int64_t ntile = n / FQ_NTILE;
     const int nl = (int)(n % FQ_NTILE);
@@ -45,7 +53,7 @@ __host__ __device__ inline fq_pos fq_locate(int64_t k, int64_t n, int64_t K, int
     p.t = kr / FQ_KSTEP;
     const int j = (kr % FQ_KSTEP) / 8;
     p.e = kr % 8;
-    p.rec = (ntile * (K / kblk) + kb) * 64 + (j * 16 + nl);
+    p.rec = fq_rec(ntile, kb, N / FQ_NTILE, j * 16 + nl);
     return p;
 }
 

@@ -102,7 +102,7 @@ __global__ __launch_bounds__(256) void fq_encode_kernel(const uint16_t* __restri
             }
         }
     }
-    codes[(ntile * (K / KBLK) + kb) * 64 + lane] = make_uint4(rec[0], rec[1], rec[2], rec[3]);
+    codes[fq_rec(ntile, kb, ntiles, lane)] = make_uint4(rec[0], rec[1], rec[2], rec[3]);
 }
 
 // ---------------------------------------------------------------------------------
@@ -114,7 +114,7 @@ __global__ __launch_bounds__(256) void fq_unpack_kernel(const uint32_t* __restri
     const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (n >= N) return;
     for (int64_t k = blockIdx.y; k < K; k += gridDim.y) {
-        const fq_pos p = fq_locate(k, n, K, BITS);
+        const fq_pos p = fq_locate(k, n, N, BITS);
         int v;
         if (BITS == 4) {
             const uint32_t w = codes[p.rec * 4 + p.t];

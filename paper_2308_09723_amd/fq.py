@@ -54,6 +54,7 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "fq_gemm": (i32, [vp, i32, i64, i64, i64, vp, vp, i32, i32, vp, vp, sz, vp]),
         "fq_gemm_grouped": (i32, [vp, i32, ctypes.POINTER(ctypes.c_int32), i32, i64, i64, vp, vp, i32, i32,
                                   vp, vp, sz, vp]),
+        "fq_gemm_describe": (i32, [i64, i64, i64, i32, i32, ctypes.c_char_p, sz]),
         "fq_status_string": (ctypes.c_char_p, [i32]),
         "fq_version": (ctypes.c_char_p, []),
     }
@@ -68,7 +69,7 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
 EXPORTED = [
     "fq_codes_bytes", "fq_scales_bytes", "fq_gemm_workspace_bytes", "fq_gemm_grouped_workspace_bytes",
     "fq_choose_group_workspace_bytes", "fq_quantize", "fq_unpack", "fq_choose_group", "fq_gemm",
-    "fq_gemm_grouped", "fq_status_string", "fq_version",
+    "fq_gemm_grouped", "fq_gemm_describe", "fq_status_string", "fq_version",
 ]
 
 
@@ -91,6 +92,14 @@ def scales_bytes(K, N, group_size):
 
 def gemm_workspace_bytes(M, N, K, bits, group_size):
     return int(load().fq_gemm_workspace_bytes(M, N, K, bits, group_size))
+
+
+def gemm_describe(M, N, K, bits, group_size):
+    buf = ctypes.create_string_buffer(256)
+    st = int(load().fq_gemm_describe(M, N, K, bits, group_size, buf, 256))
+    if st != FQ_OK:
+        raise FqError(st, "fq_gemm_describe")
+    return buf.value.decode()
 
 
 def choose_group_workspace_bytes(K, N, g_start, g_min):

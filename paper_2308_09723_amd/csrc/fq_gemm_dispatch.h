@@ -1,0 +1,180 @@
+// Host-side dispatch templates of the product kernels (included by the per-type translation
+// units fq_gemm_f16_4.hip ... so that they compile in parallel).
+#ifndef FQ_GEMM_DISPATCH_H_
+#define FQ_GEMM_DISPATCH_H_
+
+#include <math.h>
+#include <stdint.h>
+
+#include "fq_gemm_config.h"
+#include "fq_gemm_kernels.h"
+
+namespace fqd {
+
+using namespace fqk;
+
+
+using namespace fqk;
+
+template <int ACT, int BITS, int NT, int DEPTH, int MAXW, int AU>
+int launch_skinny(const void* A, int64_t M, int64_t N, int64_t K, const void* codes, const void* scales, int g,
+                  void* C, float* partial, const fq_gemm_plan& plan, hipStream_t stream) {
+    const int kblk = fq_kblk(BITS);
+    const bool per_step = (g % kblk) != 0;
+    const int ntiles = (int)(N / FQ_NTILE);
+    const int ngroups = (ntiles + NT - 1) / NT;
+    const int bgroups = (ngroups + plan.gp - 1) / plan.gp;
+    const int kc = kblk / 8;
+    const size_t lds_act = (size_t)2 * plan.kw * kc * FQ_SK_PITCH * 16;
+    const size_t lds_red = (size_t)plan.gp * plan.kw * NT * 64 * 16;
+    const size_t lds = lds_act > lds_red ? lds_act : lds_red;
+    const uint32_t g32 = (uint32_t)(g / 32);
+    const uint32_t g32_recip = (uint32_t)((((uint64_t)1 << 32) + g32 - 1) / g32);   // unused when g32 == 1
+    auto kern = per_step ? fq_gemm_skinny_kernel<ACT, BITS, NT, DEPTH, true, MAXW, AU>
+                         : fq_gemm_skinny_kernel<ACT, BITS, NT, DEPTH, false, MAXW, AU>;
+    if (lds > 65536) {
+        // more than the default dynamic LDS limit: raise it for this kernel (up to the 160 KiB of a CU)
+        if (lds > 160 * 1024) return FQ_ERR_UNSUPPORTED;
+        static bool raised[2] = {false, false};   // per instantiation: [per_step]
+        if (!raised[per_step ? 1 : 0]) {
+            if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    160 * 1024) != hipSuccess)
+                return FQ_ERR_HIP;
+            raised[per_step ? 1 : 0] = true;
+        }
+    }
+    hipLaunchKernelGGL(kern, dim3((unsigned)(bgroups * plan.splits)), dim3((unsigned)(plan.gp * plan.kw * 64)),
+                       lds, stream, (const uint16_t*)A, (const u32x4*)codes, (const uint16_t*)scales,
+                       (uint16_t*)C, partial, (int)M, (int)N, (int)K, g32, g32_recip, plan.gp, plan.kw,
+                       plan.splits);
+    return FQ_OK;
+}
+
+template <int ACT, int BITS, int NT, int DEPTH, int MAXW>
+int launch_skinny_au(const void* A, int64_t M, int64_t N, int64_t K, const void* codes, const void* scales,
+                     int g, void* C, float* partial, const fq_gemm_plan& plan, hipStream_t stream) {
+    switch (plan.au) {
+        case 1: return launch_skinny<ACT, BITS, NT, DEPTH, MAXW, 1>(A, M, N, K, codes, scales, g, C, partial, plan, stream);
+        case 2: return launch_skinny<ACT, BITS, NT, DEPTH, MAXW, 2>(A, M, N, K, codes, scales, g, C, partial, plan, stream);
+        default: return launch_skinny<ACT, BITS, NT, DEPTH, MAXW, 4>(A, M, N, K, codes, scales, g, C, partial, plan, stream);
+    }
+}
+
+template <int ACT, int BITS>
+int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* codes, const void* scales,
+                 int g, void* C, void* workspace, const fq_gemm_plan& plan, hipStream_t stream) {
+    const int kblk = fq_kblk(BITS);
+    const bool per_step = (g % kblk) != 0;
+    const int ntiles = (int)(N / FQ_NTILE);
+    float* partial = (float*)workspace;
+    if (plan.kind == 0) {
+        int st;
+        switch (plan.variant) {
+            case 0: st = launch_skinny_au<ACT, BITS, 3, 2, 12>(A, M, N, K, codes, scales, g, C, partial, plan, stream); break;
+            case 1: st = launch_skinny_au<ACT, BITS, 3, 3, 8>(A, M, N, K, codes, scales, g, C, partial, plan, stream); break;
+            case 2: st = launch_skinny_au<ACT, BITS, 1, 4, 12>(A, M, N, K, codes, scales, g, C, partial, plan, stream); break;
+            default: st = launch_skinny_au<ACT, BITS, 2, 3, 12>(A, M, N, K, codes, scales, g, C, partial, plan, stream); break;
+        }
+        if (st != FQ_OK) return st;
+    } else {
+        const int bm = plan.mt * 16;
+        const int nblocks_n = (ntiles + plan.waves * TILE_NT - 1) / (plan.waves * TILE_NT);
+        const int nblocks_m = (int)((M + bm - 1) / bm);
+        const size_t lds = (size_t)2 * (kblk / 8) * (bm + 1) * 16;
+        dim3 grid((unsigned)((int64_t)nblocks_n * nblocks_m * plan.splits));
+        fq_group_items none;
+        none.count = 0;
+#define FQ_MMA_LAUNCH(MT_, W_)                                                                          \
+    do {                                                                                                \
+        auto kern = per_step ? fq_gemm_mma_kernel<ACT, BITS, MT_, TILE_NT, W_, true, false>             \
+                             : fq_gemm_mma_kernel<ACT, BITS, MT_, TILE_NT, W_, false, false>;           \
+        if (lds > 65536) {                                                                              \
+            static bool raised[2] = {false, false};                                                     \
+            if (!raised[per_step ? 1 : 0]) {                                                            \
+                if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,  \
+                                        160 * 1024) != hipSuccess)                                      \
+                    return FQ_ERR_HIP;                                                                  \
+                raised[per_step ? 1 : 0] = true;                                                        \
+            }                                                                                           \
+        }                                                                                               \
+        hipLaunchKernelGGL(kern, grid, dim3(W_ * 64), lds, stream, (const uint16_t*)A,                  \
+                           (const u32x4*)codes, (const uint16_t*)scales, (uint16_t*)C, partial, (int)M, \
+                           (int)N, (int)K, g, plan.kb_per_split, plan.splits, nblocks_n, nblocks_m,     \
+                           (int64_t)0, (int64_t)0, none);                                               \
+    } while (0)
+        if (plan.waves == 8) {
+            if (plan.mt == 2) FQ_MMA_LAUNCH(2, 8);
+            else if (plan.mt == 4) FQ_MMA_LAUNCH(4, 8);
+            else FQ_MMA_LAUNCH(8, 8);
+        } else {
+            if (plan.mt == 2) FQ_MMA_LAUNCH(2, 4);
+            else if (plan.mt == 4) FQ_MMA_LAUNCH(4, 4);
+            else FQ_MMA_LAUNCH(8, 4);
+        }
+#undef FQ_MMA_LAUNCH
+    }
+    if (plan.splits > 1) {
+        const int64_t MN = M * N;
+        dim3 grid((unsigned)((MN / 4 + 255) / 256));
+        hipLaunchKernelGGL(fq_reduce_kernel<ACT>, grid, dim3(256), 0, stream, (const float*)partial,
+                           plan.splits, MN, (uint16_t*)C);
+    }
+    return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;
+}
+
+template <int ACT, int BITS>
+int launch_grouped_typed(const void* A, const int32_t* offsets, int E, int64_t N, int64_t K,
+                         const void* codes, const void* scales, int g, void* C, hipStream_t stream) {
+    constexpr int MT = 4;
+    constexpr int BM = MT * 16;
+    const int kblk = fq_kblk(BITS);
+    const bool per_step = (g % kblk) != 0;
+    const int ntiles = (int)(N / FQ_NTILE);
+    const int KB = (int)(K / kblk);
+    const int64_t codes_stride16 = (int64_t)(K * N * BITS / 8) / 16;
+    const int64_t scales_stride = (K / g) * N;
+    fq_group_items items;
+    items.count = 0;
+    auto flush_items = [&]() -> int {
+        if (items.count == 0) return FQ_OK;
+        dim3 grid((unsigned)((ntiles + 4 * TILE_NT - 1) / (4 * TILE_NT)), (unsigned)items.count, 1u);
+        auto kern = per_step ? fq_gemm_tile_kernel<ACT, BITS, MT, TILE_NT, true, true>
+                             : fq_gemm_tile_kernel<ACT, BITS, MT, TILE_NT, false, true>;
+        hipLaunchKernelGGL(kern, grid, dim3(256), 0, stream, (const uint16_t*)A, (const u32x4*)codes,
+                           (const uint16_t*)scales, (uint16_t*)C, (float*)nullptr, 0, (int)N, (int)K, g, KB, 1,
+                           codes_stride16, scales_stride, items);
+        items.count = 0;
+        return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;
+    };
+    for (int e = 0; e < E; ++e) {
+        for (int32_t r = offsets[e]; r < offsets[e + 1]; r += BM) {
+            const int i = items.count++;
+            items.row0[i] = r;
+            items.rows[i] = (int16_t)min(BM, offsets[e + 1] - r);
+            items.expert[i] = (int16_t)e;
+            if (items.count == 256) {
+                const int st = flush_items();
+                if (st != FQ_OK) return st;
+            }
+        }
+    }
+    return flush_items();
+}
+
+
+}  // namespace fqd
+
+// Explicitly instantiated once per (activation type, code width) in its own translation unit.
+#define FQ_INSTANTIATE_GEMM(ACT, BITS)                                                                     \
+    int fq_launch_typed_##ACT##_##BITS(const void* A, int64_t M, int64_t N, int64_t K, const void* codes,  \
+                                       const void* scales, int g, void* C, void* workspace,                \
+                                       const fq_gemm_plan& plan, hipStream_t stream) {                     \
+        return fqd::launch_typed<ACT, BITS>(A, M, N, K, codes, scales, g, C, workspace, plan, stream);     \
+    }                                                                                                      \
+    int fq_launch_grouped_typed_##ACT##_##BITS(const void* A, const int32_t* offsets, int E, int64_t N,    \
+                                               int64_t K, const void* codes, const void* scales, int g,    \
+                                               void* C, hipStream_t stream) {                              \
+        return fqd::launch_grouped_typed<ACT, BITS>(A, offsets, E, N, K, codes, scales, g, C, stream);     \
+    }
+
+#endif  // FQ_GEMM_DISPATCH_H_

@@ -1,4 +1,21 @@
-// Device code of the fused dequantise-and-multiply kernels (included by fq_gemm.hip).
+// Fused dequantise-and-multiply kernels for gfx950 (section 4.1, "GPU kernel
+// implementations": int4/int8 weights with a matrix of scales, fp16/bf16 activations,
+// floating-point matrix-core math, output in the activation type).
+//
+// Orientation: every product is computed as 16x16 tiles of C^T with
+// v_mfma_f32_16x16x32_{f16,bf16}.  The WEIGHTS are the first MFMA operand (its 16 rows are
+// 16 output columns n), the ACTIVATIONS the second (its 16 columns are 16 rows m of A).
+// A lane's 16-byte record of the packed layout is, after the integer->float step, directly
+// its slice of the first operand: weights never pass through LDS.  The result tile leaves
+// lane l with C[m = l % 16][n = 4 (l / 16) + 0..3], i.e. four consecutive columns of one row.
+//
+// Numerics: the integer codes are converted EXACTLY to the activation type (bf16 carries
+// them with a constant offset that is removed in binary32), multiplied on the matrix cores
+// with binary32 accumulation over one scale group (or one k-block), and the group's scale
+// is applied to that partial sum in binary32.  Nothing is rounded to 16 bits before the
+// final store.
+//
+// (device code; included by the per-type translation units through fq_gemm_dispatch.h)
 #ifndef FQ_GEMM_KERNELS_H_
 #define FQ_GEMM_KERNELS_H_
 
@@ -644,6 +661,301 @@ __global__ __launch_bounds__(256) void fq_gemm_tile_kernel(
     }
 }
 
+
+
+// ==========================================================================================
+// Large-M kernel (prefill): pre-scaled weights, one accumulator set.
+//
+// Section 4.1 reports that in compute-bound cases the integer->float conversion, not the
+// matrix-core math, limits such kernels.  Here every weight record is converted AND scaled
+// exactly once per block (by the one wave that owns its columns) and then reused for all
+// BM = 16 MT rows of the block straight from registers; the conversion cost per MFMA is
+// therefore 1/MT of a fragment conversion.  Scaling before the MFMA (the paper's order:
+// "dequantize the weights to match the data type of the activation") keeps a single set of
+// accumulators, which is what allows MT = 8.
+//   fp16: q (exact) * s rounded once to fp16          (relative error <= 2^-11 per weight)
+//   bf16: fma(u, s, -bias * s) in binary32 = q * s exactly, rounded once to bf16 (<= 2^-9)
+// Block = WAVES waves, all sharing one activation tile (BM x KBLK) staged through LDS with
+// double buffering; wave w owns column tiles [(bx * WAVES + w) * NT, +NT).
+// ==========================================================================================
+template <int ACT, int BITS>
+struct DequantScaled;
+
+template <>
+struct DequantScaled<FQ_F16, 4> {
+    // s2 = (s, s) as packed fp16
+    template <int T>
+    static __device__ inline u32x4 run(const u32x4& rec, uint32_t MAGIC, uint32_t s2) {
+        const u32x4 q = Dequant<FQ_F16, 4>::template run<T>(rec, MAGIC);
+        const f16x2 s = bitcast<f16x2>(s2);
+        u32x4 r;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = bitcast<uint32_t>(bitcast<f16x2>(q[i]) * s);
+        return r;
+    }
+};
+
+template <>
+struct DequantScaled<FQ_F16, 8> {
+    template <int T>
+    static __device__ inline u32x4 run(const u32x4& rec, uint32_t MAGIC, uint32_t s2) {
+        const u32x4 q = Dequant<FQ_F16, 8>::template run<T>(rec, MAGIC);
+        const f16x2 s = bitcast<f16x2>(s2);
+        u32x4 r;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) r[i] = bitcast<uint32_t>(bitcast<f16x2>(q[i]) * s);
+        return r;
+    }
+};
+
+__device__ inline uint32_t pack_bf16x2(float lo, float hi) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 v = {(__bf16)lo, (__bf16)hi};
+    return bitcast<uint32_t>(v);
+}
+
+template <>
+struct DequantScaled<FQ_BF16, 4> {
+    // s2 = binary32 bits of the scale
+    template <int T>
+    static __device__ inline u32x4 run(const u32x4& rec, uint32_t, uint32_t s2) {
+        const uint32_t w = rec[T];
+        const float s = bitcast<float>(s2);
+        const float b = -8.0f * s;
+        uint32_t lo = w & 0x0f0f0f0fu;          // nibbles 0,2,4,6 = elements 0,4,1,5
+        uint32_t hi = (w >> 4) & 0x0f0f0f0fu;   // nibbles 1,3,5,7 = elements 2,6,3,7
+        // opaque to the optimiser: byte k of lo / hi then converts with one v_cvt_f32_ubyte<k>
+        // instead of a bit-field extract plus a conversion
+        asm("" : "+v"(lo));
+        asm("" : "+v"(hi));
+        auto f = [&](uint32_t x, int byte) { return __builtin_fmaf((float)((x >> (8 * byte)) & 0xffu), s, b); };
+        u32x4 r;
+        r[0] = pack_bf16x2(f(lo, 0), f(lo, 2));
+        r[1] = pack_bf16x2(f(hi, 0), f(hi, 2));
+        r[2] = pack_bf16x2(f(lo, 1), f(lo, 3));
+        r[3] = pack_bf16x2(f(hi, 1), f(hi, 3));
+        return r;
+    }
+};
+
+template <>
+struct DequantScaled<FQ_BF16, 8> {
+    template <int T>
+    static __device__ inline u32x4 run(const u32x4& rec, uint32_t, uint32_t s2) {
+        const uint32_t w0 = rec[2 * T], w1 = rec[2 * T + 1];
+        const float s = bitcast<float>(s2);
+        const float b = -128.0f * s;
+        auto f = [&](uint32_t x, int byte) { return __builtin_fmaf((float)((x >> (8 * byte)) & 0xffu), s, b); };
+        u32x4 r;
+        r[0] = pack_bf16x2(f(w0, 0), f(w0, 1));
+        r[1] = pack_bf16x2(f(w0, 2), f(w0, 3));
+        r[2] = pack_bf16x2(f(w1, 0), f(w1, 1));
+        r[3] = pack_bf16x2(f(w1, 2), f(w1, 3));
+        return r;
+    }
+};
+
+// scale (binary16 bits) -> the form DequantScaled wants
+template <int ACT>
+__device__ inline uint32_t scale_operand(uint16_t h) {
+    if constexpr (ACT == FQ_F16) {
+        return (uint32_t)h | ((uint32_t)h << 16);
+    } else {
+        return bitcast<uint32_t>((float)bitcast<_Float16>(h));
+    }
+}
+
+template <int ACT, int BITS, int MT, int NT, int WAVES, bool PER_STEP, bool GROUPED>
+__global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
+    const uint16_t* __restrict__ A, const u32x4* __restrict__ codes, const uint16_t* __restrict__ scales,
+    uint16_t* __restrict__ C, float* __restrict__ partial, int M, int N, int K, int g, int kb_per_split,
+    int splits, int nblocks_n, int nblocks_m, int64_t codes_stride16, int64_t scales_stride,
+    fq_group_items items) {
+    constexpr int KBLK = BITS == 4 ? 128 : 64;
+    constexpr int STEPS = KBLK / FQ_KSTEP;
+    constexpr int KC = KBLK / 8;
+    constexpr int BM = MT * 16;
+    constexpr int LDROW = BM + 1;
+    constexpr int UNITS = BM * KC;
+    constexpr int NTHR = WAVES * 64;
+    constexpr int UPT = (UNITS + NTHR - 1) / NTHR;
+    constexpr int SROWS = PER_STEP ? STEPS : 1;
+    extern __shared__ u32x4 lds[];   // [2][KC * LDROW]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ntiles = N / FQ_NTILE;
+    const int KB = K / KBLK;
+    const int ml = lane & 15, j = lane >> 4;
+    const int64_t kb_stride = (int64_t)ntiles * 64;
+
+    // Block -> (n-block, m-block).  Consecutive block ids are dealt round-robin to the 8 XCDs,
+    // each with its own L2; the ids an XCD receives are mapped to one contiguous run of logical
+    // tiles, and logical tiles walk panels of PW n-blocks x all m-blocks, so that the blocks
+    // resident on an XCD at one time share activation rows and weight columns in its L2.
+    int bn, bm_idx, split;
+    {
+        const int per_split = nblocks_n * nblocks_m;
+        int bid = blockIdx.x;
+        split = bid / per_split;
+        bid -= split * per_split;
+        int L = bid;
+        if ((per_split & 7) == 0) L = (bid & 7) * (per_split >> 3) + (bid >> 3);
+        const int PW = nblocks_n < 4 ? nblocks_n : 4;
+        const int panel = L / (PW * nblocks_m);
+        const int within = L - panel * PW * nblocks_m;
+        const int pw_here = min(PW, nblocks_n - panel * PW);
+        bm_idx = within / pw_here;
+        bn = panel * PW + within - bm_idx * pw_here;
+    }
+    const int kb0 = split * kb_per_split;
+    const int kb1 = min(KB, kb0 + kb_per_split);
+
+    int64_t row0;
+    int rows;
+    if constexpr (GROUPED) {
+        row0 = items.row0[bm_idx];
+        rows = items.rows[bm_idx];
+        const int e = items.expert[bm_idx];
+        codes += (int64_t)e * codes_stride16;
+        scales += (int64_t)e * scales_stride;
+    } else {
+        row0 = (int64_t)bm_idx * BM;
+        rows = (int)min((int64_t)BM, (int64_t)M - row0);
+    }
+
+    const u32x4* wbase[NT];
+    const uint16_t* sbase[NT];
+    bool tvalid[NT];
+    const int tile0 = (bn * WAVES + wave) * NT;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int tile = tile0 + nt;
+        tvalid[nt] = tile < ntiles;
+        const int tc = tvalid[nt] ? tile : 0;
+        wbase[nt] = codes + fq_rec(tc, 0, ntiles, 0);
+        sbase[nt] = scales + tc * FQ_NTILE;
+    }
+
+    // activation staging: unit u = tid + NTHR r  ->  (row = u / KC, kc = u % KC)
+    uint32_t a_off[UPT];     // element offset of the unit inside A (relative to row0, k = 0)
+    int a_dst[UPT];
+    bool a_ok[UPT];
+#pragma unroll
+    for (int r = 0; r < UPT; ++r) {
+        const int u = tid + NTHR * r;
+        const int row = u / KC, kc = u % KC;
+        a_ok[r] = (u < UNITS) && (row < rows);
+        a_off[r] = (uint32_t)(a_ok[r] ? row : 0) * (uint32_t)K + (uint32_t)kc * 8u;
+        a_dst[r] = (u < UNITS) ? kc * LDROW + row : -1;
+    }
+    const uint16_t* Arow = A + row0 * K;
+
+    f32x4 acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+    const uint32_t magic = Dequant<ACT, BITS>::init();
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    u32x4 wq[NT], areg[UPT];
+    uint16_t sc[SROWS][NT];
+    auto load_w = [&](u32x4 (&q)[NT], uint16_t (&s)[SROWS][NT], int kb) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) q[nt] = (wbase[nt] + (int64_t)kb * kb_stride)[lane];
+#pragma unroll
+        for (int r = 0; r < SROWS; ++r) {
+            const int64_t srow = (int64_t)((kb * KBLK + r * FQ_KSTEP) / g) * N;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) s[r][nt] = sbase[nt][srow + ml];
+        }
+    };
+    auto load_a = [&](u32x4 (&a)[UPT], int kb) {
+        const uint16_t* base = Arow + (int64_t)kb * KBLK;
+#pragma unroll
+        for (int r = 0; r < UPT; ++r) a[r] = a_ok[r] ? *reinterpret_cast<const u32x4*>(base + a_off[r]) : zero4;
+    };
+
+    if (kb0 < kb1) {
+        load_w(wq, sc, kb0);
+        load_a(areg, kb0);
+    }
+    int buf = 0;
+    const int abuf_units = KC * LDROW;
+    for (int kb = kb0; kb < kb1; ++kb) {
+#pragma unroll
+        for (int r = 0; r < UPT; ++r)
+            if (a_dst[r] >= 0) lds[buf * abuf_units + a_dst[r]] = areg[r];
+        __syncthreads();
+        // prefetch the next k-block into registers
+        u32x4 wq_n[NT];
+        uint16_t sc_n[SROWS][NT];
+        const int kbn = kb + 1 < kb1 ? kb + 1 : kb;
+        load_w(wq_n, sc_n, kbn);
+        load_a(areg, kbn);
+
+        // Activation fragments are read from LDS APD fragments ahead of the MFMAs that use them
+        // (a rotating window of APD + 1 registers sets), so the LDS latency is covered by matrix
+        // work instead of being waited for in front of every fragment.
+        const u32x4* abuf = lds + buf * abuf_units + j * LDROW + ml;
+        constexpr int NFR = STEPS * MT;
+        constexpr int APD = 3;
+        u32x4 afr[APD + 1];
+#pragma unroll
+        for (int i = 0; i < APD && i < NFR; ++i) afr[i] = abuf[((i / MT) * 4) * LDROW + (i % MT) * 16];
+#pragma unroll
+        for (int t = 0; t < STEPS; ++t) {
+            u32x4 w[NT];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+                const uint32_t s2 = scale_operand<ACT>(sc[PER_STEP ? t : 0][nt]);
+                if (t == 0) w[nt] = DequantScaled<ACT, BITS>::template run<0>(wq[nt], magic, s2);
+                if (t == 1) w[nt] = DequantScaled<ACT, BITS>::template run<1>(wq[nt], magic, s2);
+                if (STEPS > 2 && t == 2) w[nt] = DequantScaled<ACT, BITS>::template run<2 % STEPS>(wq[nt], magic, s2);
+                if (STEPS > 2 && t == 3) w[nt] = DequantScaled<ACT, BITS>::template run<3 % STEPS>(wq[nt], magic, s2);
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const int i = t * MT + mt;
+                if (i + APD < NFR) {
+                    const int ip = i + APD;
+                    afr[ip % (APD + 1)] = abuf[((ip / MT) * 4) * LDROW + (ip % MT) * 16];
+                }
+                // keep the read above where it is: without this the scheduler sinks it next to its
+                // use (to save registers) and every fragment is then waited for
+                __builtin_amdgcn_sched_barrier(0);
+                const u32x4 a = afr[i % (APD + 1)];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = mfma16x16x32<ACT>(w[nt], a, acc[mt][nt]);
+            }
+        }
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) wq[nt] = wq_n[nt];
+#pragma unroll
+        for (int r = 0; r < SROWS; ++r)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) sc[r][nt] = sc_n[r][nt];
+        buf ^= 1;
+    }
+
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int row = mt * 16 + ml;
+        if (row >= rows) continue;
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            if (!tvalid[nt]) continue;
+            const int64_t n = (int64_t)(tile0 + nt) * FQ_NTILE + j * 4;
+            if (splits == 1) {
+                *reinterpret_cast<u32x2*>(C + (row0 + row) * N + n) = pack4<ACT>(acc[mt][nt]);
+            } else {
+                *reinterpret_cast<f32x4*>(partial + ((int64_t)split * M + row0 + row) * N + n) = acc[mt][nt];
+            }
+        }
+    }
+}
 
 }  // namespace fqk
 

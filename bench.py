@@ -79,6 +79,10 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--large-m", action="store_true", help="also time the M >= 256 products (reported under 'extra')")
+    ap.add_argument("--profile", choices=["decode", "prefill", "copy"], default=None,
+                    help="short untimed run of one case for rocprofv3 (no JSON line): 'decode' = the benchmark "
+                         "step, 'prefill' = QKV-shaped product at M = 2048 (bf16), 'copy' = a 1 GiB device copy "
+                         "whose FETCH_SIZE / WRITE_SIZE calibrate the counters")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build targets one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
@@ -93,6 +97,16 @@ def main():
         sys.exit(1)
     fq.load(build_if_missing=False)
     torch.cuda.set_device(0)
+    if args.profile == "copy":
+        src = torch.empty(1 << 30, dtype=torch.uint8, device="cuda").zero_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        return
+    if args.profile == "prefill":
+        profile_prefill(torch, fq, workloads, args.steps)
+        return
 
     layers = []
     for i, (name, (K, N)) in enumerate(workloads.OPT175B_LAYERS.items()):
@@ -131,6 +145,11 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    if args.profile == "decode":
+        for _ in range(args.steps):
+            step()
+        torch.cuda.synchronize()
+        return
     # timed region: exactly `steps` steps.  In every EVENT_STRIDE-th step HIP events (recorded on the
     # launch stream) bracket each product; the other steps run back to back, because every event record
     # is a command of its own and eight pairs per step would stretch the step by ~10 %.
@@ -197,6 +216,26 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
+
+
+def profile_prefill(torch, fq, workloads, reps):
+    """QKV-shaped product at M = 2048 with bf16 activations, `reps` launches (for rocprofv3)."""
+    K, N = workloads.OPT175B_LAYERS["qkv"]
+    M = 2048
+    W = make_weight(torch, K, N, 100)
+    codes, scales = fq.quantize(W, BITS, GROUP)
+    del W
+    A = torch.randn((M, K), device="cuda", dtype=torch.float32).to(torch.bfloat16)
+    C = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)
+    need = fq.gemm_workspace_bytes(M, N, K, BITS, GROUP)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    for _ in range(max(1, min(reps, 20))):
+        st = fq.gemm_raw(A.data_ptr(), fq.FQ_BF16, M, N, K, codes.data_ptr(), scales.data_ptr(), BITS, GROUP,
+                         C.data_ptr(), ws.data_ptr(), ws.numel(), stream)
+        if st != fq.FQ_OK:
+            raise fq.FqError(st, "fq_gemm")
+    torch.cuda.synchronize()
 
 
 def large_m_section(torch, fq, layers):

@@ -85,8 +85,8 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
         p.mt = M <= 32 ? 2 : (M <= 64 ? 4 : 8);
         const int bm = p.mt * 16;
         const int64_t nbm = (M + bm - 1) / bm;
-        const int64_t blocks8 = ((ntiles + 8 * TILE_NT - 1) / (8 * TILE_NT)) * nbm;
-        const int64_t blocks4 = ((ntiles + 4 * TILE_NT - 1) / (4 * TILE_NT)) * nbm;
+        const int64_t blocks8 = ((ntiles + 8 * MMA_NT - 1) / (8 * MMA_NT)) * nbm;
+        const int64_t blocks4 = ((ntiles + 4 * MMA_NT - 1) / (4 * MMA_NT)) * nbm;
         p.waves = blocks8 >= 512 ? 8 : 4;
         const int64_t blocks = p.waves == 8 ? blocks8 : blocks4;
         int splits = 1;

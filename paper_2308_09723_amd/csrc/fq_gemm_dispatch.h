@@ -78,7 +78,7 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
         if (st != FQ_OK) return st;
     } else {
         const int bm = plan.mt * 16;
-        const int nblocks_n = (ntiles + plan.waves * TILE_NT - 1) / (plan.waves * TILE_NT);
+        const int nblocks_n = (ntiles + plan.waves * MMA_NT - 1) / (plan.waves * MMA_NT);
         const int nblocks_m = (int)((M + bm - 1) / bm);
         const size_t lds = (size_t)2 * (kblk / 8) * (bm + 1) * 16;
         dim3 grid((unsigned)((int64_t)nblocks_n * nblocks_m * plan.splits));
@@ -86,8 +86,8 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
         none.count = 0;
 #define FQ_MMA_LAUNCH(MT_, W_)                                                                          \
     do {                                                                                                \
-        auto kern = per_step ? fq_gemm_mma_kernel<ACT, BITS, MT_, TILE_NT, W_, true, false>             \
-                             : fq_gemm_mma_kernel<ACT, BITS, MT_, TILE_NT, W_, false, false>;           \
+        auto kern = per_step ? fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, true, false>             \
+                             : fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, false, false>;           \
         if (lds > 65536) {                                                                              \
             static bool raised[2] = {false, false};                                                     \
             if (!raised[per_step ? 1 : 0]) {                                                            \

@@ -897,25 +897,30 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
         load_a(areg, kbn);
 
         // Activation fragments are read from LDS APD fragments ahead of the MFMAs that use them
-        // (a rotating window of APD + 1 registers sets), so the LDS latency is covered by matrix
+        // (a rotating window of APD + 1 register sets), so the LDS latency is covered by matrix
         // work instead of being waited for in front of every fragment.
+        // The weights of step t + 1 are converted while the MFMAs of step t run (one column tile
+        // per row-tile iteration, into a second fragment set): the VALU port and the matrix pipe
+        // then overlap inside one wave, instead of both waves of a SIMD converting at the same
+        // time and multiplying at the same time.
         const u32x4* abuf = lds + buf * abuf_units + j * LDROW + ml;
         constexpr int NFR = STEPS * MT;
         constexpr int APD = 3;
         u32x4 afr[APD + 1];
 #pragma unroll
         for (int i = 0; i < APD && i < NFR; ++i) afr[i] = abuf[((i / MT) * 4) * LDROW + (i % MT) * 16];
+        auto convert = [&](int t, int nt) -> u32x4 {
+            const uint32_t s2 = scale_operand<ACT>(sc[PER_STEP ? t : 0][nt]);
+            if (t == 0) return DequantScaled<ACT, BITS>::template run<0>(wq[nt], magic, s2);
+            if (t == 1) return DequantScaled<ACT, BITS>::template run<1>(wq[nt], magic, s2);
+            if (STEPS > 2 && t == 2) return DequantScaled<ACT, BITS>::template run<2 % STEPS>(wq[nt], magic, s2);
+            return DequantScaled<ACT, BITS>::template run<3 % STEPS>(wq[nt], magic, s2);
+        };
+        u32x4 w[2][NT];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) w[0][nt] = convert(0, nt);
 #pragma unroll
         for (int t = 0; t < STEPS; ++t) {
-            u32x4 w[NT];
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                const uint32_t s2 = scale_operand<ACT>(sc[PER_STEP ? t : 0][nt]);
-                if (t == 0) w[nt] = DequantScaled<ACT, BITS>::template run<0>(wq[nt], magic, s2);
-                if (t == 1) w[nt] = DequantScaled<ACT, BITS>::template run<1>(wq[nt], magic, s2);
-                if (STEPS > 2 && t == 2) w[nt] = DequantScaled<ACT, BITS>::template run<2 % STEPS>(wq[nt], magic, s2);
-                if (STEPS > 2 && t == 3) w[nt] = DequantScaled<ACT, BITS>::template run<3 % STEPS>(wq[nt], magic, s2);
-            }
 #pragma unroll
             for (int mt = 0; mt < MT; ++mt) {
                 const int i = t * MT + mt;
@@ -923,12 +928,16 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
                     const int ip = i + APD;
                     afr[ip % (APD + 1)] = abuf[((ip / MT) * 4) * LDROW + (ip % MT) * 16];
                 }
-                // keep the read above where it is: without this the scheduler sinks it next to its
-                // use (to save registers) and every fragment is then waited for
+                if (t + 1 < STEPS) {
+#pragma unroll
+                    for (int nt = mt; nt < NT; nt += MT) w[(t + 1) & 1][nt] = convert(t + 1, nt);
+                }
+                // keep the read and the conversion above where they are: without this the scheduler
+                // sinks them next to their uses and every fragment is then waited for
                 __builtin_amdgcn_sched_barrier(0);
                 const u32x4 a = afr[i % (APD + 1)];
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = mfma16x16x32<ACT>(w[nt], a, acc[mt][nt]);
+                for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = mfma16x16x32<ACT>(w[t & 1][nt], a, acc[mt][nt]);
             }
         }
 #pragma unroll

@@ -204,7 +204,9 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            "traffic": None,
+            # FETCH_SIZE summed over the 8 launches of a step, rocprofv3 --pmc, 2 KiB per count as calibrated
+            # with a 1 GiB copy (profiles/fq_gemm_skinny_kernel_opt175b_decode.md); bytes per step
+            "traffic": 1.91e9,
             "kernel": "fq_gemm_skinny_kernel (8 launches per step; sum of algorithmic bytes / sum of mean HIP-event durations)",
             "algorithmic_bytes_per_step": algo_bytes,
             "kernel_us_per_step": round(kernel_us, 2),

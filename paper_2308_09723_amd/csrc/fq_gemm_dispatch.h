@@ -80,14 +80,16 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
         const int bm = plan.mt * 16;
         const int nblocks_n = (ntiles + plan.waves * MMA_NT - 1) / (plan.waves * MMA_NT);
         const int nblocks_m = (int)((M + bm - 1) / bm);
-        const size_t lds = (size_t)2 * (kblk / 8) * (bm + 1) * 16;
+        // 128 rows x 8 waves runs the three-buffer pipeline; the other shapes keep two buffers
+        const bool pipe = plan.mt == 8 && plan.waves == 8;
+        const size_t lds = (size_t)(pipe ? 3 : 2) * (kblk / 8) * bm * 16;
         dim3 grid((unsigned)((int64_t)nblocks_n * nblocks_m * plan.splits));
         fq_group_items none;
         none.count = 0;
-#define FQ_MMA_LAUNCH(MT_, W_)                                                                          \
+#define FQ_MMA_LAUNCH(MT_, W_, PIPE_)                                                                   \
     do {                                                                                                \
-        auto kern = per_step ? fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, true, false>             \
-                             : fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, false, false>;           \
+        auto kern = per_step ? fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, true, false, PIPE_>      \
+                             : fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, false, false, PIPE_>;    \
         if (lds > 65536) {                                                                              \
             static bool raised[2] = {false, false};                                                     \
             if (!raised[per_step ? 1 : 0]) {                                                            \
@@ -103,13 +105,13 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
                            (int64_t)0, (int64_t)0, none);                                               \
     } while (0)
         if (plan.waves == 8) {
-            if (plan.mt == 2) FQ_MMA_LAUNCH(2, 8);
-            else if (plan.mt == 4) FQ_MMA_LAUNCH(4, 8);
-            else FQ_MMA_LAUNCH(8, 8);
+            if (plan.mt == 2) FQ_MMA_LAUNCH(2, 8, false);
+            else if (plan.mt == 4) FQ_MMA_LAUNCH(4, 8, false);
+            else FQ_MMA_LAUNCH(8, 8, true);
         } else {
-            if (plan.mt == 2) FQ_MMA_LAUNCH(2, 4);
-            else if (plan.mt == 4) FQ_MMA_LAUNCH(4, 4);
-            else FQ_MMA_LAUNCH(8, 4);
+            if (plan.mt == 2) FQ_MMA_LAUNCH(2, 4, false);
+            else if (plan.mt == 4) FQ_MMA_LAUNCH(4, 4, false);
+            else FQ_MMA_LAUNCH(8, 4, false);
         }
 #undef FQ_MMA_LAUNCH
     }

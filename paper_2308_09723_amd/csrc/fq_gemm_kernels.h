@@ -505,8 +505,8 @@ __global__ __launch_bounds__(256) void fq_gemm_tile_kernel(
     constexpr int STEPS = KBLK / FQ_KSTEP;
     constexpr int KC = KBLK / 8;             // 16-byte units per row and k-block
     constexpr int BM = MT * 16;
-    constexpr int LDROW = BM + 1;
     constexpr int UNITS = BM * KC;
+    constexpr int LDROW = BM + 1;
     constexpr int UPT = (UNITS + 255) / 256;  // units per thread
     constexpr float OFF = Dequant<ACT, BITS>::OFFSET;
     __shared__ u32x4 lds[2][KC * LDROW];
@@ -765,7 +765,7 @@ __device__ inline uint32_t scale_operand(uint16_t h) {
     }
 }
 
-template <int ACT, int BITS, int MT, int NT, int WAVES, bool PER_STEP, bool GROUPED>
+template <int ACT, int BITS, int MT, int NT, int WAVES, bool PER_STEP, bool GROUPED, bool PIPE>
 __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
     const uint16_t* __restrict__ A, const u32x4* __restrict__ codes, const uint16_t* __restrict__ scales,
     uint16_t* __restrict__ C, float* __restrict__ partial, int M, int N, int K, int g, int kb_per_split,
@@ -775,12 +775,16 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
     constexpr int STEPS = KBLK / FQ_KSTEP;
     constexpr int KC = KBLK / 8;
     constexpr int BM = MT * 16;
-    constexpr int LDROW = BM + 1;
     constexpr int UNITS = BM * KC;
+    // LDS layout of the activation tile, in 16-byte units: unit(kc, row) = kc * BM + (row ^ swz(kc)),
+    // swz(kc) = kc * (16 / KC) mod 16.  A fragment read (16 rows of one kc per 16 lanes) then covers
+    // one aligned 256-byte span, and a staging write (the KC units of a row in neighbouring lanes)
+    // spreads over all banks; a padded pitch keeps the writes conflict-free but halves the read rate.
+    constexpr int SWZ = 16 / KC;
     constexpr int NTHR = WAVES * 64;
     constexpr int UPT = (UNITS + NTHR - 1) / NTHR;
     constexpr int SROWS = PER_STEP ? STEPS : 1;
-    extern __shared__ u32x4 lds[];   // [2][KC * LDROW]
+    extern __shared__ u32x4 lds[];   // [PIPE ? 3 : 2][KC * BM]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -848,7 +852,7 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
         const int row = u / KC, kc = u % KC;
         a_ok[r] = (u < UNITS) && (row < rows);
         a_off[r] = (uint32_t)(a_ok[r] ? row : 0) * (uint32_t)K + (uint32_t)kc * 8u;
-        a_dst[r] = (u < UNITS) ? kc * LDROW + row : -1;
+        a_dst[r] = (u < UNITS) ? kc * BM + (row ^ ((kc * SWZ) & 15)) : -1;
     }
     const uint16_t* Arow = A + row0 * K;
 
@@ -860,8 +864,8 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
 
     const uint32_t magic = Dequant<ACT, BITS>::init();
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
-    u32x4 wq[NT], areg[UPT];
-    uint16_t sc[SROWS][NT];
+    u32x4 wq[NT], wq_n[NT], areg[UPT];
+    uint16_t sc[SROWS][NT], sc_n[SROWS][NT];
     auto load_w = [&](u32x4 (&q)[NT], uint16_t (&s)[SROWS][NT], int kb) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) q[nt] = (wbase[nt] + (int64_t)kb * kb_stride)[lane];
@@ -872,81 +876,155 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
             for (int nt = 0; nt < NT; ++nt) s[r][nt] = sbase[nt][srow + ml];
         }
     };
-    auto load_a = [&](u32x4 (&a)[UPT], int kb) {
+    auto load_a = [&](int kb) {
         const uint16_t* base = Arow + (int64_t)kb * KBLK;
 #pragma unroll
-        for (int r = 0; r < UPT; ++r) a[r] = a_ok[r] ? *reinterpret_cast<const u32x4*>(base + a_off[r]) : zero4;
+        for (int r = 0; r < UPT; ++r) areg[r] = *reinterpret_cast<const u32x4*>(base + a_off[r]);
     };
-
-    if (kb0 < kb1) {
-        load_w(wq, sc, kb0);
-        load_a(areg, kb0);
-    }
-    int buf = 0;
-    const int abuf_units = KC * LDROW;
-    for (int kb = kb0; kb < kb1; ++kb) {
+    // Rows past the end of the matrix load row 0 (always valid) and are zeroed here: a load under
+    // a condition would hide the number of loads in flight from the wait-count bookkeeping, and
+    // every later wait would then drain all of them.
+    auto store_a = [&](u32x4* dst) {
 #pragma unroll
         for (int r = 0; r < UPT; ++r)
-            if (a_dst[r] >= 0) lds[buf * abuf_units + a_dst[r]] = areg[r];
-        __syncthreads();
-        // prefetch the next k-block into registers
-        u32x4 wq_n[NT];
-        uint16_t sc_n[SROWS][NT];
-        const int kbn = kb + 1 < kb1 ? kb + 1 : kb;
-        load_w(wq_n, sc_n, kbn);
-        load_a(areg, kbn);
+            if (a_dst[r] >= 0) dst[a_dst[r]] = a_ok[r] ? areg[r] : zero4;
+    };
+    auto convert = [&](const u32x4 (&q)[NT], const uint16_t (&s)[SROWS][NT], int t, int nt) -> u32x4 {
+        const uint32_t s2 = scale_operand<ACT>(s[PER_STEP ? t : 0][nt]);
+        if (t == 0) return DequantScaled<ACT, BITS>::template run<0>(q[nt], magic, s2);
+        if (t == 1) return DequantScaled<ACT, BITS>::template run<1>(q[nt], magic, s2);
+        if (STEPS > 2 && t == 2) return DequantScaled<ACT, BITS>::template run<2 % STEPS>(q[nt], magic, s2);
+        return DequantScaled<ACT, BITS>::template run<3 % STEPS>(q[nt], magic, s2);
+    };
 
-        // Activation fragments are read from LDS APD fragments ahead of the MFMAs that use them
-        // (a rotating window of APD + 1 register sets), so the LDS latency is covered by matrix
-        // work instead of being waited for in front of every fragment.
-        // The weights of step t + 1 are converted while the MFMAs of step t run (one column tile
-        // per row-tile iteration, into a second fragment set): the VALU port and the matrix pipe
-        // then overlap inside one wave, instead of both waves of a SIMD converting at the same
-        // time and multiplying at the same time.
-        const u32x4* abuf = lds + buf * abuf_units + j * LDROW + ml;
-        constexpr int NFR = STEPS * MT;
-        constexpr int APD = 3;
-        u32x4 afr[APD + 1];
+    constexpr int NFR = STEPS * MT;
+    constexpr int APD = NFR >= 8 ? 3 : 1;   // fragments read ahead of their MFMAs
+    static_assert(NFR % (APD + 1) == 0, "the fragment window must wrap at a k-block boundary");
+    static_assert(STEPS % 2 == 0, "fragment sets alternate per k-step");
+    constexpr int abuf_units = KC * BM;
+    int a_rd[STEPS];   // unit of this lane's fragment row for k-step t (row tile 0)
 #pragma unroll
-        for (int i = 0; i < APD && i < NFR; ++i) afr[i] = abuf[((i / MT) * 4) * LDROW + (i % MT) * 16];
-        auto convert = [&](int t, int nt) -> u32x4 {
-            const uint32_t s2 = scale_operand<ACT>(sc[PER_STEP ? t : 0][nt]);
-            if (t == 0) return DequantScaled<ACT, BITS>::template run<0>(wq[nt], magic, s2);
-            if (t == 1) return DequantScaled<ACT, BITS>::template run<1>(wq[nt], magic, s2);
-            if (STEPS > 2 && t == 2) return DequantScaled<ACT, BITS>::template run<2 % STEPS>(wq[nt], magic, s2);
-            return DequantScaled<ACT, BITS>::template run<3 % STEPS>(wq[nt], magic, s2);
-        };
-        u32x4 w[2][NT];
+    for (int t = 0; t < STEPS; ++t) a_rd[t] = (4 * t + j) * BM + (ml ^ (((4 * t + j) * SWZ) & 15));
+    u32x4 w[2][NT];
+    u32x4 afr[APD + 1];
+
+    if constexpr (PIPE) {
+        // The k loop is one software pipeline that does not drain at k-block boundaries.
+        // Slot i = t * MT + mt of a k-block holds the NT MFMAs of (k-step t, row tile mt); around them:
+        //   * the activation fragment of slot i + APD is read from LDS (from the next k-block's buffer
+        //     in the last APD slots), so the LDS latency is covered by matrix work;
+        //   * the weights of k-step t + 1 are converted, one column tile per slot, into the other
+        //     fragment set; in the last k-step these are the weights of step 0 of the next k-block;
+        //   * at slot WR_SLOT the next k-block's activation tile goes from registers to LDS and the
+        //     global loads of the tile after it are issued; at BAR_SLOT the one barrier per k-block
+        //     makes that tile visible before the first fragment of it is read.
+        // Three LDS buffers: the tile written during k-block kb was last read during kb - 2, which
+        // every wave has finished before any wave passes the barrier of kb - 1.
+        constexpr int BAR_SLOT = NFR - APD - 1;
+        constexpr int WR_SLOT = BAR_SLOT >= 2 ? BAR_SLOT - 2 : 0;
+        int cur = 0;
+        if (kb0 < kb1) {
+            load_w(wq, sc, kb0);
+            load_a(kb0);
+            store_a(lds);
+            load_a(kb0 + 1 < kb1 ? kb0 + 1 : kb0);
+            __syncthreads();
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) w[0][nt] = convert(0, nt);
+            for (int i = 0; i < APD; ++i) afr[i] = lds[a_rd[i / MT] + (i % MT) * 16];
 #pragma unroll
-        for (int t = 0; t < STEPS; ++t) {
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const int i = t * MT + mt;
-                if (i + APD < NFR) {
-                    const int ip = i + APD;
-                    afr[ip % (APD + 1)] = abuf[((ip / MT) * 4) * LDROW + (ip % MT) * 16];
-                }
-                if (t + 1 < STEPS) {
-#pragma unroll
-                    for (int nt = mt; nt < NT; nt += MT) w[(t + 1) & 1][nt] = convert(t + 1, nt);
-                }
-                // keep the read and the conversion above where they are: without this the scheduler
-                // sinks them next to their uses and every fragment is then waited for
-                __builtin_amdgcn_sched_barrier(0);
-                const u32x4 a = afr[i % (APD + 1)];
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = mfma16x16x32<ACT>(w[t & 1][nt], a, acc[mt][nt]);
-            }
+            for (int nt = 0; nt < NT; ++nt) w[0][nt] = convert(wq, sc, 0, nt);
         }
+        for (int kb = kb0; kb < kb1; ++kb) {
+            const int nxt = cur == 2 ? 0 : cur + 1;
+            const u32x4* abuf = lds + cur * abuf_units;
+            u32x4* nbuf = lds + nxt * abuf_units;
+            load_w(wq_n, sc_n, kb + 1 < kb1 ? kb + 1 : kb);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) wq[nt] = wq_n[nt];
+            for (int t = 0; t < STEPS; ++t) {
 #pragma unroll
-        for (int r = 0; r < SROWS; ++r)
+                for (int mt = 0; mt < MT; ++mt) {
+                    const int i = t * MT + mt;
+                    if (i == WR_SLOT) {
+                        store_a(nbuf);
+                        load_a(kb + 2 < kb1 ? kb + 2 : kb1 - 1);
+                    }
+                    if (i == BAR_SLOT) __syncthreads();
+                    const int ip = i + APD;
+                    if (ip < NFR) {
+                        afr[ip % (APD + 1)] = abuf[a_rd[ip / MT] + (ip % MT) * 16];
+                    } else {
+                        afr[ip % (APD + 1)] = nbuf[a_rd[(ip - NFR) / MT] + ((ip - NFR) % MT) * 16];
+                    }
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) sc[r][nt] = sc_n[r][nt];
-        buf ^= 1;
+                    for (int nt = mt; nt < NT; nt += MT) {
+                        if (t + 1 < STEPS) w[(t + 1) & 1][nt] = convert(wq, sc, t + 1, nt);
+                        else w[0][nt] = convert(wq_n, sc_n, 0, nt);
+                    }
+                    // keep the read and the conversion above where they are: without this the scheduler
+                    // sinks them next to their uses and every fragment is then waited for
+                    __builtin_amdgcn_sched_barrier(0);
+                    const u32x4 a = afr[i % (APD + 1)];
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = mfma16x16x32<ACT>(w[t & 1][nt], a, acc[mt][nt]);
+                }
+            }
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) wq[nt] = wq_n[nt];
+#pragma unroll
+            for (int r = 0; r < SROWS; ++r)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) sc[r][nt] = sc_n[r][nt];
+            cur = nxt;
+        }
+    } else {
+        // Two LDS buffers, one barrier at the top of every k-block: a smaller footprint in LDS and
+        // registers, so that two blocks fit a compute unit, which pays for the block shapes that
+        // rely on several resident blocks (few rows, or 4 waves) rather than on one long pipeline.
+        if (kb0 < kb1) {
+            load_w(wq, sc, kb0);
+            load_a(kb0);
+        }
+        int buf = 0;
+        for (int kb = kb0; kb < kb1; ++kb) {
+            store_a(lds + buf * abuf_units);
+            __syncthreads();
+            const int kbn = kb + 1 < kb1 ? kb + 1 : kb;
+            load_w(wq_n, sc_n, kbn);
+            load_a(kbn);
+            const u32x4* abuf = lds + buf * abuf_units;
+#pragma unroll
+            for (int i = 0; i < APD; ++i) afr[i] = abuf[a_rd[i / MT] + (i % MT) * 16];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) w[0][nt] = convert(wq, sc, 0, nt);
+#pragma unroll
+            for (int t = 0; t < STEPS; ++t) {
+#pragma unroll
+                for (int mt = 0; mt < MT; ++mt) {
+                    const int i = t * MT + mt;
+                    if (i + APD < NFR) {
+                        const int ip = i + APD;
+                        afr[ip % (APD + 1)] = abuf[a_rd[ip / MT] + (ip % MT) * 16];
+                    }
+                    if (t + 1 < STEPS) {
+#pragma unroll
+                        for (int nt = mt; nt < NT; nt += MT) w[(t + 1) & 1][nt] = convert(wq, sc, t + 1, nt);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    const u32x4 a = afr[i % (APD + 1)];
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt)
+                        acc[mt][nt] = mfma16x16x32<ACT>(w[t & 1][nt], a, acc[mt][nt]);
+                }
+            }
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) wq[nt] = wq_n[nt];
+#pragma unroll
+            for (int r = 0; r < SROWS; ++r)
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) sc[r][nt] = sc_n[r][nt];
+            buf ^= 1;
+        }
     }
 
 #pragma unroll

@@ -75,8 +75,11 @@ def cpu_baseline(seconds_target=12.0):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=200)
+    ap.add_argument("--settle", type=float, default=1.0,
+                    help="seconds of untimed steps before the warm-up: after idling, the device runs about 10 %% "
+                         "slower for the first ~0.1-0.5 s of sustained load (clock ramp); 0 disables")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--large-m", action="store_true", help="also time the M >= 256 products (reported under 'extra')")
     ap.add_argument("--profile", choices=["decode", "prefill", "copy"], default=None,
@@ -105,7 +108,7 @@ def main():
         torch.cuda.synchronize()
         return
     if args.profile == "prefill":
-        profile_prefill(torch, fq, workloads, args.steps)
+        profile_prefill(torch, fq, workloads, args.steps, args.settle)
         return
 
     layers = []
@@ -118,8 +121,11 @@ def main():
     torch.cuda.empty_cache()
 
     calls = []   # (name, M, A, codes, scales, C, workspace, weight_bytes, algorithmic_bytes)
-    for name, K, N, codes, scales in layers:
-        for M in DECODE_M:
+    # Order: every layer at M = 1, then every layer at M = 8.  Between two uses of one layer's weights the
+    # other three layers (>= 620 MB) stream through, more than twice the 256 MB Infinity Cache, so no
+    # product finds its weights cache-resident.
+    for M in DECODE_M:
+        for name, K, N, codes, scales in layers:
             gen = torch.Generator(device="cuda")
             gen.manual_seed(1000 + M)
             A = torch.randn((M, K), generator=gen, device="cuda", dtype=torch.float32).to(torch.float16)
@@ -142,6 +148,12 @@ def main():
             if events is not None:
                 events[i][1].record()
 
+    if args.settle > 0:
+        t_end = time.perf_counter() + args.settle
+        while time.perf_counter() < t_end:
+            for _ in range(50):
+                step()
+            torch.cuda.synchronize()
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
@@ -150,30 +162,39 @@ def main():
             step()
         torch.cuda.synchronize()
         return
-    # timed region: exactly `steps` steps.  In every EVENT_STRIDE-th step HIP events (recorded on the
-    # launch stream) bracket each product; the other steps run back to back, because every event record
-    # is a command of its own and eight pairs per step would stretch the step by ~10 %.
+    # timed region: exactly `steps` steps.  HIP events are recorded on the launch stream: in every
+    # EVENT_STRIDE-th step one pair brackets the whole step (its eight launches run back to back, so the
+    # pair measures the sum of their durations: this is what the roofline uses), and half a stride later
+    # a pair brackets each product (the per-product breakdown; each of these carries the ~1.5 us that an
+    # event record between two kernels costs, so their sum is larger than the step figure).
     EVENT_STRIDE = 8
+    ev_step = {k: (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for k in range(0, args.steps, EVENT_STRIDE)}
     ev = {k: [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in calls]
-          for k in range(0, args.steps, EVENT_STRIDE)}
+          for k in range(EVENT_STRIDE // 2, args.steps, EVENT_STRIDE)}
     torch.cuda.synchronize()
     t0 = time.perf_counter()
     for k in range(args.steps):
+        pair = ev_step.get(k)
+        if pair is not None:
+            pair[0].record()
         step(ev.get(k))
+        if pair is not None:
+            pair[1].record()
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
 
     ms_per_step = elapsed * 1e3 / args.steps
     weight_bytes_step = sum(c[7] for c in calls)
     value = weight_bytes_step / (elapsed / args.steps) / 1e12
-    # per-launch durations from the events
+    step_us = [a.elapsed_time(b) * 1e3 for a, b in ev_step.values()]
+    kernel_us = sum(step_us) / len(step_us)
+    algo_bytes = sum(c[8] for c in calls)
+    achieved = algo_bytes / (kernel_us * 1e-6) / 1e9
     per_call_us = []
     for i in range(len(calls)):
         ts = [ev[k][i][0].elapsed_time(ev[k][i][1]) * 1e3 for k in ev]
-        per_call_us.append(sum(ts) / len(ts))
-    algo_bytes = sum(c[8] for c in calls)
-    kernel_us = sum(per_call_us)
-    achieved = algo_bytes / (kernel_us * 1e-6) / 1e9
+        per_call_us.append(sum(ts) / len(ts) if ts else float("nan"))
     per_layer = {f"{c[0]}_M{c[1]}": {"us": round(t, 2), "weight_TBps": round(c[7] / t / 1e6, 3),
                                     "plan": fq.gemm_describe(c[1], c[5].shape[1], c[2].shape[1], BITS, GROUP)}
                  for c, t in zip(calls, per_call_us)}
@@ -185,6 +206,7 @@ def main():
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
+        "settle_seconds": args.settle,
         "ms_per_step": round(ms_per_step, 5),
         "higher_is_better": True,
         "scaling": "weak",
@@ -207,7 +229,8 @@ def main():
             # FETCH_SIZE summed over the 8 launches of a step, rocprofv3 --pmc, 2 KiB per count as calibrated
             # with a 1 GiB copy (profiles/fq_gemm_skinny_kernel_opt175b_decode.md); bytes per step
             "traffic": 1.91e9,
-            "kernel": "fq_gemm_skinny_kernel (8 launches per step; sum of algorithmic bytes / sum of mean HIP-event durations)",
+            "kernel": "fq_gemm_skinny_kernel (8 launches per step; algorithmic bytes of the step / mean HIP-event "
+                      "duration of the 8 back-to-back launches)",
             "algorithmic_bytes_per_step": algo_bytes,
             "kernel_us_per_step": round(kernel_us, 2),
         },
@@ -220,8 +243,9 @@ def main():
     print(json.dumps(out))
 
 
-def profile_prefill(torch, fq, workloads, reps):
-    """QKV-shaped product at M = 2048 with bf16 activations, `reps` launches (for rocprofv3)."""
+def profile_prefill(torch, fq, workloads, reps, settle):
+    """QKV-shaped product at M = 2048 with bf16 activations: `settle` seconds of launches, then `reps` more
+    (for rocprofv3; the last `reps` records of the kernel trace are the settled ones)."""
     K, N = workloads.OPT175B_LAYERS["qkv"]
     M = 2048
     W = make_weight(torch, K, N, 100)
@@ -232,45 +256,59 @@ def profile_prefill(torch, fq, workloads, reps):
     need = fq.gemm_workspace_bytes(M, N, K, BITS, GROUP)
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
-    for _ in range(max(1, min(reps, 20))):
+    def run():
         st = fq.gemm_raw(A.data_ptr(), fq.FQ_BF16, M, N, K, codes.data_ptr(), scales.data_ptr(), BITS, GROUP,
                          C.data_ptr(), ws.data_ptr(), ws.numel(), stream)
         if st != fq.FQ_OK:
             raise fq.FqError(st, "fq_gemm")
+    t_end = time.perf_counter() + settle
+    while time.perf_counter() < t_end:
+        for _ in range(4):
+            run()
+        torch.cuda.synchronize()
+    for _ in range(max(1, min(reps, 20))):
+        run()
     torch.cuda.synchronize()
 
 
 def large_m_section(torch, fq, layers):
-    """Prefill-sized products on the same int4 weights (bf16 activations): TFLOP/s and fraction of MFMA peak."""
+    """Prefill-sized products on the same int4 weights: TFLOP/s and fraction of the dense MFMA peak."""
     res = {}
     stream = torch.cuda.current_stream().cuda_stream
     for name, K, N, codes, scales in layers:
         for M in (256, 2048):
-            A = torch.randn((M, K), device="cuda", dtype=torch.float32).to(torch.bfloat16)
-            C = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)
-            need = fq.gemm_workspace_bytes(M, N, K, BITS, GROUP)
-            ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+            for tag, act, dt in (("bf16", fq.FQ_BF16, torch.bfloat16), ("f16", fq.FQ_F16, torch.float16)):
+                A = torch.randn((M, K), device="cuda", dtype=torch.float32).to(dt)
+                C = torch.empty((M, N), device="cuda", dtype=dt)
+                need = fq.gemm_workspace_bytes(M, N, K, BITS, GROUP)
+                ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
 
-            def run():
-                st = fq.gemm_raw(A.data_ptr(), fq.FQ_BF16, M, N, K, codes.data_ptr(), scales.data_ptr(), BITS, GROUP,
-                                 C.data_ptr(), ws.data_ptr(), ws.numel(), stream)
-                if st != fq.FQ_OK:
-                    raise fq.FqError(st, "fq_gemm")
-            for _ in range(2):
+                def run():
+                    st = fq.gemm_raw(A.data_ptr(), act, M, N, K, codes.data_ptr(), scales.data_ptr(), BITS, GROUP,
+                                     C.data_ptr(), ws.data_ptr(), ws.numel(), stream)
+                    if st != fq.FQ_OK:
+                        raise fq.FqError(st, "fq_gemm")
+                # untimed: about 0.3 s of the same product, so that the clocks have settled
                 run()
-            reps = 5
-            e0 = torch.cuda.Event(enable_timing=True)
-            e1 = torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(reps):
-                run()
-            e1.record()
-            torch.cuda.synchronize()
-            ms = e0.elapsed_time(e1) / reps
-            tflops = 2.0 * M * N * K / (ms * 1e-3) / 1e12
-            res[f"{name}_M{M}"] = {"ms": round(ms, 4), "TFLOPs": round(tflops, 1),
-                                   "frac_of_mfma_peak": round(tflops / MFMA_PEAK_TFLOPS, 4),
-                                   "plan": fq.gemm_describe(M, N, K, BITS, GROUP)}
+                torch.cuda.synchronize()
+                t_end = time.perf_counter() + 0.3
+                while time.perf_counter() < t_end:
+                    for _ in range(4):
+                        run()
+                    torch.cuda.synchronize()
+                reps = 20
+                e0 = torch.cuda.Event(enable_timing=True)
+                e1 = torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(reps):
+                    run()
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1) / reps
+                tflops = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+                res[f"{name}_M{M}_{tag}"] = {"ms": round(ms, 4), "TFLOPs": round(tflops, 1),
+                                             "frac_of_mfma_peak": round(tflops / MFMA_PEAK_TFLOPS, 4),
+                                             "plan": fq.gemm_describe(M, N, K, BITS, GROUP)}
     return res
 
 

@@ -942,6 +942,33 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int t = 0; t < STEPS; ++t) {
+#ifdef FQ_DEV_INTERLEAVE
+                if (t + 1 < STEPS) {
+#pragma unroll
+                    for (int nt = 0; nt < NT; ++nt) w[(t + 1) & 1][nt] = convert(wq, sc, t + 1, nt);
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        const int i = t * MT + mt;
+                        const int ip = i + APD;
+                        afr[ip % (APD + 1)] = abuf[a_rd[ip / MT] + (ip % MT) * 16];
+                        const u32x4 a = afr[i % (APD + 1)];
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt)
+                            acc[mt][nt] = mfma16x16x32<ACT>(w[t & 1][nt], a, acc[mt][nt]);
+                    }
+#pragma unroll
+                    for (int mt = 0; mt < MT; ++mt) {
+                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt) {
+                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                            __builtin_amdgcn_sched_group_barrier(0x002, FQ_DEV_INTERLEAVE, 0);
+                        }
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                    continue;
+                }
+#endif
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
                     const int i = t * MT + mt;

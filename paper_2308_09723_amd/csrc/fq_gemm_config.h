@@ -4,7 +4,6 @@
 
 namespace fqd {
 
-constexpr int TILE_NT = 4;      // column tiles per wave of the older tiled kernel (grouped product)
 constexpr int MMA_NT = 3;       // column tiles per wave of the large-M kernel
 
 // Small-M kernel variants that are compiled in: (NT column tiles per wave, ring DEPTH,

@@ -124,43 +124,77 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
     return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;
 }
 
+// Grouped (per-expert) product.  Every expert's rows are cut into row tiles of 128, 64 or 32
+// rows (the smallest that holds what is left), and the tiles of each size go to the kernel
+// instantiated for that size: experts with few rows then stream their weights through small
+// tiles instead of multiplying mostly padding.  Experts without rows produce no tile.
 template <int ACT, int BITS>
 int launch_grouped_typed(const void* A, const int32_t* offsets, int E, int64_t N, int64_t K,
                          const void* codes, const void* scales, int g, void* C, hipStream_t stream) {
-    constexpr int MT = 4;
-    constexpr int BM = MT * 16;
+    constexpr int W = 8;
     const int kblk = fq_kblk(BITS);
     const bool per_step = (g % kblk) != 0;
     const int ntiles = (int)(N / FQ_NTILE);
     const int KB = (int)(K / kblk);
+    const int nblocks_n = (ntiles + W * MMA_NT - 1) / (W * MMA_NT);
     const int64_t codes_stride16 = (int64_t)(K * N * BITS / 8) / 16;
     const int64_t scales_stride = (K / g) * N;
     fq_group_items items;
-    items.count = 0;
-    auto flush_items = [&]() -> int {
-        if (items.count == 0) return FQ_OK;
-        dim3 grid((unsigned)((ntiles + 4 * TILE_NT - 1) / (4 * TILE_NT)), (unsigned)items.count, 1u);
-        auto kern = per_step ? fq_gemm_tile_kernel<ACT, BITS, MT, TILE_NT, true, true>
-                             : fq_gemm_tile_kernel<ACT, BITS, MT, TILE_NT, false, true>;
-        hipLaunchKernelGGL(kern, grid, dim3(256), 0, stream, (const uint16_t*)A, (const u32x4*)codes,
-                           (const uint16_t*)scales, (uint16_t*)C, (float*)nullptr, 0, (int)N, (int)K, g, KB, 1,
-                           codes_stride16, scales_stride, items);
+    for (int mt = 8; mt >= 2; mt /= 2) {
+        const int bm = mt * 16;
+        const size_t lds = (size_t)(mt == 8 ? 3 : 2) * (kblk / 8) * bm * 16;
         items.count = 0;
-        return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;
-    };
-    for (int e = 0; e < E; ++e) {
-        for (int32_t r = offsets[e]; r < offsets[e + 1]; r += BM) {
-            const int i = items.count++;
-            items.row0[i] = r;
-            items.rows[i] = (int16_t)min(BM, offsets[e + 1] - r);
-            items.expert[i] = (int16_t)e;
-            if (items.count == 256) {
-                const int st = flush_items();
-                if (st != FQ_OK) return st;
+        auto flush_items = [&]() -> int {
+            if (items.count == 0) return FQ_OK;
+            dim3 grid((unsigned)((int64_t)nblocks_n * items.count));
+#define FQ_GROUPED_LAUNCH(MT_, PIPE_)                                                                   \
+    do {                                                                                                \
+        auto kern = per_step ? fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W, true, true, PIPE_>        \
+                             : fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W, false, true, PIPE_>;      \
+        if (lds > 65536) {                                                                              \
+            static bool raised[2] = {false, false};                                                     \
+            if (!raised[per_step ? 1 : 0]) {                                                            \
+                if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,  \
+                                        160 * 1024) != hipSuccess)                                      \
+                    return FQ_ERR_HIP;                                                                  \
+                raised[per_step ? 1 : 0] = true;                                                        \
+            }                                                                                           \
+        }                                                                                               \
+        hipLaunchKernelGGL(kern, grid, dim3(W * 64), lds, stream, (const uint16_t*)A,                   \
+                           (const u32x4*)codes, (const uint16_t*)scales, (uint16_t*)C, (float*)nullptr, \
+                           0, (int)N, (int)K, g, KB, 1, nblocks_n, items.count, codes_stride16,         \
+                           scales_stride, items);                                                       \
+    } while (0)
+            if (mt == 8) FQ_GROUPED_LAUNCH(8, true);
+            else if (mt == 4) FQ_GROUPED_LAUNCH(4, false);
+            else FQ_GROUPED_LAUNCH(2, false);
+#undef FQ_GROUPED_LAUNCH
+            items.count = 0;
+            return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;
+        };
+        for (int e = 0; e < E; ++e) {
+            int32_t r = offsets[e];
+            while (r < offsets[e + 1]) {
+                const int32_t left = offsets[e + 1] - r;
+                const int tile_mt = left > 64 ? 8 : (left > 32 ? 4 : 2);
+                const int32_t take = left < tile_mt * 16 ? left : tile_mt * 16;
+                if (tile_mt == mt) {
+                    const int i = items.count++;
+                    items.row0[i] = r;
+                    items.rows[i] = (int16_t)take;
+                    items.expert[i] = (int16_t)e;
+                    if (items.count == 256) {
+                        const int st = flush_items();
+                        if (st != FQ_OK) return st;
+                    }
+                }
+                r += take;
             }
         }
+        const int st = flush_items();
+        if (st != FQ_OK) return st;
     }
-    return flush_items();
+    return FQ_OK;
 }
 
 

@@ -478,190 +478,14 @@ __global__ __launch_bounds__(256) void fq_reduce_kernel(const float* __restrict_
     *reinterpret_cast<u32x2*>(C + i) = pack4<ACT>(v);
 }
 
-// ==========================================================================================
-// Tiled kernel (any M): the prefill / batched case (section 4.1: in compute-bound cases
-// the integer->float conversion, not the matrix-core math, is the bottleneck -- so each
-// weight record is converted exactly once per block and reused for all BM rows).
-//
-// Block = 4 waves.  All four share one activation tile (BM = 16 MT rows x KBLK) staged
-// through LDS with double buffering; wave w owns column tiles [4 bx + w) NT ... and converts
-// only its own weights, straight from its global-load registers.
-// LDS layout: 16-byte units (8 consecutive k of one row) at unit[kc * (BM + 1) + row];
-// a fragment read is 16 lanes x 16 contiguous bytes per lane group.
-// ==========================================================================================
+// One row tile of a grouped (per-expert) product: rows [row0, row0 + rows) of the stacked
+// activations belong to expert `expert`.  Passed by value in the kernel arguments.
 struct fq_group_items {
     int count;
     int32_t row0[256];
     int16_t rows[256];
     int16_t expert[256];
 };
-
-template <int ACT, int BITS, int MT, int NT, bool PER_STEP, bool GROUPED>
-__global__ __launch_bounds__(256) void fq_gemm_tile_kernel(
-    const uint16_t* __restrict__ A, const u32x4* __restrict__ codes, const uint16_t* __restrict__ scales,
-    uint16_t* __restrict__ C, float* __restrict__ partial, int M, int N, int K, int g, int kb_per_split,
-    int splits, int64_t codes_stride16, int64_t scales_stride, fq_group_items items) {
-    constexpr int KBLK = BITS == 4 ? 128 : 64;
-    constexpr int STEPS = KBLK / FQ_KSTEP;
-    constexpr int KC = KBLK / 8;             // 16-byte units per row and k-block
-    constexpr int BM = MT * 16;
-    constexpr int UNITS = BM * KC;
-    constexpr int LDROW = BM + 1;
-    constexpr int UPT = (UNITS + 255) / 256;  // units per thread
-    constexpr float OFF = Dequant<ACT, BITS>::OFFSET;
-    __shared__ u32x4 lds[2][KC * LDROW];
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = tid >> 6;
-    const int ntiles = N / FQ_NTILE;
-    const int KB = K / KBLK;
-    const int split = blockIdx.z;
-    const int kb0 = split * kb_per_split;
-    const int kb1 = min(KB, kb0 + kb_per_split);
-    const int ml = lane & 15, j = lane >> 4;
-    const int64_t kb_stride = (int64_t)ntiles * 64;
-
-    int64_t row0;      // first row of this block in A / C
-    int rows;          // valid rows in this block
-    if constexpr (GROUPED) {
-        const int it = blockIdx.y;
-        row0 = items.row0[it];
-        rows = items.rows[it];
-        const int e = items.expert[it];
-        codes += (int64_t)e * codes_stride16;
-        scales += (int64_t)e * scales_stride;
-    } else {
-        row0 = (int64_t)blockIdx.y * BM;
-        rows = (int)min((int64_t)BM, (int64_t)M - row0);
-    }
-
-    const u32x4* wp[NT];
-    const uint16_t* sp[NT];
-    bool tvalid[NT];
-    const int tile0 = (blockIdx.x * 4 + wave) * NT;
-#pragma unroll
-    for (int nt = 0; nt < NT; ++nt) {
-        const int tile = tile0 + nt;
-        tvalid[nt] = tile < ntiles;
-        const int tc = tvalid[nt] ? tile : 0;
-        wp[nt] = codes + fq_rec(tc, 0, ntiles, lane);
-        sp[nt] = scales + tc * FQ_NTILE + j * 4;
-    }
-
-    // activation staging: unit u = tid + 256 r  ->  (row = u / KC, kc = u % KC)
-    const uint16_t* a_src[UPT];
-    int a_dst[UPT];
-    bool a_ok[UPT];
-#pragma unroll
-    for (int r = 0; r < UPT; ++r) {
-        const int u = tid + 256 * r;
-        const int row = u / KC, kc = u % KC;
-        a_ok[r] = (u < UNITS) && (row < rows);
-        a_src[r] = A + (row0 + (a_ok[r] ? row : 0)) * K + kc * 8;
-        a_dst[r] = (u < UNITS) ? kc * LDROW + row : -1;
-    }
-
-    f32x4 acc[MT][NT], p[MT][NT], psa[MT];
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        psa[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            acc[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            p[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        }
-    }
-
-    const uint32_t magic = Dequant<ACT, BITS>::init();
-    const u32x4 zero4 = {0u, 0u, 0u, 0u};
-    u32x4 wq[NT], areg[UPT];
-    if (kb0 < kb1) {
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) wq[nt] = wp[nt][(int64_t)kb0 * kb_stride];
-#pragma unroll
-        for (int r = 0; r < UPT; ++r)
-            areg[r] = a_ok[r] ? *reinterpret_cast<const u32x4*>(a_src[r] + (int64_t)kb0 * KBLK) : zero4;
-    }
-    int buf = 0;
-    for (int kb = kb0; kb < kb1; ++kb) {
-#pragma unroll
-        for (int r = 0; r < UPT; ++r)
-            if (a_dst[r] >= 0) lds[buf][a_dst[r]] = areg[r];
-        __syncthreads();
-        // prefetch the next k-block into registers
-        u32x4 wq_n[NT];
-        const int kbn = kb + 1 < kb1 ? kb + 1 : kb;
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) wq_n[nt] = wp[nt][(int64_t)kbn * kb_stride];
-#pragma unroll
-        for (int r = 0; r < UPT; ++r)
-            areg[r] = a_ok[r] ? *reinterpret_cast<const u32x4*>(a_src[r] + (int64_t)kbn * KBLK) : zero4;
-
-#pragma unroll
-        for (int t = 0; t < STEPS; ++t) {
-            u32x4 w[NT];
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                if (t == 0) w[nt] = Dequant<ACT, BITS>::template run<0>(wq[nt], magic);
-                if (t == 1) w[nt] = Dequant<ACT, BITS>::template run<1>(wq[nt], magic);
-                if (STEPS > 2 && t == 2) w[nt] = Dequant<ACT, BITS>::template run<2 % STEPS>(wq[nt], magic);
-                if (STEPS > 2 && t == 3) w[nt] = Dequant<ACT, BITS>::template run<3 % STEPS>(wq[nt], magic);
-            }
-#pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const u32x4 a = lds[buf][(t * 4 + j) * LDROW + mt * 16 + ml];
-                if constexpr (OFF != 0.0f) psa[mt] = mfma16x16x32<ACT>(ones_operand<ACT>(), a, psa[mt]);
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) p[mt][nt] = mfma16x16x32<ACT>(w[nt], a, p[mt][nt]);
-            }
-            bool do_flush;
-            int64_t srow;
-            if constexpr (PER_STEP) {
-                do_flush = true;
-                srow = (int64_t)((kb * KBLK + t * FQ_KSTEP) / g) * N;
-            } else {
-                const int kend = (kb + 1) * KBLK;
-                do_flush = (t == STEPS - 1) && (OFF != 0.0f || kend % g == 0 || kb == kb1 - 1);
-                srow = (int64_t)((kb * KBLK) / g) * N;
-            }
-            if (do_flush) {
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) {
-                    const f32x4 s = scales4(sp[nt] + srow);
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        flush<ACT, BITS>(acc[mt][nt], p[mt][nt], s, psa[mt][0]);
-                        p[mt][nt] = f32x4{0.f, 0.f, 0.f, 0.f};
-                    }
-                }
-#pragma unroll
-                for (int mt = 0; mt < MT; ++mt) psa[mt] = f32x4{0.f, 0.f, 0.f, 0.f};
-            }
-        }
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) wq[nt] = wq_n[nt];
-        buf ^= 1;
-    }
-
-#pragma unroll
-    for (int mt = 0; mt < MT; ++mt) {
-        const int row = mt * 16 + ml;
-        if (row >= rows) continue;
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            if (!tvalid[nt]) continue;
-            const int64_t n = (int64_t)(tile0 + nt) * FQ_NTILE + j * 4;
-            if (splits == 1) {
-                *reinterpret_cast<u32x2*>(C + (row0 + row) * N + n) = pack4<ACT>(acc[mt][nt]);
-            } else {
-                *reinterpret_cast<f32x4*>(partial + ((int64_t)split * M + row0 + row) * N + n) = acc[mt][nt];
-            }
-        }
-    }
-}
-
-
 
 // ==========================================================================================
 // Large-M kernel (prefill): pre-scaled weights, one accumulator set.
@@ -670,13 +494,15 @@ __global__ __launch_bounds__(256) void fq_gemm_tile_kernel(
 // matrix-core math, limits such kernels.  Here every weight record is converted AND scaled
 // exactly once per block (by the one wave that owns its columns) and then reused for all
 // BM = 16 MT rows of the block straight from registers; the conversion cost per MFMA is
-// therefore 1/MT of a fragment conversion.  Scaling before the MFMA (the paper's order:
-// "dequantize the weights to match the data type of the activation") keeps a single set of
-// accumulators, which is what allows MT = 8.
+// therefore 1/MT of a fragment conversion.  Scaling before the MFMA (the order section 4.1
+// describes: weights are brought to the activation type, then multiplied) keeps a single set
+// of accumulators, which is what allows MT = 8.
 //   fp16: q (exact) * s rounded once to fp16          (relative error <= 2^-11 per weight)
 //   bf16: fma(u, s, -bias * s) in binary32 = q * s exactly, rounded once to bf16 (<= 2^-9)
-// Block = WAVES waves, all sharing one activation tile (BM x KBLK) staged through LDS with
-// double buffering; wave w owns column tiles [(bx * WAVES + w) * NT, +NT).
+// Block = WAVES waves, all sharing one activation tile (BM x KBLK) staged through LDS (two
+// or three buffers); wave w owns column tiles [(bx * WAVES + w) * NT, +NT).
+// With GROUPED, row tile i of the grid is items.row0/rows/expert[i] and the weights of expert e
+// start e * codes_stride16 records / e * scales_stride scales into the buffers.
 // ==========================================================================================
 template <int ACT, int BITS>
 struct DequantScaled;

@@ -4,6 +4,10 @@
 #include <hip/hip_runtime.h>
 #include <math.h>
 #include <stdint.h>
+#ifdef FQ_DEV_PLAN_ENV
+#include <stdio.h>
+#include <stdlib.h>
+#endif
 
 #include "fq_gemm_config.h"
 #include "fq_internal.h"
@@ -80,22 +84,46 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
         p.splits = gs;
         p.kb_per_split = 0;
     } else {
-        // Tiled MFMA kernel: BM = 16 * mt rows per block, 64 columns per wave.
+        // Tiled MFMA kernel: BM = 16 * mt rows per block, 48 columns per wave, 4 or 8 waves, and
+        // optionally a split of K over `splits` blocks whose binary32 partial tiles a second kernel
+        // adds.  The block shape is the one that minimises a measured cost model:
+        //   time = ceil(blocks / 256) * k-blocks per block * u(mt, waves)  +  cost of the partials
+        // where u is the time one block spends on one k-block of 128 rows of K when every compute
+        // unit holds its share of blocks (microseconds, fitted to sweeps over the OPT-175B shapes at
+        // M = 32 ... 2048), and the partials cost their write plus read at ~4 TB/s plus a launch.
         p.kind = 1;
         p.mt = M <= 32 ? 2 : (M <= 64 ? 4 : 8);
         const int bm = p.mt * 16;
         const int64_t nbm = (M + bm - 1) / bm;
-        const int64_t blocks8 = ((ntiles + 8 * MMA_NT - 1) / (8 * MMA_NT)) * nbm;
-        const int64_t blocks4 = ((ntiles + 4 * MMA_NT - 1) / (4 * MMA_NT)) * nbm;
-        p.waves = blocks8 >= 512 ? 8 : 4;
-        const int64_t blocks = p.waves == 8 ? blocks8 : blocks4;
-        int splits = 1;
-        if (blocks < 256) splits = (int)((512 + blocks - 1) / blocks);
-        if (splits > 8) splits = 8;
-        if (splits > KB) splits = KB;
-        const int kbs = (KB + splits - 1) / splits;
-        p.kb_per_split = kbs;
-        p.splits = (KB + kbs - 1) / kbs;
+        const double u8 = p.mt == 8 ? 2.6 : (p.mt == 4 ? 1.7 : 1.3);
+        const double u4 = p.mt == 8 ? 1.43 : (p.mt == 4 ? 0.92 : 0.77);
+        const double kscale = (double)kblk / 128.0;
+        const int split_opts[6] = {1, 2, 3, 4, 6, 8};
+        double best = 1e30;
+        for (int waves = 8; waves >= 4; waves -= 4) {
+            const int64_t nbn = (ntiles + waves * MMA_NT - 1) / (waves * MMA_NT);
+            for (int si = 0; si < 6; ++si) {
+                int splits = split_opts[si];
+                if (splits > KB) break;
+                const int kbs = (KB + splits - 1) / splits;
+                splits = (KB + kbs - 1) / kbs;
+                const int64_t blocks = nbn * nbm * splits;
+                const int64_t per_cu = (blocks + 255) / 256;
+                double t = (double)per_cu * kbs * (waves == 8 ? u8 : u4) * kscale;
+                // two 128-row 4-wave blocks share a compute unit; an odd one left over runs alone
+                // and takes a little more than half the time of a pair
+                if (p.mt == 8 && waves == 4 && (per_cu & 1)) t += 0.13 * u4 * kbs * kscale;
+                // fewer blocks than compute units: the idle ones also pull no weights
+                if (blocks < 256) t *= 256.0 / (double)blocks;
+                if (splits > 1) t += 2.0 * splits * (double)M * (double)N * 4.0 / 4e6 + 5.0;
+                if (t < best - 1e-9) {
+                    best = t;
+                    p.waves = waves;
+                    p.splits = splits;
+                    p.kb_per_split = kbs;
+                }
+            }
+        }
     }
     return p;
 }

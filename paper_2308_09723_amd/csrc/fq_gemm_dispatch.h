@@ -131,26 +131,26 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
 template <int ACT, int BITS>
 int launch_grouped_typed(const void* A, const int32_t* offsets, int E, int64_t N, int64_t K,
                          const void* codes, const void* scales, int g, void* C, hipStream_t stream) {
-    constexpr int W = 8;
     const int kblk = fq_kblk(BITS);
     const bool per_step = (g % kblk) != 0;
     const int ntiles = (int)(N / FQ_NTILE);
     const int KB = (int)(K / kblk);
-    const int nblocks_n = (ntiles + W * MMA_NT - 1) / (W * MMA_NT);
     const int64_t codes_stride16 = (int64_t)(K * N * BITS / 8) / 16;
     const int64_t scales_stride = (K / g) * N;
     fq_group_items items;
     for (int mt = 8; mt >= 2; mt /= 2) {
         const int bm = mt * 16;
+        const int waves = mt == 8 ? 8 : 4;   // small tiles: 4-wave blocks, three of which fit a compute unit
+        const int nblocks_n = (ntiles + waves * MMA_NT - 1) / (waves * MMA_NT);
         const size_t lds = (size_t)(mt == 8 ? 3 : 2) * (kblk / 8) * bm * 16;
         items.count = 0;
         auto flush_items = [&]() -> int {
             if (items.count == 0) return FQ_OK;
             dim3 grid((unsigned)((int64_t)nblocks_n * items.count));
-#define FQ_GROUPED_LAUNCH(MT_, PIPE_)                                                                   \
+#define FQ_GROUPED_LAUNCH(MT_, W_, PIPE_)                                                                  \
     do {                                                                                                \
-        auto kern = per_step ? fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W, true, true, PIPE_>        \
-                             : fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W, false, true, PIPE_>;      \
+        auto kern = per_step ? fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, true, true, PIPE_>       \
+                             : fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, false, true, PIPE_>;     \
         if (lds > 65536) {                                                                              \
             static bool raised[2] = {false, false};                                                     \
             if (!raised[per_step ? 1 : 0]) {                                                            \
@@ -160,14 +160,14 @@ int launch_grouped_typed(const void* A, const int32_t* offsets, int E, int64_t N
                 raised[per_step ? 1 : 0] = true;                                                        \
             }                                                                                           \
         }                                                                                               \
-        hipLaunchKernelGGL(kern, grid, dim3(W * 64), lds, stream, (const uint16_t*)A,                   \
+        hipLaunchKernelGGL(kern, grid, dim3(W_ * 64), lds, stream, (const uint16_t*)A,                  \
                            (const u32x4*)codes, (const uint16_t*)scales, (uint16_t*)C, (float*)nullptr, \
                            0, (int)N, (int)K, g, KB, 1, nblocks_n, items.count, codes_stride16,         \
                            scales_stride, items);                                                       \
     } while (0)
-            if (mt == 8) FQ_GROUPED_LAUNCH(8, true);
-            else if (mt == 4) FQ_GROUPED_LAUNCH(4, false);
-            else FQ_GROUPED_LAUNCH(2, false);
+            if (mt == 8) FQ_GROUPED_LAUNCH(8, 8, true);
+            else if (mt == 4) FQ_GROUPED_LAUNCH(4, 4, false);
+            else FQ_GROUPED_LAUNCH(2, 4, false);
 #undef FQ_GROUPED_LAUNCH
             items.count = 0;
             return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;

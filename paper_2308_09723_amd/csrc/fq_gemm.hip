@@ -3,6 +3,7 @@
 // in fq_gemm_<type>_<bits>.hip.
 #include <hip/hip_runtime.h>
 #include <math.h>
+#include <mutex>
 #include <stdint.h>
 #ifdef FQ_DEV_PLAN_ENV
 #include <stdio.h>
@@ -22,7 +23,7 @@ using namespace fqd;
                                        const fq_gemm_plan& plan, hipStream_t stream);                      \
     int fq_launch_grouped_typed_##ACT##_##BITS(const void* A, const int32_t* offsets, int E, int64_t N,    \
                                                int64_t K, const void* codes, const void* scales, int g,    \
-                                               void* C, hipStream_t stream);
+                                               void* C, const hipStream_t* streams);
 FQ_DECLARE_GEMM(0, 4)
 FQ_DECLARE_GEMM(0, 8)
 FQ_DECLARE_GEMM(1, 4)
@@ -139,13 +140,85 @@ int fq_launch_gemm(const void* A, int act, int64_t M, int64_t N, int64_t K, cons
     return fq_launch_typed_1_8(A, M, N, K, codes, scales, g, C, workspace, plan, stream);
 }
 
+// The grouped product launches up to three kernels (row tiles of 128, 64 and 32 rows) that do not
+// depend on each other.  Launched one after the other on the caller's stream, each would end with
+// a partly filled last round of blocks; on three streams the blocks of the next kernel fill the
+// compute units the previous one leaves idle.  The two extra streams (default priority) and the
+// events that fork them from and join them to the caller's stream are created once per device and
+// live until the process ends.
+namespace {
+struct fq_side {
+    bool tried = false, ok = false;
+    hipStream_t s[2];
+    hipEvent_t fork, join[2];
+};
+std::mutex g_side_mutex;
+fq_side g_side[64];
+
+fq_side* side_streams() {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return nullptr;
+    std::lock_guard<std::mutex> lock(g_side_mutex);
+    fq_side& x = g_side[dev];
+    if (!x.tried) {
+        x.tried = true;
+        bool ok = hipStreamCreateWithFlags(&x.s[0], hipStreamNonBlocking) == hipSuccess &&
+                  hipStreamCreateWithFlags(&x.s[1], hipStreamNonBlocking) == hipSuccess &&
+                  hipEventCreateWithFlags(&x.fork, hipEventDisableTiming) == hipSuccess &&
+                  hipEventCreateWithFlags(&x.join[0], hipEventDisableTiming) == hipSuccess &&
+                  hipEventCreateWithFlags(&x.join[1], hipEventDisableTiming) == hipSuccess;
+        x.ok = ok;
+        if (!ok) (void)hipGetLastError();
+    }
+    return x.ok ? &x : nullptr;
+}
+}  // namespace
+
 int fq_launch_gemm_grouped(const void* A, int act, const int32_t* offsets, int E, int64_t N, int64_t K,
                            const void* codes, const void* scales, int bits, int g, void* C,
                            hipStream_t stream) {
-    if (act == FQ_F16) {
-        if (bits == 4) return fq_launch_grouped_typed_0_4(A, offsets, E, N, K, codes, scales, g, C, stream);
-        return fq_launch_grouped_typed_0_8(A, offsets, E, N, K, codes, scales, g, C, stream);
+    // which tile sizes occur (same cutting rule as the launcher)
+    bool has[3] = {false, false, false};
+    for (int e = 0; e < E; ++e) {
+        const int32_t rows = offsets[e + 1] - offsets[e];
+        if (rows <= 0) continue;
+        if (rows > 64) has[0] = true;
+        const int32_t rest = rows > 64 ? rows % 128 : rows;
+        if (rest > 64) has[0] = true;
+        else if (rest > 32) has[1] = true;
+        else if (rest > 0) has[2] = true;
     }
-    if (bits == 4) return fq_launch_grouped_typed_1_4(A, offsets, E, N, K, codes, scales, g, C, stream);
-    return fq_launch_grouped_typed_1_8(A, offsets, E, N, K, codes, scales, g, C, stream);
+    hipStream_t streams[3] = {stream, stream, stream};
+    fq_side* side = (int)has[0] + (int)has[1] + (int)has[2] > 1 ? side_streams() : nullptr;
+    bool forked[2] = {false, false};
+    if (side) {
+        // the first tile size present stays on the caller's stream, the others go to the side streams
+        int next = 0;
+        bool first = true;
+        if (hipEventRecord(side->fork, stream) != hipSuccess) return FQ_ERR_HIP;
+        for (int c = 0; c < 3; ++c) {
+            if (!has[c]) continue;
+            if (first) { first = false; continue; }
+            if (hipStreamWaitEvent(side->s[next], side->fork, 0) != hipSuccess) return FQ_ERR_HIP;
+            streams[c] = side->s[next];
+            forked[next] = true;
+            ++next;
+        }
+    }
+    int st;
+    if (act == FQ_F16) {
+        st = bits == 4 ? fq_launch_grouped_typed_0_4(A, offsets, E, N, K, codes, scales, g, C, streams)
+                       : fq_launch_grouped_typed_0_8(A, offsets, E, N, K, codes, scales, g, C, streams);
+    } else {
+        st = bits == 4 ? fq_launch_grouped_typed_1_4(A, offsets, E, N, K, codes, scales, g, C, streams)
+                       : fq_launch_grouped_typed_1_8(A, offsets, E, N, K, codes, scales, g, C, streams);
+    }
+    // join even after a failed launch, so that the side streams never run ahead of the caller's
+    for (int i = 0; i < 2; ++i) {
+        if (!forked[i]) continue;
+        if (hipEventRecord(side->join[i], side->s[i]) != hipSuccess ||
+            hipStreamWaitEvent(stream, side->join[i], 0) != hipSuccess)
+            st = st == FQ_OK ? FQ_ERR_HIP : st;
+    }
+    return st;
 }

@@ -130,7 +130,7 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
 // tiles instead of multiplying mostly padding.  Experts without rows produce no tile.
 template <int ACT, int BITS>
 int launch_grouped_typed(const void* A, const int32_t* offsets, int E, int64_t N, int64_t K,
-                         const void* codes, const void* scales, int g, void* C, hipStream_t stream) {
+                         const void* codes, const void* scales, int g, void* C, const hipStream_t* streams) {
     const int kblk = fq_kblk(BITS);
     const bool per_step = (g % kblk) != 0;
     const int ntiles = (int)(N / FQ_NTILE);
@@ -141,6 +141,7 @@ int launch_grouped_typed(const void* A, const int32_t* offsets, int E, int64_t N
     for (int mt = 8; mt >= 2; mt /= 2) {
         const int bm = mt * 16;
         const int waves = mt == 8 ? 8 : 4;   // small tiles: 4-wave blocks, three of which fit a compute unit
+        const hipStream_t stream = streams[mt == 8 ? 0 : (mt == 4 ? 1 : 2)];
         const int nblocks_n = (ntiles + waves * MMA_NT - 1) / (waves * MMA_NT);
         const size_t lds = (size_t)(mt == 8 ? 3 : 2) * (kblk / 8) * bm * 16;
         items.count = 0;
@@ -209,8 +210,8 @@ int launch_grouped_typed(const void* A, const int32_t* offsets, int E, int64_t N
     }                                                                                                      \
     int fq_launch_grouped_typed_##ACT##_##BITS(const void* A, const int32_t* offsets, int E, int64_t N,    \
                                                int64_t K, const void* codes, const void* scales, int g,    \
-                                               void* C, hipStream_t stream) {                              \
-        return fqd::launch_grouped_typed<ACT, BITS>(A, offsets, E, N, K, codes, scales, g, C, stream);     \
+                                               void* C, const hipStream_t* streams) {                      \
+        return fqd::launch_grouped_typed<ACT, BITS>(A, offsets, E, N, K, codes, scales, g, C, streams);    \
     }
 
 #endif  // FQ_GEMM_DISPATCH_H_

@@ -242,3 +242,45 @@ def test_grouped_gemm_small(dtype, bits, g):
         if rows[e]:
             sl = slice(offsets[e], offsets[e + 1])
             assert_gemm_close(C[sl], C_ref[sl], dtype, f"expert {e}")
+
+
+def _grouped_case(dtype, bits, g, K, N, rows, seed, shared_weights=False):
+    """Experts with the given row counts; returns nothing, asserts parity per expert."""
+    fq = _fq()
+    torch = torch_mod()
+    E = len(rows)
+    offsets = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    A = workloads.activations(int(offsets[-1]), K, dtype, seed)
+    qs, ss, codes_l, scales_l = [], [], [], []
+    for e in range(E):
+        if e == 0 or not shared_weights:
+            W = workloads.weights_gaussian(K, N, seed + 50 + e, outlier_prob=1e-3)
+            c, s, q_ref, s_ref = assert_quantizer_parity(W, bits, g)
+        codes_l.append(c)
+        scales_l.append(s.reshape(-1))
+        qs.append(q_ref)
+        ss.append(s_ref)
+    codes = torch.cat(codes_l)
+    scales = torch.cat(scales_l)
+    out = torch.full((int(offsets[-1]), N), 3.0, dtype=torch.float16 if dtype == "f16" else torch.bfloat16, device="cuda")
+    fq.gemm_grouped(to_dev_act(A, dtype), offsets.tolist(), codes, scales, bits, g, N, out=out)
+    C = from_dev_act(out, dtype)
+    C_ref = oracle.gemm_ref_grouped(A, offsets, qs, ss)
+    for e in range(E):
+        if rows[e]:
+            sl = slice(offsets[e], offsets[e + 1])
+            assert_gemm_close(C[sl], C_ref[sl], dtype, f"expert {e} ({rows[e]} rows)")
+
+
+@pytest.mark.parametrize("dtype,bits,g", [("f16", 4, 64), ("bf16", 4, 128), ("bf16", 8, 32), ("f16", 8, 0)])
+def test_grouped_gemm_tile_boundaries(dtype, bits, g):
+    """Row counts on both sides of every row-tile size (32 / 64 / 128) and several column blocks with a
+    ragged last one for both the 4-wave (192 columns) and the 8-wave (384 columns) block shapes."""
+    _say(f"grouped tile boundaries {dtype} int{bits} g={g}")
+    _grouped_case(dtype, bits, g, 256, 400, [32, 33, 64, 65, 128, 129, 0, 193, 40, 161, 1], seed=31)
+
+
+def test_grouped_gemm_more_tiles_than_one_launch_holds():
+    """260 row tiles of 128 rows: the by-value tile list holds 256, so a second launch takes the rest."""
+    _say("grouped 130 experts x 256 rows")
+    _grouped_case("f16", 4, 128, 128, 48, [256] * 130, seed=32, shared_weights=True)

@@ -64,7 +64,8 @@ template <int ACT, int BITS>
 int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* codes, const void* scales,
                  int g, void* C, void* workspace, const fq_gemm_plan& plan, hipStream_t stream) {
     const int kblk = fq_kblk(BITS);
-    const bool per_step = (g % kblk) != 0;
+    // scale rows per k-block: 1, KBLK / g, or one per 32-row step when g does not divide KBLK
+    const int sr = (g % kblk) == 0 ? 1 : ((kblk % g) == 0 ? kblk / g : kblk / 32);
     const int ntiles = (int)(N / FQ_NTILE);
     float* partial = (float*)workspace;
     if (plan.kind == 0) {
@@ -86,23 +87,28 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
         dim3 grid((unsigned)((int64_t)nblocks_n * nblocks_m * plan.splits));
         fq_group_items none;
         none.count = 0;
-#define FQ_MMA_LAUNCH(MT_, W_, PIPE_)                                                                   \
+#define FQ_MMA_LAUNCH_SR(MT_, W_, PIPE_, SR_)                                                            \
     do {                                                                                                \
-        auto kern = per_step ? fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, true, false, PIPE_>      \
-                             : fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, false, false, PIPE_>;    \
+        auto kern = fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, SR_, false, PIPE_>;                 \
         if (lds > 65536) {                                                                              \
-            static bool raised[2] = {false, false};                                                     \
-            if (!raised[per_step ? 1 : 0]) {                                                            \
+            static bool raised = false;                                                                 \
+            if (!raised) {                                                                              \
                 if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,  \
                                         160 * 1024) != hipSuccess)                                      \
                     return FQ_ERR_HIP;                                                                  \
-                raised[per_step ? 1 : 0] = true;                                                        \
+                raised = true;                                                                          \
             }                                                                                           \
         }                                                                                               \
         hipLaunchKernelGGL(kern, grid, dim3(W_ * 64), lds, stream, (const uint16_t*)A,                  \
                            (const u32x4*)codes, (const uint16_t*)scales, (uint16_t*)C, partial, (int)M, \
                            (int)N, (int)K, g, plan.kb_per_split, plan.splits, nblocks_n, nblocks_m,     \
                            (int64_t)0, (int64_t)0, none);                                               \
+    } while (0)
+#define FQ_MMA_LAUNCH(MT_, W_, PIPE_)                                                                   \
+    do {                                                                                                \
+        if (sr == 1) FQ_MMA_LAUNCH_SR(MT_, W_, PIPE_, 1);                                               \
+        else if (sr == 2) FQ_MMA_LAUNCH_SR(MT_, W_, PIPE_, 2);                                          \
+        else if constexpr (BITS == 4) FQ_MMA_LAUNCH_SR(MT_, W_, PIPE_, 4);                              \
     } while (0)
         if (plan.waves == 8) {
             if (plan.mt == 2) FQ_MMA_LAUNCH(2, 8, false);
@@ -114,6 +120,7 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
             else FQ_MMA_LAUNCH(8, 4, false);
         }
 #undef FQ_MMA_LAUNCH
+#undef FQ_MMA_LAUNCH_SR
     }
     if (plan.splits > 1) {
         const int64_t MN = M * N;
@@ -132,7 +139,7 @@ template <int ACT, int BITS>
 int launch_grouped_typed(const void* A, const int32_t* offsets, int E, int64_t N, int64_t K,
                          const void* codes, const void* scales, int g, void* C, const hipStream_t* streams) {
     const int kblk = fq_kblk(BITS);
-    const bool per_step = (g % kblk) != 0;
+    const int sr = (g % kblk) == 0 ? 1 : ((kblk % g) == 0 ? kblk / g : kblk / 32);
     const int ntiles = (int)(N / FQ_NTILE);
     const int KB = (int)(K / kblk);
     const int64_t codes_stride16 = (int64_t)(K * N * BITS / 8) / 16;
@@ -148,17 +155,16 @@ int launch_grouped_typed(const void* A, const int32_t* offsets, int E, int64_t N
         auto flush_items = [&]() -> int {
             if (items.count == 0) return FQ_OK;
             dim3 grid((unsigned)((int64_t)nblocks_n * items.count));
-#define FQ_GROUPED_LAUNCH(MT_, W_, PIPE_)                                                                  \
+#define FQ_GROUPED_LAUNCH_SR(MT_, W_, PIPE_, SR_)                                                        \
     do {                                                                                                \
-        auto kern = per_step ? fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, true, true, PIPE_>       \
-                             : fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, false, true, PIPE_>;     \
+        auto kern = fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, SR_, true, PIPE_>;                  \
         if (lds > 65536) {                                                                              \
-            static bool raised[2] = {false, false};                                                     \
-            if (!raised[per_step ? 1 : 0]) {                                                            \
+            static bool raised = false;                                                                 \
+            if (!raised) {                                                                              \
                 if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,  \
                                         160 * 1024) != hipSuccess)                                      \
                     return FQ_ERR_HIP;                                                                  \
-                raised[per_step ? 1 : 0] = true;                                                        \
+                raised = true;                                                                          \
             }                                                                                           \
         }                                                                                               \
         hipLaunchKernelGGL(kern, grid, dim3(W_ * 64), lds, stream, (const uint16_t*)A,                  \
@@ -166,10 +172,17 @@ int launch_grouped_typed(const void* A, const int32_t* offsets, int E, int64_t N
                            0, (int)N, (int)K, g, KB, 1, nblocks_n, items.count, codes_stride16,         \
                            scales_stride, items);                                                       \
     } while (0)
+#define FQ_GROUPED_LAUNCH(MT_, W_, PIPE_)                                                               \
+    do {                                                                                                \
+        if (sr == 1) FQ_GROUPED_LAUNCH_SR(MT_, W_, PIPE_, 1);                                           \
+        else if (sr == 2) FQ_GROUPED_LAUNCH_SR(MT_, W_, PIPE_, 2);                                      \
+        else if constexpr (BITS == 4) FQ_GROUPED_LAUNCH_SR(MT_, W_, PIPE_, 4);                          \
+    } while (0)
             if (mt == 8) FQ_GROUPED_LAUNCH(8, 8, true);
             else if (mt == 4) FQ_GROUPED_LAUNCH(4, 4, false);
             else FQ_GROUPED_LAUNCH(2, 4, false);
 #undef FQ_GROUPED_LAUNCH
+#undef FQ_GROUPED_LAUNCH_SR
             items.count = 0;
             return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;
         };

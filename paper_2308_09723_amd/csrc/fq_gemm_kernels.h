@@ -591,7 +591,7 @@ __device__ inline uint32_t scale_operand(uint16_t h) {
     }
 }
 
-template <int ACT, int BITS, int MT, int NT, int WAVES, bool PER_STEP, bool GROUPED, bool PIPE>
+template <int ACT, int BITS, int MT, int NT, int WAVES, int SR, bool GROUPED, bool PIPE>
 __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
     const uint16_t* __restrict__ A, const u32x4* __restrict__ codes, const uint16_t* __restrict__ scales,
     uint16_t* __restrict__ C, float* __restrict__ partial, int M, int N, int K, int g, int kb_per_split,
@@ -609,7 +609,10 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
     constexpr int SWZ = 16 / KC;
     constexpr int NTHR = WAVES * 64;
     constexpr int UPT = (UNITS + NTHR - 1) / NTHR;
-    constexpr int SROWS = PER_STEP ? STEPS : 1;
+    // SR = scale rows a k-block spans: 1 when the group size is a multiple of KBLK, else KBLK / g
+    // (or one per 32-row k-step when g does not divide KBLK)
+    constexpr int SROWS = SR;
+    static_assert(SR >= 1 && SR <= STEPS && STEPS % SR == 0, "");
     extern __shared__ u32x4 lds[];   // [PIPE ? 3 : 2][KC * BM]
 
     const int tid = threadIdx.x;
@@ -691,15 +694,32 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
     const uint32_t magic = Dequant<ACT, BITS>::init();
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
     u32x4 wq[NT], wq_n[NT], areg[UPT];
-    uint16_t sc[SROWS][NT], sc_n[SROWS][NT];
-    auto load_w = [&](u32x4 (&q)[NT], uint16_t (&s)[SROWS][NT], int kb) {
+    // Scale registers: one per (scale row, column tile), or, with four scale rows per k-block,
+    // two rows per register (low / high half, filled by 16-bit loads into register halves).
+    constexpr int SPK = SROWS >= 4 ? 2 : 1;      // scale rows packed per register
+    constexpr int SREG = SROWS / SPK;
+    typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
+    uint32_t sc[SREG][NT], sc_n[SREG][NT];
+    auto load_w = [&](u32x4 (&q)[NT], uint32_t (&s)[SREG][NT], int kb) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) q[nt] = (wbase[nt] + (int64_t)kb * kb_stride)[lane];
 #pragma unroll
-        for (int r = 0; r < SROWS; ++r) {
-            const int64_t srow = (int64_t)((kb * KBLK + r * FQ_KSTEP) / g) * N;
+        for (int r = 0; r < SREG; ++r) {
+            if constexpr (SPK == 1) {
+                const int64_t srow = (int64_t)((kb * KBLK + r * (KBLK / SROWS)) / g) * N;
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) s[r][nt] = sbase[nt][srow + ml];
+                for (int nt = 0; nt < NT; ++nt) s[r][nt] = sbase[nt][srow + ml];
+            } else {
+                const int64_t srow0 = (int64_t)((kb * KBLK + (2 * r) * (KBLK / SROWS)) / g) * N;
+                const int64_t srow1 = (int64_t)((kb * KBLK + (2 * r + 1) * (KBLK / SROWS)) / g) * N;
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    u16x2 pr;
+                    pr[0] = sbase[nt][srow0 + ml];
+                    pr[1] = sbase[nt][srow1 + ml];
+                    s[r][nt] = bitcast<uint32_t>(pr);
+                }
+            }
         }
     };
     auto load_a = [&](int kb) {
@@ -715,8 +735,14 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
         for (int r = 0; r < UPT; ++r)
             if (a_dst[r] >= 0) dst[a_dst[r]] = a_ok[r] ? areg[r] : zero4;
     };
-    auto convert = [&](const u32x4 (&q)[NT], const uint16_t (&s)[SROWS][NT], int t, int nt) -> u32x4 {
-        const uint32_t s2 = scale_operand<ACT>(s[PER_STEP ? t : 0][nt]);
+    auto convert = [&](const u32x4 (&q)[NT], const uint32_t (&s)[SREG][NT], int t, int nt) -> u32x4 {
+        // opaque until here: otherwise the widening of the scale is moved to the end of the previous
+        // k-block, and with it the wait for the scale's load
+        const int srow = t / (STEPS / SROWS);
+        uint32_t h = s[srow / SPK][nt];
+        asm volatile("" : "+v"(h));
+        if (SPK == 2 && (srow & 1)) h >>= 16;
+        const uint32_t s2 = scale_operand<ACT>((uint16_t)h);
         if (t == 0) return DequantScaled<ACT, BITS>::template run<0>(q[nt], magic, s2);
         if (t == 1) return DequantScaled<ACT, BITS>::template run<1>(q[nt], magic, s2);
         if (STEPS > 2 && t == 2) return DequantScaled<ACT, BITS>::template run<2 % STEPS>(q[nt], magic, s2);
@@ -741,78 +767,97 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
         //     in the last APD slots), so the LDS latency is covered by matrix work;
         //   * the weights of k-step t + 1 are converted, one column tile per slot, into the other
         //     fragment set; in the last k-step these are the weights of step 0 of the next k-block;
-        //   * at slot WR_SLOT the next k-block's activation tile goes from registers to LDS and the
-        //     global loads of the tile after it are issued; at BAR_SLOT the one barrier per k-block
-        //     makes that tile visible before the first fragment of it is read.
-        // Three LDS buffers: the tile written during k-block kb was last read during kb - 2, which
-        // every wave has finished before any wave passes the barrier of kb - 1.
+        //   * the weight registers of k-block kb are reloaded with k-block kb + 2 as soon as their last
+        //     conversion is done (slot W_SLOT), and the two register sets swap roles every k-block,
+        //     so a weight load has more than a whole k-block to arrive;
+        //   * activations go from global memory straight into LDS (no registers, no staging
+        //     stores): at BAR_SLOT the wave waits for its own share of the next tile, the one barrier
+        //     per k-block makes the tile visible, and the loads of the tile after it are issued.
+        // Three LDS buffers: the tile loaded after the barrier of k-block kb replaces the one read
+        // during kb - 1, which every wave has finished before it arrives at that barrier.
+        // LDS tile layout, in 16-byte units: unit(row, kc) = row * KC + (kc ^ swz(row)).  A wave-level
+        // direct load fills 64 consecutive units = whole rows, each row a permutation of its own
+        // contiguous 16 * KC bytes in global memory; a fragment read (16 rows of one kc) touches 16
+        // different bank groups.  Rows past the end of the matrix load the last valid row; their
+        // results are never stored.
+        static_assert(UNITS % (NTHR) == 0 && (64 % KC) == 0, "whole rows per wave-level load");
         constexpr int BAR_SLOT = NFR - APD - 1;
-        constexpr int WR_SLOT = BAR_SLOT >= 2 ? BAR_SLOT - 2 : 0;
+        constexpr int W_SLOT = (STEPS - 2) * MT + (NT < MT ? NT : MT);   // after the last conversion from the set
+        constexpr int NWLOADS = NT + SROWS * NT;                          // vector loads of one load_w
+        auto swz = [](int row) { return KC == 16 ? (row & 15) : ((row >> 1) & 7); };
+        uint32_t d_off[UPT];   // element offset inside A (relative to row0, k-block 0) of this lane's unit
+#pragma unroll
+        for (int r = 0; r < UPT; ++r) {
+            const int u = (wave * UPT + r) * 64 + lane;
+            const int row = u / KC, kcp = u % KC;
+            const int rowc = row < rows ? row : rows - 1;
+            d_off[r] = (uint32_t)rowc * (uint32_t)K + (uint32_t)((kcp ^ swz(row)) * 8);
+        }
+        auto load_a_lds = [&](int kb, int bufi) {
+            const uint16_t* base = Arow + (int64_t)kb * KBLK;
+            // Written as assembly on purpose: issued through the compiler's builtin, these loads make
+            // its wait-count pass drain the whole memory queue (vmcnt(0)) at every later wait, which
+            // would undo the weight prefetch.  The compiler's own waits stay correct without knowing
+            // about them (the counter retires in order, so a wait for an older load only gets
+            // stricter); the waits for these loads themselves are written out below.
+            const uint32_t lds_base =
+                (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(lds + bufi * abuf_units + wave * UPT * 64);
+#pragma unroll
+            for (int r = 0; r < UPT; ++r) {
+                const uint16_t* src = base + d_off[r];
+                asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                             :
+                             : "s"(lds_base + r * 1024), "v"(src)
+                             : "memory", "m0");
+            }
+        };
+#pragma unroll
+        for (int t = 0; t < STEPS; ++t) a_rd[t] = ml * KC + ((4 * t + j) ^ swz(ml));
+
         int cur = 0;
         if (kb0 < kb1) {
             load_w(wq, sc, kb0);
-            load_a(kb0);
-            store_a(lds);
-            load_a(kb0 + 1 < kb1 ? kb0 + 1 : kb0);
+            load_w(wq_n, sc_n, kb0 + 1 < kb1 ? kb0 + 1 : kb0);
+            load_a_lds(kb0, 0);
+            load_a_lds(kb0 + 1 < kb1 ? kb0 + 1 : kb0, 1);
+            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): both tiles have landed
             __syncthreads();
 #pragma unroll
-            for (int i = 0; i < APD; ++i) afr[i] = lds[a_rd[i / MT] + (i % MT) * 16];
+            for (int i = 0; i < APD; ++i) afr[i] = lds[a_rd[i / MT] + (i % MT) * 16 * KC];
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) w[0][nt] = convert(wq, sc, 0, nt);
         }
-        for (int kb = kb0; kb < kb1; ++kb) {
+        // one k-block; (qa, sa) hold its weights, (qb, sb) those of the next one
+        auto kblock = [&](int kb, u32x4 (&qa)[NT], uint32_t (&sa)[SREG][NT], u32x4 (&qb)[NT],
+                          uint32_t (&sb)[SREG][NT]) {
             const int nxt = cur == 2 ? 0 : cur + 1;
+            const int nn = nxt == 2 ? 0 : nxt + 1;
             const u32x4* abuf = lds + cur * abuf_units;
-            u32x4* nbuf = lds + nxt * abuf_units;
-            load_w(wq_n, sc_n, kb + 1 < kb1 ? kb + 1 : kb);
+            const u32x4* nbuf = lds + nxt * abuf_units;
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int t = 0; t < STEPS; ++t) {
-#ifdef FQ_DEV_INTERLEAVE
-                if (t + 1 < STEPS) {
-#pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) w[(t + 1) & 1][nt] = convert(wq, sc, t + 1, nt);
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        const int i = t * MT + mt;
-                        const int ip = i + APD;
-                        afr[ip % (APD + 1)] = abuf[a_rd[ip / MT] + (ip % MT) * 16];
-                        const u32x4 a = afr[i % (APD + 1)];
-#pragma unroll
-                        for (int nt = 0; nt < NT; ++nt)
-                            acc[mt][nt] = mfma16x16x32<ACT>(w[t & 1][nt], a, acc[mt][nt]);
-                    }
-#pragma unroll
-                    for (int mt = 0; mt < MT; ++mt) {
-                        __builtin_amdgcn_sched_group_barrier(0x100, 1, 0);
-#pragma unroll
-                        for (int nt = 0; nt < NT; ++nt) {
-                            __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                            __builtin_amdgcn_sched_group_barrier(0x002, FQ_DEV_INTERLEAVE, 0);
-                        }
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                    continue;
-                }
-#endif
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
                     const int i = t * MT + mt;
-                    if (i == WR_SLOT) {
-                        store_a(nbuf);
-                        load_a(kb + 2 < kb1 ? kb + 2 : kb1 - 1);
+                    if (i == W_SLOT) load_w(qa, sa, kb + 2 < kb1 ? kb + 2 : kb1 - 1);
+                    if (i == BAR_SLOT) {
+                        // this wave's share of the next tile (issued a k-block ago) has landed once at
+                        // most the weight loads issued since are still in flight
+                        __builtin_amdgcn_s_waitcnt(0x0F70 | (NWLOADS & 15) | ((NWLOADS >> 4) << 14));
+                        __syncthreads();
+                        load_a_lds(kb + 2 < kb1 ? kb + 2 : kb1 - 1, nn);
                     }
-                    if (i == BAR_SLOT) __syncthreads();
                     const int ip = i + APD;
                     if (ip < NFR) {
-                        afr[ip % (APD + 1)] = abuf[a_rd[ip / MT] + (ip % MT) * 16];
+                        afr[ip % (APD + 1)] = abuf[a_rd[ip / MT] + (ip % MT) * 16 * KC];
                     } else {
-                        afr[ip % (APD + 1)] = nbuf[a_rd[(ip - NFR) / MT] + ((ip - NFR) % MT) * 16];
+                        afr[ip % (APD + 1)] = nbuf[a_rd[(ip - NFR) / MT] + ((ip - NFR) % MT) * 16 * KC];
                     }
 #pragma unroll
                     for (int nt = mt; nt < NT; nt += MT) {
-                        if (t + 1 < STEPS) w[(t + 1) & 1][nt] = convert(wq, sc, t + 1, nt);
-                        else w[0][nt] = convert(wq_n, sc_n, 0, nt);
+                        if (t + 1 < STEPS) w[(t + 1) & 1][nt] = convert(qa, sa, t + 1, nt);
+                        else w[0][nt] = convert(qb, sb, 0, nt);
                     }
                     // keep the read and the conversion above where they are: without this the scheduler
                     // sinks them next to their uses and every fragment is then waited for
@@ -822,14 +867,17 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
                     for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = mfma16x16x32<ACT>(w[t & 1][nt], a, acc[mt][nt]);
                 }
             }
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) wq[nt] = wq_n[nt];
-#pragma unroll
-            for (int r = 0; r < SROWS; ++r)
-#pragma unroll
-                for (int nt = 0; nt < NT; ++nt) sc[r][nt] = sc_n[r][nt];
             cur = nxt;
+        };
+        int kb = kb0;
+        for (; kb + 1 < kb1; kb += 2) {
+            kblock(kb, wq, sc, wq_n, sc_n);
+            kblock(kb + 1, wq_n, sc_n, wq, sc);
         }
+        if (kb < kb1) kblock(kb, wq, sc, wq_n, sc_n);
+        // the last (redundant) direct loads still target this block's LDS: let them land before
+        // the block can end and its LDS be given to another block
+        __builtin_amdgcn_s_waitcnt(0x0F70);
     } else {
         // Two LDS buffers, one barrier at the top of every k-block: a smaller footprint in LDS and
         // registers, so that two blocks fit a compute unit, which pays for the block shapes that
@@ -873,7 +921,7 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) wq[nt] = wq_n[nt];
 #pragma unroll
-            for (int r = 0; r < SROWS; ++r)
+            for (int r = 0; r < SREG; ++r)
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) sc[r][nt] = sc_n[r][nt];
             buf ^= 1;

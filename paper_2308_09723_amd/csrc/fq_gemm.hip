@@ -5,10 +5,6 @@
 #include <math.h>
 #include <mutex>
 #include <stdint.h>
-#ifdef FQ_DEV_PLAN_ENV
-#include <stdio.h>
-#include <stdlib.h>
-#endif
 
 #include "fq_gemm_config.h"
 #include "fq_internal.h"

@@ -82,6 +82,10 @@ def main():
                          "slower for the first ~0.1-0.5 s of sustained load (clock ramp); 0 disables")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--large-m", action="store_true", help="also time the M >= 256 products (reported under 'extra')")
+    ap.add_argument("--all-configs", action="store_true",
+                    help="also time the other BASELINE configurations (reported under 'extra'): prefill and mid-M "
+                         "products (configs[2]), the grouped expert products (configs[3]) and the heavy-tailed "
+                         "stress layer (configs[4])")
     ap.add_argument("--profile", choices=["decode", "prefill", "copy"], default=None,
                     help="short untimed run of one case for rocprofv3 (no JSON line): 'decode' = the benchmark "
                          "step, 'prefill' = QKV-shaped product at M = 2048 (bf16), 'copy' = a 1 GiB device copy "
@@ -236,8 +240,13 @@ def main():
         },
         "per_product": per_layer,
     }
-    if args.large_m:
-        out["extra"] = large_m_section(torch, fq, layers)
+    if args.large_m or args.all_configs:
+        out["extra"] = large_m_section(torch, fq, layers, (32, 128, 512, 2048) if args.all_configs else (256, 2048))
+    if args.all_configs:
+        del layers, calls
+        torch.cuda.empty_cache()
+        out["extra_moe"] = moe_section(torch, fq, workloads)
+        out["extra_stress"] = stress_section(torch, fq, workloads)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
@@ -271,12 +280,112 @@ def profile_prefill(torch, fq, workloads, reps, settle):
     torch.cuda.synchronize()
 
 
-def large_m_section(torch, fq, layers):
+def _timed(torch, run, settle=0.3, reps=20):
+    """Mean milliseconds per call of run(), after `settle` seconds of the same call."""
+    run()
+    torch.cuda.synchronize()
+    t_end = time.perf_counter() + settle
+    while time.perf_counter() < t_end:
+        for _ in range(4):
+            run()
+        torch.cuda.synchronize()
+    e0 = torch.cuda.Event(enable_timing=True)
+    e1 = torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(reps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    return e0.elapsed_time(e1) / reps
+
+
+def moe_section(torch, fq, workloads):
+    """BASELINE configs[3]: 64 experts, d_model 4096, d_ff 16384, int4 g = 64, fp16; 2048 tokens routed top-2
+    with Zipf(1.1) popularity.  FC1 and FC2 timed separately.  Both rooflines are reported: the weights of
+    the experts that received rows must be read once (HBM), and 2 * rows * K * N flops must be done (MFMA)."""
+    import numpy as np
+    E = workloads.MOE["experts"]
+    dm, dff = workloads.MOE["d_model"], workloads.MOE["d_ff"]
+    offsets, _ = workloads.zipf_routing(2048, E, 2, 1.1, seed=5)
+    counts = np.diff(offsets)
+    rows = int(offsets[-1])
+    hit = int((counts > 0).sum())
+    stream = torch.cuda.current_stream().cuda_stream
+    res = {"rows_per_expert": counts.tolist()}
+    for K, N, tag in ((dm, dff, "fc1"), (dff, dm, "fc2")):
+        codes_l, scales_l = [], []
+        for e in range(E):
+            c, s = fq.quantize(make_weight(torch, K, N, 500 + e), 4, 64)
+            codes_l.append(c)
+            scales_l.append(s.reshape(-1))
+        codes = torch.cat(codes_l)
+        scales = torch.cat(scales_l)
+        del codes_l, scales_l
+        A = torch.randn((rows, K), device="cuda", dtype=torch.float32).to(torch.float16)
+        C = torch.empty((rows, N), device="cuda", dtype=torch.float16)
+        offs = offsets.tolist()
+
+        def run():
+            st = fq.gemm_grouped_raw(A.data_ptr(), fq.FQ_F16, offs, N, K, codes.data_ptr(), scales.data_ptr(), 4, 64,
+                                     C.data_ptr(), None, 0, stream)
+            if st != fq.FQ_OK:
+                raise fq.FqError(st, "fq_gemm_grouped")
+        ms = _timed(torch, run, settle=0.5, reps=10)
+        wbytes = hit * (K * N // 2 + (K // 64) * N * 2)
+        flops = 2.0 * rows * K * N
+        res[tag] = {"ms": round(ms, 4), "weight_TBps": round(wbytes / ms / 1e9, 3),
+                    "frac_of_hbm_peak": round(wbytes / ms / 1e6 / HBM_PEAK_GBS, 4),
+                    "TFLOPs": round(flops / ms / 1e9, 1), "frac_of_mfma_peak": round(flops / ms / 1e9 / MFMA_PEAK_TFLOPS, 4),
+                    "experts_hit": hit, "weight_bytes": wbytes}
+        del codes, scales, A, C
+        torch.cuda.empty_cache()
+    return res
+
+
+def stress_section(torch, fq, workloads):
+    """BASELINE configs[4]: K = 8192, N = 28672, 0.02 * Student-t(3) weights with 1 % of the columns x50,
+    bf16 activations and output, M in {1, 16, 256}, int4 and int8 at g in {32, 128, K}."""
+    K, N = workloads.STRESS_LAYER
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(900)
+    # Student-t(3) = normal / sqrt(chi2_3 / 3)
+    z = torch.randn((K, N), generator=gen, device="cuda")
+    chi = (torch.randn((3, K, N), generator=gen, device="cuda") ** 2).sum(0)
+    W = 0.02 * z / torch.sqrt(chi / 3.0)
+    del z, chi
+    cols = torch.rand((N,), generator=gen, device="cuda") < 0.01
+    W = torch.where(cols[None, :], W * 50.0, W).clamp_(-65504.0, 65504.0).to(torch.float16)
+    stream = torch.cuda.current_stream().cuda_stream
+    res = {}
+    for bits in (4, 8):
+        for g in (32, 128, 0):
+            codes, scales = fq.quantize(W, bits, g)
+            wbytes = codes.numel() + scales.numel() * 2
+            for M in (1, 16, 256):
+                A = torch.randn((M, K), device="cuda", dtype=torch.float32).to(torch.bfloat16)
+                C = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)
+                need = fq.gemm_workspace_bytes(M, N, K, bits, g)
+                ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+
+                def run():
+                    st = fq.gemm_raw(A.data_ptr(), fq.FQ_BF16, M, N, K, codes.data_ptr(), scales.data_ptr(), bits, g,
+                                     C.data_ptr(), ws.data_ptr(), ws.numel(), stream)
+                    if st != fq.FQ_OK:
+                        raise fq.FqError(st, "fq_gemm")
+                ms = _timed(torch, run, settle=0.15, reps=20)
+                res[f"int{bits}_g{g or K}_M{M}"] = {
+                    "us": round(ms * 1e3, 2), "weight_TBps": round(wbytes / ms / 1e9, 3),
+                    "TFLOPs": round(2.0 * M * N * K / ms / 1e9, 1), "plan": fq.gemm_describe(M, N, K, bits, g)}
+            del codes, scales
+    return res
+
+
+def large_m_section(torch, fq, layers, Ms=(256, 2048)):
     """Prefill-sized products on the same int4 weights: TFLOP/s and fraction of the dense MFMA peak."""
     res = {}
     stream = torch.cuda.current_stream().cuda_stream
     for name, K, N, codes, scales in layers:
-        for M in (256, 2048):
+        for M in Ms:
             for tag, act, dt in (("bf16", fq.FQ_BF16, torch.bfloat16), ("f16", fq.FQ_F16, torch.float16)):
                 A = torch.randn((M, K), device="cuda", dtype=torch.float32).to(dt)
                 C = torch.empty((M, N), device="cuda", dtype=dt)
@@ -306,8 +415,10 @@ def large_m_section(torch, fq, layers):
                 torch.cuda.synchronize()
                 ms = e0.elapsed_time(e1) / reps
                 tflops = 2.0 * M * N * K / (ms * 1e-3) / 1e12
+                wbytes = codes.numel() + scales.numel() * 2
                 res[f"{name}_M{M}_{tag}"] = {"ms": round(ms, 4), "TFLOPs": round(tflops, 1),
                                              "frac_of_mfma_peak": round(tflops / MFMA_PEAK_TFLOPS, 4),
+                                             "weight_TBps": round(wbytes / ms / 1e9, 3),
                                              "plan": fq.gemm_describe(M, N, K, BITS, GROUP)}
     return res
 

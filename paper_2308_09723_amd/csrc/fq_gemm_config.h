@@ -6,6 +6,17 @@ namespace fqd {
 
 constexpr int MMA_NT = 3;       // column tiles per wave of the large-M kernel
 
+// Ring depth (k-blocks in flight) of the pipelined form of the large-M kernel for the 64-row and
+// the 32-row block shapes; 0 selects the two-buffer form.  The 128-row, 8-wave shape uses depth 2.
+// Measured on the OPT-175B shapes at M = 32 and 64: depth 2 is 2-6 % faster than the two-buffer form,
+// depths 3 and 4 are slower (their registers cost a resident wave per SIMD).
+#ifndef FQ_RING_MT4
+#define FQ_RING_MT4 2
+#endif
+#ifndef FQ_RING_MT2
+#define FQ_RING_MT2 2
+#endif
+
 // Small-M kernel variants that are compiled in: (NT column tiles per wave, ring DEPTH,
 // register class = maximum waves per block).  The plan picks one of them plus the run-time
 // block shape (GP column groups x KW k-workers).

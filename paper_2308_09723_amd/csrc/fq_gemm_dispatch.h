@@ -81,9 +81,10 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
         const int bm = plan.mt * 16;
         const int nblocks_n = (ntiles + plan.waves * MMA_NT - 1) / (plan.waves * MMA_NT);
         const int nblocks_m = (int)((M + bm - 1) / bm);
-        // 128 rows x 8 waves runs the three-buffer pipeline; the other shapes keep two buffers
-        const bool pipe = plan.mt == 8 && plan.waves == 8;
-        const size_t lds = (size_t)(pipe ? 3 : 2) * (kblk / 8) * bm * 16;
+        // ring depth of the pipelined form per block shape (0 = two-buffer form); must match the
+        // instantiations below
+        const int ring = plan.mt == 8 ? (plan.waves == 8 ? 2 : 0) : (plan.mt == 4 ? FQ_RING_MT4 : FQ_RING_MT2);
+        const size_t lds = (size_t)(ring ? ring + 1 : 2) * (kblk / 8) * bm * 16;
         dim3 grid((unsigned)((int64_t)nblocks_n * nblocks_m * plan.splits));
         fq_group_items none;
         none.count = 0;
@@ -111,13 +112,13 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
         else if constexpr (BITS == 4) FQ_MMA_LAUNCH_SR(MT_, W_, PIPE_, 4);                              \
     } while (0)
         if (plan.waves == 8) {
-            if (plan.mt == 2) FQ_MMA_LAUNCH(2, 8, false);
-            else if (plan.mt == 4) FQ_MMA_LAUNCH(4, 8, false);
-            else FQ_MMA_LAUNCH(8, 8, true);
+            if (plan.mt == 2) FQ_MMA_LAUNCH(2, 8, FQ_RING_MT2);
+            else if (plan.mt == 4) FQ_MMA_LAUNCH(4, 8, FQ_RING_MT4);
+            else FQ_MMA_LAUNCH(8, 8, 2);
         } else {
-            if (plan.mt == 2) FQ_MMA_LAUNCH(2, 4, false);
-            else if (plan.mt == 4) FQ_MMA_LAUNCH(4, 4, false);
-            else FQ_MMA_LAUNCH(8, 4, false);
+            if (plan.mt == 2) FQ_MMA_LAUNCH(2, 4, FQ_RING_MT2);
+            else if (plan.mt == 4) FQ_MMA_LAUNCH(4, 4, FQ_RING_MT4);
+            else FQ_MMA_LAUNCH(8, 4, 0);
         }
 #undef FQ_MMA_LAUNCH
 #undef FQ_MMA_LAUNCH_SR
@@ -150,7 +151,8 @@ int launch_grouped_typed(const void* A, const int32_t* offsets, int E, int64_t N
         const int waves = mt == 8 ? 8 : 4;   // small tiles: 4-wave blocks, three of which fit a compute unit
         const hipStream_t stream = streams[mt == 8 ? 0 : (mt == 4 ? 1 : 2)];
         const int nblocks_n = (ntiles + waves * MMA_NT - 1) / (waves * MMA_NT);
-        const size_t lds = (size_t)(mt == 8 ? 3 : 2) * (kblk / 8) * bm * 16;
+        const int ring = mt == 8 ? 2 : (mt == 4 ? FQ_RING_MT4 : FQ_RING_MT2);
+        const size_t lds = (size_t)(ring ? ring + 1 : 2) * (kblk / 8) * bm * 16;
         items.count = 0;
         auto flush_items = [&]() -> int {
             if (items.count == 0) return FQ_OK;
@@ -178,9 +180,9 @@ int launch_grouped_typed(const void* A, const int32_t* offsets, int E, int64_t N
         else if (sr == 2) FQ_GROUPED_LAUNCH_SR(MT_, W_, PIPE_, 2);                                      \
         else if constexpr (BITS == 4) FQ_GROUPED_LAUNCH_SR(MT_, W_, PIPE_, 4);                          \
     } while (0)
-            if (mt == 8) FQ_GROUPED_LAUNCH(8, 8, true);
-            else if (mt == 4) FQ_GROUPED_LAUNCH(4, 4, false);
-            else FQ_GROUPED_LAUNCH(2, 4, false);
+            if (mt == 8) FQ_GROUPED_LAUNCH(8, 8, 2);
+            else if (mt == 4) FQ_GROUPED_LAUNCH(4, 4, FQ_RING_MT4);
+            else FQ_GROUPED_LAUNCH(2, 4, FQ_RING_MT2);
 #undef FQ_GROUPED_LAUNCH
 #undef FQ_GROUPED_LAUNCH_SR
             items.count = 0;

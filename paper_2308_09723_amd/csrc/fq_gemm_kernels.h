@@ -591,7 +591,14 @@ __device__ inline uint32_t scale_operand(uint16_t h) {
     }
 }
 
-template <int ACT, int BITS, int MT, int NT, int WAVES, int SR, bool GROUPED, bool PIPE>
+// s_waitcnt vmcnt(N) only (the other counters left alone); gfx9 encoding: vmcnt in bits 3:0 and 15:14
+template <int N>
+__device__ inline void wait_vmcnt() {
+    static_assert(N >= 0 && N < 64, "");
+    __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
+}
+
+template <int ACT, int BITS, int MT, int NT, int WAVES, int SR, bool GROUPED, int PIPE>
 __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
     const uint16_t* __restrict__ A, const u32x4* __restrict__ codes, const uint16_t* __restrict__ scales,
     uint16_t* __restrict__ C, float* __restrict__ partial, int M, int N, int K, int g, int kb_per_split,
@@ -613,7 +620,7 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
     // (or one per 32-row k-step when g does not divide KBLK)
     constexpr int SROWS = SR;
     static_assert(SR >= 1 && SR <= STEPS && STEPS % SR == 0, "");
-    extern __shared__ u32x4 lds[];   // [PIPE ? 3 : 2][KC * BM]
+    extern __shared__ u32x4 lds[];   // [PIPE ? PIPE + 1 : 2][KC * BM]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -760,50 +767,61 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
     u32x4 w[2][NT];
     u32x4 afr[APD + 1];
 
-    if constexpr (PIPE) {
-        // The k loop is one software pipeline that does not drain at k-block boundaries.
-        // Slot i = t * MT + mt of a k-block holds the NT MFMAs of (k-step t, row tile mt); around them:
-        //   * the activation fragment of slot i + APD is read from LDS (from the next k-block's buffer
+    if constexpr (PIPE > 0) {
+        // PIPE = D >= 2: the k loop is one software pipeline, D k-blocks deep, that does not drain at
+        // k-block boundaries.  Slot i = t * MT + mt of a k-block holds the NT MFMAs of (k-step t, row
+        // tile mt); around them:
+        //   * the activation fragment of slot i + APD is read from LDS (from the next k-block's tile
         //     in the last APD slots), so the LDS latency is covered by matrix work;
         //   * the weights of k-step t + 1 are converted, one column tile per slot, into the other
         //     fragment set; in the last k-step these are the weights of step 0 of the next k-block;
-        //   * the weight registers of k-block kb are reloaded with k-block kb + 2 as soon as their last
-        //     conversion is done (slot W_SLOT), and the two register sets swap roles every k-block,
-        //     so a weight load has more than a whole k-block to arrive;
-        //   * activations go from global memory straight into LDS (no registers, no staging
-        //     stores): at BAR_SLOT the wave waits for its own share of the next tile, the one barrier
-        //     per k-block makes the tile visible, and the loads of the tile after it are issued.
-        // Three LDS buffers: the tile loaded after the barrier of k-block kb replaces the one read
-        // during kb - 1, which every wave has finished before it arrives at that barrier.
+        //   * D weight register sets: the set of k-block kb is reloaded with k-block kb + D as soon
+        //     as its last conversion is done (slot W_SLOT); the sets take turns by unrolling the loop
+        //     D times, so nothing in flight is ever copied;
+        //   * D + 1 LDS tiles, filled straight from global memory (no registers, no staging stores):
+        //     at BAR_SLOT the wave waits for its own share of tile kb + 1, the one barrier per
+        //     k-block makes that tile visible, and the loads of tile kb + D are issued into the tile
+        //     read during kb - 1, which every wave has finished before it arrives at that barrier.
         // LDS tile layout, in 16-byte units: unit(row, kc) = row * KC + (kc ^ swz(row)).  A wave-level
         // direct load fills 64 consecutive units = whole rows, each row a permutation of its own
         // contiguous 16 * KC bytes in global memory; a fragment read (16 rows of one kc) touches 16
         // different bank groups.  Rows past the end of the matrix load the last valid row; their
         // results are never stored.
-        static_assert(UNITS % (NTHR) == 0 && (64 % KC) == 0, "whole rows per wave-level load");
+        constexpr int D = PIPE;
+        constexpr int NI = UNITS / 64;                  // wave-level direct loads per tile
+        constexpr int DPT = NI >= WAVES ? NI / WAVES : 1;   // of which this wave issues DPT (or none)
+        static_assert(UNITS % 64 == 0 && 64 % KC == 0 && (NI % WAVES == 0 || NI < WAVES),
+                      "every wave issues the same number of direct loads, or none");
+        static_assert(D >= 2, "");
         constexpr int BAR_SLOT = NFR - APD - 1;
         constexpr int W_SLOT = (STEPS - 2) * MT + (NT < MT ? NT : MT);   // after the last conversion from the set
-        constexpr int NWLOADS = NT + SROWS * NT;                          // vector loads of one load_w
+        constexpr bool W_FIRST = W_SLOT <= BAR_SLOT;    // order of the two issue points inside a k-block
+        constexpr int NWLOADS = NT + SREG * SPK * NT;   // vector loads of one load_w
+        // loads issued after those of tile kb + 1 and before the barrier of k-block kb
+        constexpr int NYOUNGER = (D - 1) * NWLOADS + (D - 2) * DPT;
+        static_assert(NYOUNGER < 64 && (D - 1) * (NWLOADS + DPT) < 64, "wait counter range");
         auto swz = [](int row) { return KC == 16 ? (row & 15) : ((row >> 1) & 7); };
-        uint32_t d_off[UPT];   // element offset inside A (relative to row0, k-block 0) of this lane's unit
+        const bool a_loader = NI >= WAVES || wave < NI;   // wave-uniform
+        uint32_t d_off[DPT];   // element offset inside A (relative to row0, k-block 0) of this lane's unit
 #pragma unroll
-        for (int r = 0; r < UPT; ++r) {
-            const int u = (wave * UPT + r) * 64 + lane;
+        for (int r = 0; r < DPT; ++r) {
+            const int u = (wave * DPT + r) * 64 + lane;
             const int row = u / KC, kcp = u % KC;
             const int rowc = row < rows ? row : rows - 1;
             d_off[r] = (uint32_t)rowc * (uint32_t)K + (uint32_t)((kcp ^ swz(row)) * 8);
         }
         auto load_a_lds = [&](int kb, int bufi) {
+            if (!a_loader) return;
             const uint16_t* base = Arow + (int64_t)kb * KBLK;
             // Written as assembly on purpose: issued through the compiler's builtin, these loads make
             // its wait-count pass drain the whole memory queue (vmcnt(0)) at every later wait, which
             // would undo the weight prefetch.  The compiler's own waits stay correct without knowing
             // about them (the counter retires in order, so a wait for an older load only gets
             // stricter); the waits for these loads themselves are written out below.
-            const uint32_t lds_base =
-                (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(lds + bufi * abuf_units + wave * UPT * 64);
+            const uint32_t lds_base = __builtin_amdgcn_readfirstlane(
+                (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(lds + bufi * abuf_units + wave * DPT * 64));
 #pragma unroll
-            for (int r = 0; r < UPT; ++r) {
+            for (int r = 0; r < DPT; ++r) {
                 const uint16_t* src = base + d_off[r];
                 asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
                              :
@@ -814,24 +832,30 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
 #pragma unroll
         for (int t = 0; t < STEPS; ++t) a_rd[t] = ml * KC + ((4 * t + j) ^ swz(ml));
 
+        u32x4 wqs[D][NT];
+        uint32_t scs[D][SREG][NT];
         int cur = 0;
         if (kb0 < kb1) {
-            load_w(wq, sc, kb0);
-            load_w(wq_n, sc_n, kb0 + 1 < kb1 ? kb0 + 1 : kb0);
-            load_a_lds(kb0, 0);
-            load_a_lds(kb0 + 1 < kb1 ? kb0 + 1 : kb0, 1);
-            __builtin_amdgcn_s_waitcnt(0x0F70);   // vmcnt(0): both tiles have landed
+            // same issue order as inside the loop, so that the wait counts below hold from the start
+#pragma unroll
+            for (int u = 0; u < D; ++u) {
+                const int kbu = kb0 + u < kb1 ? kb0 + u : kb1 - 1;
+                if (W_FIRST) load_w(wqs[u], scs[u], kbu);
+                load_a_lds(kbu, u);
+                if (!W_FIRST) load_w(wqs[u], scs[u], kbu);
+            }
+            wait_vmcnt<(D - 1) * (NWLOADS + DPT)>();   // tile 0 and weight set 0 have landed
             __syncthreads();
 #pragma unroll
             for (int i = 0; i < APD; ++i) afr[i] = lds[a_rd[i / MT] + (i % MT) * 16 * KC];
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) w[0][nt] = convert(wq, sc, 0, nt);
+            for (int nt = 0; nt < NT; ++nt) w[0][nt] = convert(wqs[0], scs[0], 0, nt);
         }
         // one k-block; (qa, sa) hold its weights, (qb, sb) those of the next one
         auto kblock = [&](int kb, u32x4 (&qa)[NT], uint32_t (&sa)[SREG][NT], u32x4 (&qb)[NT],
                           uint32_t (&sb)[SREG][NT]) {
-            const int nxt = cur == 2 ? 0 : cur + 1;
-            const int nn = nxt == 2 ? 0 : nxt + 1;
+            const int nxt = cur == D ? 0 : cur + 1;
+            const int last = cur == 0 ? D : cur - 1;     // the tile read during kb - 1
             const u32x4* abuf = lds + cur * abuf_units;
             const u32x4* nbuf = lds + nxt * abuf_units;
             __builtin_amdgcn_sched_barrier(0);
@@ -840,13 +864,13 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
                     const int i = t * MT + mt;
-                    if (i == W_SLOT) load_w(qa, sa, kb + 2 < kb1 ? kb + 2 : kb1 - 1);
+                    if (i == W_SLOT) load_w(qa, sa, kb + D < kb1 ? kb + D : kb1 - 1);
                     if (i == BAR_SLOT) {
-                        // this wave's share of the next tile (issued a k-block ago) has landed once at
-                        // most the weight loads issued since are still in flight
-                        __builtin_amdgcn_s_waitcnt(0x0F70 | (NWLOADS & 15) | ((NWLOADS >> 4) << 14));
+                        // this wave's share of tile kb + 1 has landed once at most the loads issued
+                        // after it are still in flight
+                        wait_vmcnt<NYOUNGER>();
                         __syncthreads();
-                        load_a_lds(kb + 2 < kb1 ? kb + 2 : kb1 - 1, nn);
+                        load_a_lds(kb + D < kb1 ? kb + D : kb1 - 1, last);
                     }
                     const int ip = i + APD;
                     if (ip < NFR) {
@@ -870,14 +894,20 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
             cur = nxt;
         };
         int kb = kb0;
-        for (; kb + 1 < kb1; kb += 2) {
-            kblock(kb, wq, sc, wq_n, sc_n);
-            kblock(kb + 1, wq_n, sc_n, wq, sc);
+        for (; kb + D <= kb1; kb += D) {
+#pragma unroll
+            for (int u = 0; u < D; ++u) kblock(kb + u, wqs[u], scs[u], wqs[(u + 1) % D], scs[(u + 1) % D]);
         }
-        if (kb < kb1) kblock(kb, wq, sc, wq_n, sc_n);
+#pragma unroll
+        for (int u = 0; u < D - 1; ++u) {
+            if (kb < kb1) {
+                kblock(kb, wqs[u], scs[u], wqs[u + 1], scs[u + 1]);
+                ++kb;
+            }
+        }
         // the last (redundant) direct loads still target this block's LDS: let them land before
         // the block can end and its LDS be given to another block
-        __builtin_amdgcn_s_waitcnt(0x0F70);
+        wait_vmcnt<0>();
     } else {
         // Two LDS buffers, one barrier at the top of every k-block: a smaller footprint in LDS and
         // registers, so that two blocks fit a compute unit, which pays for the block shapes that

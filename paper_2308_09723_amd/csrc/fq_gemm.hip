@@ -33,9 +33,10 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
     const int ntiles = (int)(N / FQ_NTILE);
     if (M <= 16) {
         // One block per compute unit, all resident at once.  Candidates are scored by how evenly
-        // the column tiles fill 256 blocks, by the bytes a compute unit keeps in flight
-        // (waves x NT KiB x ring depth, ~64 KiB saturates), and by how many activation units a
-        // lane must stage (fewer registers); ties keep the earlier variant.
+        // the column tiles (times the grid's split of K) fill 256 blocks, by the bytes a compute
+        // unit keeps in flight (waves x NT KiB x ring depth, ~64 KiB saturates), and by how many
+        // activation units a lane must stage (fewer registers); ties keep the earlier variant.
+        // The factors come from sweeps over the OPT-175B shapes at M = 1 and 8.
         p.kind = 0;
         p.mt = 1;
         const int kc = kblk / 8;
@@ -46,8 +47,6 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
             for (int gp = 1; gp <= sv.maxw; ++gp) {
                 const int tb = sv.nt * gp;
                 const int64_t blocks = (ntiles + tb - 1) / tb;
-                const int64_t rounds = (blocks + 255) / 256;
-                const double eff = (double)ntiles / (double)(rounds * 256 * tb);
                 const int need = (int)M * kc;
                 const int au = need <= 64 * gp ? 1 : (need <= 128 * gp ? 2 : (need <= 256 * gp ? 4 : 0));
                 if (au == 0) continue;
@@ -55,11 +54,28 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
                 if (kw > 8) kw = 8;
                 if (kw > KB) kw = KB;
                 if (kw < 1) continue;
+                const int SB = (KB + kw - 1) / kw;       // iterations if one block walks all of K
+                // Few column blocks: K is also split over the grid (binary32 partials + a second kernel),
+                // which moreover divides the activation bytes every block has to fetch.
+                int gs = 1;
+                if (blocks <= 128) gs = (int)(256 / blocks);
+                if (gs > 8) gs = 8;
+                if (gs > SB) gs = SB;
+                const int64_t grid = blocks * gs;
+                const int64_t rounds = (grid + 255) / 256;
+                const double eff = (double)ntiles * gs / (double)(rounds * 256 * tb);
                 const int waves = gp * kw;
                 const double inflight = (double)waves * sv.nt * sv.depth;   // KiB
+                const double n_it = (double)((SB + gs - 1) / gs);
                 double score = eff * eff * (inflight >= 64.0 ? 1.0 : sqrt(inflight / 64.0)) * f_nt[sv.nt];
                 score /= 1.0 + 0.1 * (double)(rounds - 1);   // a single resident round beats several
                 score *= au == 1 ? 1.0 : (au == 2 ? 0.8 : 0.6);
+                // a split of K over the grid costs a second kernel, and with few iterations left per
+                // block the register ring is mostly filling and draining
+                if (gs > 1) score *= n_it >= 16.0 ? 0.93 : 0.72;
+                // every block fetches its whole k range of the activations: M * K * 2 / gs bytes,
+                // 256 times over, next to K * N * bits / 8 bytes of weights
+                score /= 1.0 + 0.15 * ((double)M * 2.0 * 256.0 / gs) / ((double)N * bits / 8.0);
                 if (waves < 6) score *= 0.85;
                 if (score > best + 1e-9) {
                     best = score;
@@ -68,17 +84,10 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
                     p.kw = kw;
                     p.au = au;
                     p.waves = waves;
+                    p.splits = gs;
                 }
             }
         }
-        const SkinnyVariant sv = SKINNY_VARIANTS[p.variant];
-        const int64_t blocks = (ntiles + sv.nt * p.gp - 1) / (sv.nt * p.gp);
-        const int SB = (KB + p.kw - 1) / p.kw;
-        int gs = 1;
-        if (blocks <= 128) gs = (int)(256 / blocks);
-        if (gs > 8) gs = 8;
-        if (gs > SB) gs = SB;
-        p.splits = gs;
         p.kb_per_split = 0;
     } else {
         // Tiled MFMA kernel: BM = 16 * mt rows per block, 48 columns per wave, 4 or 8 waves, and

@@ -132,6 +132,32 @@ def test_gemm_tiled(dtype, bits, g, M):
     _gemm_case(M, 768, 304, dtype, bits, g, seed=2000 + M + bits + g)
 
 
+def _sweep_cases():
+    """Seeded draw of (M, K, N, dtype, bits, g): M on both sides of every plan boundary, K from one to a
+    few k-blocks (so that the pipelined loops run their prologue, their unrolled body and their tail with
+    clamped prefetches), N from one column tile to several ragged column blocks."""
+    rng = np.random.default_rng(20240611)
+    Ms = [1, 2, 7, 15, 16, 17, 31, 32, 33, 63, 64, 65, 96, 127, 128, 129, 200, 257, 300]
+    cases = []
+    for i in range(48):
+        bits = int(rng.choice([4, 8]))
+        kblk = 128 if bits == 4 else 64
+        K = kblk * int(rng.choice([1, 2, 3, 4, 5, 7, 12]))
+        N = 16 * int(rng.choice([1, 2, 3, 5, 12, 13, 24, 25, 31, 49]))
+        gs = [g for g in (32, 64, 96, 128, 256, 0) if g == 0 or (g <= K and K % g == 0)]
+        g = int(rng.choice(gs))
+        M = int(Ms[i % len(Ms)])
+        dtype = "f16" if rng.integers(2) else "bf16"
+        cases.append((M, K, N, dtype, bits, g))
+    return cases
+
+
+@pytest.mark.parametrize("M,K,N,dtype,bits,g", _sweep_cases())
+def test_gemm_shape_sweep(M, K, N, dtype, bits, g):
+    _say(f"gemm sweep M={M} K={K} N={N} {dtype} int{bits} g={g}")
+    _gemm_case(M, K, N, dtype, bits, g, seed=7000 + M + K + N + bits + g)
+
+
 @pytest.mark.parametrize("dtype,bits,g,M", [("f16", 4, 96, 8), ("bf16", 4, 192, 33), ("f16", 8, 96, 3), ("bf16", 8, 160, 70)])
 def test_gemm_group_sizes_that_are_not_powers_of_two(dtype, bits, g, M):
     _say(f"gemm odd group {dtype} int{bits} g={g} M={M}")

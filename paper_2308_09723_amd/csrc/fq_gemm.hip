@@ -72,11 +72,12 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
                 score *= au == 1 ? 1.0 : (au == 2 ? 0.8 : 0.6);
                 // a split of K over the grid costs a second kernel, and with few iterations left per
                 // block the register ring is mostly filling and draining
-                if (gs > 1) score *= n_it >= 16.0 ? 0.93 : 0.72;
+                if (gs > 1) score *= n_it >= 16.0 ? 0.80 : 0.65;
                 // every block fetches its whole k range of the activations: M * K * 2 / gs bytes,
                 // 256 times over, next to K * N * bits / 8 bytes of weights
                 score /= 1.0 + 0.15 * ((double)M * 2.0 * 256.0 / gs) / ((double)N * bits / 8.0);
                 if (waves < 6) score *= 0.85;
+                if (kw == 1) score *= 0.95;                  // no k-workers: measured ~5 % slower
                 if (score > best + 1e-9) {
                     best = score;
                     p.variant = v;

@@ -225,10 +225,13 @@ __device__ inline void flush(f32x4& acc, const f32x4& p, const f32x4& s, float r
 template <int BITS, int NT, bool PER_STEP, int AU_>
 struct SkinnyStage {
     static constexpr int STEPS = (BITS == 4 ? 128 : 64) / FQ_KSTEP;
-    static constexpr int SROWS = PER_STEP ? STEPS : 1;
     static constexpr int AU = AU_;
     u32x4 wq[NT];
-    u32x2 sc[SROWS][NT];
+    // four scales (output columns 4j .. 4j+3) of one scale row.  PER_STEP: the lane holds the row of
+    // k-step (lane % STEPS), so each quad of lanes holds all the rows of the k-block and a
+    // quad broadcast hands every lane the row of the step at hand: one load per tile and k-block
+    // instead of one per step.
+    u32x2 sc[NT];
     u32x4 areg[AU];
 };
 
@@ -236,6 +239,15 @@ __device__ inline f32x4 scales4(const u32x2& v) {
     const f16x2 a = bitcast<f16x2>(v[0]);
     const f16x2 b = bitcast<f16x2>(v[1]);
     f32x4 r = {(float)a[0], (float)a[1], (float)b[0], (float)b[1]};
+    return r;
+}
+
+// value of lane (4 * (lane / 4) + T) for every lane of the quad
+template <int T>
+__device__ inline u32x2 quad_bcast(const u32x2& v) {
+    u32x2 r;
+    r[0] = (uint32_t)__builtin_amdgcn_mov_dpp((int)v[0], T * 0x55, 0xf, 0xf, true);
+    r[1] = (uint32_t)__builtin_amdgcn_mov_dpp((int)v[1], T * 0x55, 0xf, 0xf, true);
     return r;
 }
 
@@ -267,7 +279,7 @@ __device__ inline void skinny_block(const SkinnyStage<BITS, NT, PER_STEP, AU>& s
             }
         }
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) flush<ACT, BITS>(acc[nt], p[nt], scales4(sl.sc[0][nt]), psa[0]);
+        for (int nt = 0; nt < NT; ++nt) flush<ACT, BITS>(acc[nt], p[nt], scales4(sl.sc[nt]), psa[0]);
     } else {
 #pragma unroll
         for (int t = 0; t < STEPS; ++t) {
@@ -282,7 +294,12 @@ __device__ inline void skinny_block(const SkinnyStage<BITS, NT, PER_STEP, AU>& s
                 if (STEPS > 2 && t == 2) w = Dequant<ACT, BITS>::template run<2 % STEPS>(sl.wq[nt], magic);
                 if (STEPS > 2 && t == 3) w = Dequant<ACT, BITS>::template run<3 % STEPS>(sl.wq[nt], magic);
                 const f32x4 p = mfma16x16x32<ACT>(w, a, zero);
-                flush<ACT, BITS>(acc[nt], p, scales4(sl.sc[t % SkinnyStage<BITS, NT, PER_STEP, AU>::SROWS][nt]), psa[0]);
+                u32x2 sq;
+                if (t == 0) sq = quad_bcast<0>(sl.sc[nt]);
+                if (t == 1) sq = quad_bcast<1>(sl.sc[nt]);
+                if (STEPS > 2 && t == 2) sq = quad_bcast<2 % STEPS>(sl.sc[nt]);
+                if (STEPS > 2 && t == 3) sq = quad_bcast<3 % STEPS>(sl.sc[nt]);
+                flush<ACT, BITS>(acc[nt], p, scales4(sq), psa[0]);
             }
         }
     }
@@ -377,16 +394,16 @@ __global__ __launch_bounds__(MAXW * 64) void fq_gemm_skinny_kernel(
         kb = kb < KB ? kb : KB - 1;                      // tail super-block: idle workers re-read the last block
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) sl.wq[nt] = __builtin_nontemporal_load(wbase[nt] + (int64_t)kb * kb_stride + lane);
-#pragma unroll
-        for (int r = 0; r < Stage::SROWS; ++r) {
-            // scale row of 32-row step (kb * STEPS + r): an exact division by g / 32 done as a
-            // multiplication by its rounded-up reciprocal (valid while the step index < 2^32 / (g/32))
-            const uint32_t step = (uint32_t)kb * STEPS + (PER_STEP ? r : 0);
+        {
+            // scale row of a 32-row k-step: an exact division by g / 32 done as a multiplication by
+            // its rounded-up reciprocal (valid while the step index < 2^32 / (g/32)).  PER_STEP: the
+            // lane fetches the row of step (lane % STEPS) of the k-block.
+            const uint32_t step = (uint32_t)kb * STEPS + (PER_STEP ? (uint32_t)(lane & (STEPS - 1)) : 0u);
             const uint32_t row = g32 == 1 ? step : __umulhi(step, g32_recip);
             const int64_t srow = (int64_t)row * N;
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
-                sl.sc[r][nt] = *reinterpret_cast<const u32x2*>(sbase[nt] + srow + s_off);
+                sl.sc[nt] = *reinterpret_cast<const u32x2*>(sbase[nt] + srow + s_off);
         }
         load_act(sl.areg, it + 1);
     };

@@ -16,4 +16,5 @@ from .fq_oracle import (  # noqa: F401
     gemm_ref_grouped,
     choose_group,
     bits_per_weight,
+    quant_error,
 )

@@ -14,6 +14,10 @@ What is defined here, and the passage of the paper each part follows:
                     compute (section 4.1, "GPU kernel implementations"):
                     C = A . dequant(W), evaluated in fp64.
 * ``choose_group``  the adaptive fine-grained heuristic of section 3.3.
+* ``quant_error``   the quantisation error the paper plots against the group
+                    size (section 3.2, figure 2a: mean squared error between
+                    the weights and their quantise-dequantise round trip):
+                    sum and maximum of (w - q*s)^2 / |w - q*s| in fp64.
 
 Readings taken where the paper is silent or ambiguous (each one is listed in
 the design notes of the repository as well):
@@ -48,7 +52,10 @@ codes, the s/2 reconstruction bound, code range, g = K against an
 independently written per-column quantiser, sign symmetry, power-of-two
 equivariance, child-scale <= parent-scale, the footprint closed form against
 the paper's Table 5, brute-force dot products, one-hot and all-ones GEMM
-special cases, and constructed matrices with a known heuristic answer.
+special cases, and constructed matrices with a known heuristic answer; for ``quant_error``:
+a hand-computed column, the zero error of exactly representable weights, the
+s/2 bound and the (sum of s^2)/12-per-weight expectation on uniformly spread
+weights.
 """
 from __future__ import annotations
 
@@ -65,6 +72,7 @@ __all__ = [
     "gemm_ref_grouped",
     "choose_group",
     "bits_per_weight",
+    "quant_error",
 ]
 
 
@@ -237,3 +245,19 @@ def bits_per_weight(bits: int, group_size: int) -> float:
     Appendix B (half-precision scales); Table 5's footprints obey it.
     """
     return bits + 16.0 / group_size
+
+
+def quant_error(W: np.ndarray, q: np.ndarray, s: np.ndarray):
+    """Sum of squared errors and largest absolute error of the round trip.
+
+    Section 3.2 measures quantisation quality as the mean squared error
+    between a weight matrix and its dequantised codes (the MSE axis of figure
+    2a); Appendix A defines the dequantised value as Q x s.  Everything is
+    exact in fp64 up to the final additions: w is binary16, q an integer of at
+    most 8 bits and s binary16, so q*s and w - q*s are exact.
+
+    Returns ``(sse, max_abs)``; the mean squared error is ``sse / W.size``.
+    """
+    W = np.asarray(W)
+    err = W.astype(np.float64) - dequantize(q, s)
+    return float(np.sum(err * err)), float(np.max(np.abs(err))) if err.size else 0.0

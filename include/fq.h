@@ -107,6 +107,25 @@ int fq_choose_group(const void* W_f16, int64_t K, int64_t N, int g_start, int g_
                     int* g_out, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * fq_quant_error -- the quantisation error that section 3.2 studies as a function of the
+ * group size (figure 2a: mean squared error between a weight matrix and its dequantised
+ * codes, the dequantised value being q * s as in Appendix A):
+ *   sse = sum over all (k, n) of (W[k, n] - q[k, n] * s[k / g, n])^2,   max_abs = max |...|,
+ * evaluated in binary64 (every difference is exact; only the additions round) in a fixed
+ * order, so the result is deterministic.  The mean squared error is sse / (K * N).
+ *
+ *   W_f16, codes, scales_f16  in   as given to / written by fq_quantize for (K, N, bits, group_size)
+ *   sse_out, max_abs_out      out  HOST pointers
+ *   workspace                      device scratch, >= fq_quant_error_workspace_bytes(K, N) bytes
+ * The call enqueues its kernels on `stream`, then SYNCHRONISES that stream to read the two
+ * numbers back.  Errors: as fq_quantize, plus FQ_ERR_WORKSPACE.
+ */
+size_t fq_quant_error_workspace_bytes(int64_t K, int64_t N);
+int fq_quant_error(const void* W_f16, int64_t K, int64_t N, int bits, int group_size, const void* codes,
+                   const void* scales_f16, double* sse_out, double* max_abs_out, void* workspace,
+                   size_t workspace_bytes, void* stream);
+
+/*
  * fq_gemm -- the fused dequantise-and-multiply product of section 4.1 ("GPU kernel
  * implementations"):  C[m, n] = sum_k A[m, k] * (q[k, n] * s[k / g, n]),
  * accumulated in binary32, written in the activation's data type.
@@ -135,6 +154,10 @@ int fq_gemm(const void* A, int act_dtype, int64_t M, int64_t N, int64_t K, const
  *   scales_f16    in  E scale matrices back to back (fq_scales_bytes() apart)
  *   A, C              [offsets[E], K] and [offsets[E], N]
  * E <= 256.
+ * Experts are cut into row tiles of up to three sizes and each size is one kernel; these
+ * independent kernels run on `stream` and on two streams the library creates (once per
+ * device, default priority, never destroyed), forked from and joined back to `stream` with
+ * events, so the call still behaves as one asynchronous operation on `stream`.
  */
 int fq_gemm_grouped(const void* A, int act_dtype, const int32_t* offsets_host, int E, int64_t N,
                     int64_t K, const void* codes, const void* scales_f16, int bits, int group_size,

@@ -117,6 +117,28 @@ int fq_choose_group(const void* W_f16, int64_t K, int64_t N, int g_start, int g_
     return FQ_OK;
 }
 
+size_t fq_quant_error_workspace_bytes(int64_t K, int64_t N) {
+    if (K <= 0 || N <= 0) return 0;
+    return (size_t)(16 + 16 * fq_quant_error_blocks(K, N));
+}
+
+int fq_quant_error(const void* W_f16, int64_t K, int64_t N, int bits, int group_size, const void* codes,
+                   const void* scales_f16, double* sse_out, double* max_abs_out, void* workspace,
+                   size_t workspace_bytes, void* stream) {
+    if (!W_f16 || !codes || !scales_f16 || !sse_out || !max_abs_out) return FQ_ERR_INVALID_ARG;
+    int g = 0;
+    const int st = check_shape(K, N, bits, group_size, &g);
+    if (st != FQ_OK) return st;
+    if (!workspace || workspace_bytes < fq_quant_error_workspace_bytes(K, N)) return FQ_ERR_WORKSPACE;
+    double out[2] = {0.0, 0.0};
+    const int rc = fq_launch_quant_error(W_f16, K, N, bits, g, codes, scales_f16, out, workspace,
+                                         (hipStream_t)stream);
+    if (rc != FQ_OK) return rc;
+    *sse_out = out[0];
+    *max_abs_out = out[1];
+    return FQ_OK;
+}
+
 int fq_gemm(const void* A, int act_dtype, int64_t M, int64_t N, int64_t K, const void* codes,
             const void* scales_f16, int bits, int group_size, void* C, void* workspace,
             size_t workspace_bytes, void* stream) {

@@ -12,6 +12,9 @@
 int fq_launch_quantize(const void* W, int64_t K, int64_t N, int bits, int g, void* codes, void* scales,
                        hipStream_t stream);
 int fq_launch_unpack(const void* codes, int64_t K, int64_t N, int bits, int8_t* q, hipStream_t stream);
+int64_t fq_quant_error_blocks(int64_t K, int64_t N);
+int fq_launch_quant_error(const void* W, int64_t K, int64_t N, int bits, int g, const void* codes,
+                          const void* scales, double* out_host2, void* workspace, hipStream_t stream);
 int fq_launch_choose_group(const void* W, int64_t K, int64_t N, int g_top, int levels, float alpha,
                            int* flags_host, void* workspace, hipStream_t stream);
 

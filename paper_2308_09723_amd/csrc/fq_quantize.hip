@@ -202,6 +202,85 @@ __global__ void fq_zero_ints_kernel(int* p, int n) {
     if (i < n) p[i] = 0;
 }
 
+// ---------------------------------------------------------------------------------
+// Round-trip error (section 3.2, figure 2a: mean squared error between the weights and their
+// dequantised codes, Appendix A: dequantised value = q * s).  binary64 throughout: w, q * s and
+// their difference are exact, the squares are rounded once, and the sums are taken in a fixed
+// order (thread strip -> tree over the block -> one block over the per-block partials), so the
+// result is deterministic.  part[0 .. nblk) holds the sums, part[nblk .. 2 nblk) the maxima.
+// ---------------------------------------------------------------------------------
+#define FQ_QE_ROWS 64
+template <int BITS>
+__global__ __launch_bounds__(256) void fq_quant_error_kernel(const uint16_t* __restrict__ W,
+                                                             const uint32_t* __restrict__ codes,
+                                                             const uint16_t* __restrict__ scales, int64_t K,
+                                                             int64_t N, int g, double* __restrict__ part,
+                                                             int64_t nblk) {
+    __shared__ double sh_s[256];
+    __shared__ double sh_m[256];
+    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t k0 = (int64_t)blockIdx.y * FQ_QE_ROWS;
+    double sse = 0.0, mx = 0.0;
+    if (n < N) {
+        for (int64_t k = k0; k < k0 + FQ_QE_ROWS && k < K; ++k) {
+            const fq_pos p = fq_locate(k, n, N, BITS);
+            int q;
+            if (BITS == 4) {
+                const uint32_t w = codes[p.rec * 4 + p.t];
+                q = (int)((w >> (4 * fq_nibble_slot(p.e))) & 0xfu) - 8;
+            } else {
+                const uint32_t w = codes[p.rec * 4 + 2 * p.t + (p.e >> 2)];
+                q = (int)((w >> (8 * (p.e & 3))) & 0xffu) - 128;
+            }
+            const double wv = (double)half_bits_to_float(W[k * N + n]);
+            const double sv = (double)half_bits_to_float(scales[(k / g) * N + n]);
+            const double e = wv - (double)q * sv;
+            sse += e * e;
+            mx = fmax(mx, fabs(e));
+        }
+    }
+    sh_s[threadIdx.x] = sse;
+    sh_m[threadIdx.x] = mx;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) {
+            sh_s[threadIdx.x] += sh_s[threadIdx.x + w];
+            sh_m[threadIdx.x] = fmax(sh_m[threadIdx.x], sh_m[threadIdx.x + w]);
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        const int64_t b = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
+        part[b] = sh_s[0];
+        part[nblk + b] = sh_m[0];
+    }
+}
+
+__global__ __launch_bounds__(256) void fq_quant_error_final_kernel(const double* __restrict__ part, int64_t nblk,
+                                                                   double* __restrict__ out) {
+    __shared__ double sh_s[256];
+    __shared__ double sh_m[256];
+    double sse = 0.0, mx = 0.0;
+    for (int64_t i = threadIdx.x; i < nblk; i += 256) {
+        sse += part[i];
+        mx = fmax(mx, part[nblk + i]);
+    }
+    sh_s[threadIdx.x] = sse;
+    sh_m[threadIdx.x] = mx;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+        if ((int)threadIdx.x < w) {
+            sh_s[threadIdx.x] += sh_s[threadIdx.x + w];
+            sh_m[threadIdx.x] = fmax(sh_m[threadIdx.x], sh_m[threadIdx.x + w]);
+        }
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) {
+        out[0] = sh_s[0];
+        out[1] = sh_m[0];
+    }
+}
+
 }  // namespace
 
 // ----------------------------------------------------------------------------- launchers
@@ -259,6 +338,31 @@ int fq_launch_choose_group(const void* W, int64_t K, int64_t N, int g_top, int l
     }
     if (hipGetLastError() != hipSuccess) return FQ_ERR_HIP;
     if (hipMemcpyAsync(flags_host, flags, sizeof(int) * 64, hipMemcpyDeviceToHost, stream) != hipSuccess)
+        return FQ_ERR_HIP;
+    if (hipStreamSynchronize(stream) != hipSuccess) return FQ_ERR_HIP;
+    return FQ_OK;
+}
+
+int64_t fq_quant_error_blocks(int64_t K, int64_t N) {
+    return ((N + 255) / 256) * ((K + FQ_QE_ROWS - 1) / FQ_QE_ROWS);
+}
+
+int fq_launch_quant_error(const void* W, int64_t K, int64_t N, int bits, int g, const void* codes,
+                          const void* scales, double* out_host2, void* workspace, hipStream_t stream) {
+    // workspace: [out: 2 doubles][partials: 2 * nblk doubles]
+    double* out = (double*)workspace;
+    double* part = out + 2;
+    const int64_t nblk = fq_quant_error_blocks(K, N);
+    dim3 grid((unsigned)((N + 255) / 256), (unsigned)((K + FQ_QE_ROWS - 1) / FQ_QE_ROWS));
+    if (bits == 4)
+        hipLaunchKernelGGL(fq_quant_error_kernel<4>, grid, dim3(256), 0, stream, (const uint16_t*)W,
+                           (const uint32_t*)codes, (const uint16_t*)scales, K, N, g, part, nblk);
+    else
+        hipLaunchKernelGGL(fq_quant_error_kernel<8>, grid, dim3(256), 0, stream, (const uint16_t*)W,
+                           (const uint32_t*)codes, (const uint16_t*)scales, K, N, g, part, nblk);
+    hipLaunchKernelGGL(fq_quant_error_final_kernel, dim3(1), dim3(256), 0, stream, (const double*)part, nblk, out);
+    if (hipGetLastError() != hipSuccess) return FQ_ERR_HIP;
+    if (hipMemcpyAsync(out_host2, out, sizeof(double) * 2, hipMemcpyDeviceToHost, stream) != hipSuccess)
         return FQ_ERR_HIP;
     if (hipStreamSynchronize(stream) != hipSuccess) return FQ_ERR_HIP;
     return FQ_OK;

@@ -51,6 +51,9 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "fq_quantize": (i32, [vp, i64, i64, i32, i32, vp, vp, vp]),
         "fq_unpack": (i32, [vp, i64, i64, i32, vp, vp]),
         "fq_choose_group": (i32, [vp, i64, i64, i32, i32, f32, ctypes.POINTER(ctypes.c_int), vp, sz, vp]),
+        "fq_quant_error_workspace_bytes": (sz, [i64, i64]),
+        "fq_quant_error": (i32, [vp, i64, i64, i32, i32, vp, vp, ctypes.POINTER(ctypes.c_double),
+                                 ctypes.POINTER(ctypes.c_double), vp, sz, vp]),
         "fq_gemm": (i32, [vp, i32, i64, i64, i64, vp, vp, i32, i32, vp, vp, sz, vp]),
         "fq_gemm_grouped": (i32, [vp, i32, ctypes.POINTER(ctypes.c_int32), i32, i64, i64, vp, vp, i32, i32,
                                   vp, vp, sz, vp]),
@@ -70,6 +73,7 @@ EXPORTED = [
     "fq_codes_bytes", "fq_scales_bytes", "fq_gemm_workspace_bytes", "fq_gemm_grouped_workspace_bytes",
     "fq_choose_group_workspace_bytes", "fq_quantize", "fq_unpack", "fq_choose_group", "fq_gemm",
     "fq_gemm_grouped", "fq_gemm_describe", "fq_status_string", "fq_version",
+    "fq_quant_error_workspace_bytes", "fq_quant_error",
 ]
 
 
@@ -119,6 +123,18 @@ def choose_group_raw(W_ptr, K, N, g_start, g_min, alpha, ws_ptr, ws_bytes, strea
     st = int(load().fq_choose_group(W_ptr, K, N, g_start, g_min, alpha, ctypes.byref(out), ws_ptr, ws_bytes,
                                     stream))
     return st, out.value
+
+
+def quant_error_workspace_bytes(K, N):
+    return int(load().fq_quant_error_workspace_bytes(K, N))
+
+
+def quant_error_raw(W_ptr, K, N, bits, group_size, codes_ptr, scales_ptr, ws_ptr, ws_bytes, stream=0):
+    sse = ctypes.c_double(-1.0)
+    mx = ctypes.c_double(-1.0)
+    st = int(load().fq_quant_error(W_ptr, K, N, bits, group_size, codes_ptr, scales_ptr, ctypes.byref(sse),
+                                   ctypes.byref(mx), ws_ptr, ws_bytes, stream))
+    return st, sse.value, mx.value
 
 
 def gemm_raw(A_ptr, act_dtype, M, N, K, codes_ptr, scales_ptr, bits, group_size, C_ptr, ws_ptr, ws_bytes,
@@ -192,6 +208,20 @@ def choose_group(W, g_start, g_min, alpha):
     st, g = choose_group_raw(W.data_ptr(), K, N, g_start, g_min, float(alpha), ws.data_ptr(), ws_bytes, _stream())
     _check(st, "fq_choose_group")
     return g
+
+
+def quant_error(W, codes, scales, bits, group_size):
+    """Round-trip error of a quantised matrix: (sum of squared errors, largest absolute error)."""
+    import torch
+
+    assert W.is_cuda and W.dtype == torch.float16 and W.is_contiguous()
+    K, N = W.shape
+    ws_bytes = quant_error_workspace_bytes(K, N)
+    ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=W.device)
+    st, sse, mx = quant_error_raw(W.data_ptr(), K, N, bits, group_size, codes.data_ptr(), scales.data_ptr(),
+                                  ws.data_ptr(), ws_bytes, _stream())
+    _check(st, "fq_quant_error")
+    return sse, mx
 
 
 def gemm(A, codes, scales, bits, group_size, out=None, workspace=None):

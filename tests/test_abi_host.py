@@ -106,3 +106,25 @@ def test_grouped_and_heuristic_argument_checks():
     assert st == fq.FQ_OK and g == 64                     # nothing to halve: answered on the host
     assert fq.status_string(fq.FQ_ERR_WORKSPACE) == "FQ_ERR_WORKSPACE"
     assert fq.status_string(99) == "FQ_ERR_UNKNOWN"
+
+
+def test_quant_error_argument_checks():
+    """Validation precedes every launch, so these calls never touch a GPU."""
+    assert fq.quant_error_workspace_bytes(0, 16) == 0
+    assert fq.quant_error_workspace_bytes(1024, 1024) == 16 + 16 * 4 * 16      # 4 column x 16 row blocks
+    ok = dict(W=16, K=1024, N=1024, bits=4, g=128, codes=16, scales=16, ws=16, wsb=1 << 20)
+
+    def call(**kw):
+        a = dict(ok)
+        a.update(kw)
+        return fq.quant_error_raw(a["W"] or None, a["K"], a["N"], a["bits"], a["g"], a["codes"] or None,
+                                  a["scales"] or None, a["ws"] or None, a["wsb"])[0]
+
+    assert call(W=0) == fq.FQ_ERR_INVALID_ARG
+    assert call(codes=0) == fq.FQ_ERR_INVALID_ARG
+    assert call(scales=0) == fq.FQ_ERR_INVALID_ARG
+    assert call(bits=3) == fq.FQ_ERR_INVALID_ARG
+    assert call(g=96) == fq.FQ_ERR_INVALID_ARG
+    assert call(N=1032) == fq.FQ_ERR_UNSUPPORTED
+    assert call(ws=0) == fq.FQ_ERR_WORKSPACE
+    assert call(wsb=64) == fq.FQ_ERR_WORKSPACE

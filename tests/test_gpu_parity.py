@@ -239,6 +239,38 @@ def test_choose_group_matches_oracle():
         assert got == want, (gs, gm, alpha, got, want)
 
 
+# ------------------------------------------------------------------ round-trip error (section 3.2)
+@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("K,N,g", [(384, 80, 32), (512, 272, 64), (1024, 16, 0), (256, 1040, 256), (768, 304, 128)])
+def test_quant_error_matches_oracle(bits, K, N, g):
+    _say(f"quant error int{bits} K={K} N={N} g={g}")
+    fq = _fq()
+    torch = torch_mod()
+    W = workloads.weights_gaussian(K, N, 90 + K + N, outlier_prob=2e-3)
+    codes, scales, q_ref, s_ref = assert_quantizer_parity(W, bits, g)
+    sse, mx = fq.quant_error(torch.from_numpy(W).cuda(), codes, scales, bits, g)
+    sse_ref, mx_ref = oracle.quant_error(W, q_ref, s_ref)
+    assert mx == mx_ref                                   # one exact difference: bit-exact
+    # both sides add the same exactly rounded squares, in different orders: K * N <= 3e5 terms of
+    # relative rounding 2^-53 each
+    assert abs(sse - sse_ref) <= 1e-11 * sse_ref, (sse, sse_ref)
+    sse2, mx2 = fq.quant_error(torch.from_numpy(W).cuda(), codes, scales, bits, g)
+    assert (sse2, mx2) == (sse, mx)                       # deterministic
+
+
+def test_quant_error_heavy_tail_and_zero_matrix():
+    fq = _fq()
+    torch = torch_mod()
+    W = workloads.weights_heavy_tail(512, 96, seed=17)
+    codes, scales, q_ref, s_ref = assert_quantizer_parity(W, 4, 64)
+    sse, mx = fq.quant_error(torch.from_numpy(W).cuda(), codes, scales, 4, 64)
+    sse_ref, mx_ref = oracle.quant_error(W, q_ref, s_ref)
+    assert mx == mx_ref and abs(sse - sse_ref) <= 1e-11 * sse_ref
+    Z = np.zeros((256, 32), dtype=np.float16)
+    codes, scales, _, _ = assert_quantizer_parity(Z, 8, 128)
+    assert fq.quant_error(torch.from_numpy(Z).cuda(), codes, scales, 8, 128) == (0.0, 0.0)
+
+
 # ------------------------------------------------------------------ grouped (mixture of experts)
 @pytest.mark.parametrize("dtype,bits,g", [("f16", 4, 64), ("bf16", 4, 64), ("f16", 8, 0)])
 def test_grouped_gemm_small(dtype, bits, g):

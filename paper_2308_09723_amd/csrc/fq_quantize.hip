@@ -17,6 +17,16 @@ __device__ inline float half_bits_to_float(uint16_t b) {
     return __half2float(__ushort_as_half(b));
 }
 
+// Appendix A's scale for a group whose abs-max has the binary16 bit pattern m:
+// the smallest binary16 s with L * s >= 2 m (L = 2^bits - 1), as a bit pattern.
+__device__ inline uint32_t scale_bits_from_absmax_bits(uint32_t m, float L) {
+    const float two_m = 2.0f * half_bits_to_float((uint16_t)m);
+    const float t32 = __fdiv_rn(two_m, L);
+    uint32_t tb = __half_as_ushort(__float2half_rn(t32));
+    if (L * half_bits_to_float((uint16_t)tb) < two_m) tb += 1;   // next binary16 up
+    return tb;
+}
+
 // ---------------------------------------------------------------------------------
 // Scales: abs-max over each block of g rows, then the smallest binary16 s with
 // L * s >= 2 m.  Block = 64 x 4 threads: x covers 128 columns (two per thread), the four
@@ -49,14 +59,28 @@ __global__ __launch_bounds__(256) void fq_scales_kernel(const uint16_t* __restri
                 const uint32_t v = (red[y][tx] >> (16 * c)) & 0xffffu;
                 m = v > m ? v : m;
             }
-            const float two_m = 2.0f * half_bits_to_float((uint16_t)m);
-            const float t32 = __fdiv_rn(two_m, L);
-            uint32_t tb = __half_as_ushort(__float2half_rn(t32));
-            if (L * half_bits_to_float((uint16_t)tb) < two_m) tb += 1;   // next binary16 up
-            out |= tb << (16 * c);
+            out |= scale_bits_from_absmax_bits(m, L) << (16 * c);
         }
         *reinterpret_cast<uint32_t*>(scales + grp * N + n) = out;
     }
+}
+
+// Coarse groups (few groups per column): the abs-max of 128-row blocks is taken first by
+// fq_fine_absmax_kernel, with one block of threads per (128 rows x 128 columns), and this
+// kernel folds the g / 128 block maxima of each group into its scale.  One kernel walking a
+// whole 12288-row column per thread slice leaves most of the GPU idle.
+__global__ __launch_bounds__(256) void fq_scales_fold_kernel(const uint16_t* __restrict__ fine, int64_t N,
+                                                             int per_group, float L,
+                                                             uint16_t* __restrict__ scales) {
+    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    const int64_t grp = blockIdx.y;
+    uint32_t m = 0;
+    for (int i = 0; i < per_group; ++i) {
+        const uint32_t v = fine[(grp * per_group + i) * N + n];
+        m = v > m ? v : m;
+    }
+    scales[grp * N + n] = (uint16_t)scale_bits_from_absmax_bits(m, L);
 }
 
 // ---------------------------------------------------------------------------------
@@ -287,7 +311,17 @@ __global__ __launch_bounds__(256) void fq_quant_error_final_kernel(const double*
 int fq_launch_quantize(const void* W, int64_t K, int64_t N, int bits, int g, void* codes, void* scales,
                        hipStream_t stream) {
     const float L = (float)((1 << bits) - 1);
-    {
+    if (g >= 1024 && g % 128 == 0) {
+        // two stages; the block maxima (K / 128 x N binary16 = K * N / 64 bytes) are parked in the
+        // code buffer, which is only written by the encoding pass below
+        uint16_t* fine = (uint16_t*)codes;
+        dim3 block(64, 4);
+        dim3 grid((unsigned)((N + 127) / 128), (unsigned)(K / 128));
+        hipLaunchKernelGGL(fq_fine_absmax_kernel, grid, block, 0, stream, (const uint16_t*)W, N, 128, fine);
+        dim3 grid2((unsigned)((N + 255) / 256), (unsigned)(K / g));
+        hipLaunchKernelGGL(fq_scales_fold_kernel, grid2, dim3(256), 0, stream, (const uint16_t*)fine, N, g / 128, L,
+                           (uint16_t*)scales);
+    } else {
         dim3 block(64, 4);
         dim3 grid((unsigned)((N + 127) / 128), (unsigned)(K / g));
         hipLaunchKernelGGL(fq_scales_kernel, grid, block, 0, stream, (const uint16_t*)W, K, N, g, L,

@@ -248,6 +248,7 @@ def main():
         torch.cuda.empty_cache()
         out["extra_moe"] = moe_section(torch, fq, workloads)
         out["extra_stress"] = stress_section(torch, fq, workloads)
+        out["extra_quantize"] = quantize_section(torch, fq, workloads)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
@@ -340,6 +341,36 @@ def moe_section(torch, fq, workloads):
                     "experts_hit": hit, "weight_bytes": wbytes}
         del codes, scales, A, C
         torch.cuda.empty_cache()
+    return res
+
+
+def quantize_section(torch, fq, workloads):
+    """The offline steps on the FC1-shaped matrix (1.21 GB of fp16 weights): fq_quantize (scales, codes,
+    packing), fq_choose_group and fq_quant_error.  Rates count the weights read once plus the outputs."""
+    K, N = workloads.OPT175B_LAYERS["fc1"]
+    W = make_weight(torch, K, N, 321)
+    stream = torch.cuda.current_stream().cuda_stream
+    res = {}
+    for bits, g in ((4, 128), (4, 32), (8, 0)):
+        codes = torch.empty(fq.codes_bytes(K, N, bits), dtype=torch.uint8, device="cuda")
+        scales = torch.empty(fq.scales_bytes(K, N, g) // 2, dtype=torch.float16, device="cuda")
+
+        def run():
+            st = fq.quantize_raw(W.data_ptr(), K, N, bits, g, codes.data_ptr(), scales.data_ptr(), stream)
+            if st != fq.FQ_OK:
+                raise fq.FqError(st, "fq_quantize")
+        ms = _timed(torch, run, settle=0.1, reps=10)
+        nbytes = K * N * 2 + codes.numel() + scales.numel() * 2
+        res[f"quantize_int{bits}_g{g or K}"] = {"ms": round(ms, 4), "TBps": round(nbytes / ms / 1e9, 3)}
+        if (bits, g) == (4, 128):
+            t0 = time.perf_counter()
+            sse, mx = fq.quant_error(W, codes, scales, bits, g)
+            res["quant_error_int4_g128"] = {"ms": round((time.perf_counter() - t0) * 1e3, 4), "mse": sse / (K * N),
+                                            "max_abs": mx}
+    fq.choose_group(W, 0, 32, 0.9)
+    t0 = time.perf_counter()
+    gsel = fq.choose_group(W, 0, 32, 0.9)
+    res["choose_group_alpha0.9"] = {"ms": round((time.perf_counter() - t0) * 1e3, 4), "group_size": gsel}
     return res
 
 

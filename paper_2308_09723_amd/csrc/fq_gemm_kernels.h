@@ -626,7 +626,8 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
     constexpr int KC = KBLK / 8;
     constexpr int BM = MT * 16;
     constexpr int UNITS = BM * KC;
-    // LDS layout of the activation tile, in 16-byte units: unit(kc, row) = kc * BM + (row ^ swz(kc)),
+    // LDS layout of the activation tile in the two-buffer form (the pipelined form has its own, below),
+    // in 16-byte units: unit(kc, row) = kc * BM + (row ^ swz(kc)),
     // swz(kc) = kc * (16 / KC) mod 16.  A fragment read (16 rows of one kc per 16 lanes) then covers
     // one aligned 256-byte span, and a staging write (the KC units of a row in neighbouring lanes)
     // spreads over all banks; a padded pitch keeps the writes conflict-free but halves the read rate.

@@ -54,7 +54,8 @@ size_t fq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits, int gr
     int g = 0;
     if (M <= 0 || check_shape(K, N, bits, group_size, &g) != FQ_OK) return 0;
     const fq_gemm_plan plan = fq_plan_gemm(M, N, K, bits, g);
-    return plan.splits > 1 ? (size_t)plan.splits * (size_t)M * (size_t)N * sizeof(float) : 0;
+    const int parts = plan.splits > 1 ? plan.splits : (plan.tail_tiles > 0 ? plan.tail_splits : 0);
+    return (size_t)parts * (size_t)M * (size_t)N * sizeof(float);
 }
 
 size_t fq_gemm_grouped_workspace_bytes(int64_t total_rows, int E, int64_t N, int64_t K, int bits,
@@ -189,8 +190,8 @@ int fq_gemm_describe(int64_t M, int64_t N, int64_t K, int bits, int group_size, 
         snprintf(buf, buf_bytes, "small-m variant=%d gp=%d kw=%d au=%d waves=%d splits=%d", p.variant, p.gp,
                  p.kw, p.au, p.waves, p.splits);
     else
-        snprintf(buf, buf_bytes, "tiled mt=%d waves=%d splits=%d kb_per_split=%d", p.mt, p.waves, p.splits,
-                 p.kb_per_split);
+        snprintf(buf, buf_bytes, "tiled mt=%d waves=%d splits=%d kb_per_split=%d tail=%dx%d", p.mt, p.waves, p.splits,
+                 p.kb_per_split, p.tail_tiles, p.tail_tiles > 0 ? p.tail_splits : 1);
     return FQ_OK;
 }
 

@@ -107,8 +107,12 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
         const double kscale = (double)kblk / 128.0;
         const int split_opts[6] = {1, 2, 3, 4, 6, 8};
         double best = 1e30;
+        p.tail_tiles = 0;
+        p.tail_splits = 1;
+        p.tail_kbs = 0;
         for (int waves = 8; waves >= 4; waves -= 4) {
             const int64_t nbn = (ntiles + waves * MMA_NT - 1) / (waves * MMA_NT);
+            const double u = (waves == 8 ? u8 : u4) * kscale;
             for (int si = 0; si < 6; ++si) {
                 int splits = split_opts[si];
                 if (splits > KB) break;
@@ -116,10 +120,10 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
                 splits = (KB + kbs - 1) / kbs;
                 const int64_t blocks = nbn * nbm * splits;
                 const int64_t per_cu = (blocks + 255) / 256;
-                double t = (double)per_cu * kbs * (waves == 8 ? u8 : u4) * kscale;
+                double t = (double)per_cu * kbs * u;
                 // two 128-row 4-wave blocks share a compute unit; an odd one left over runs alone
                 // and takes a little more than half the time of a pair
-                if (p.mt == 8 && waves == 4 && (per_cu & 1)) t += 0.13 * u4 * kbs * kscale;
+                if (p.mt == 8 && waves == 4 && (per_cu & 1)) t += 0.13 * u * kbs;
                 // fewer blocks than compute units: the idle ones also pull no weights
                 if (blocks < 256) t *= 256.0 / (double)blocks;
                 if (splits > 1) t += 2.0 * splits * (double)M * (double)N * 4.0 / 4e6 + 5.0;
@@ -128,6 +132,37 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
                     p.waves = waves;
                     p.splits = splits;
                     p.kb_per_split = kbs;
+                    p.tail_tiles = 0;
+                }
+            }
+            // No uniform split, but the tiles of the partly filled last round are split along K so
+            // that they occupy every block slot once more: the last round then lasts 1 / tail_splits
+            // of a full one, at the price of partial tiles for those tiles only.
+            const int64_t tiles = nbn * nbm;
+            const int64_t slots = 256 * (waves == 8 ? 1 : (p.mt == 2 ? 3 : 2));
+            const int64_t rem = tiles % slots;
+            if (tiles > slots && rem > 0) {
+                // at most 4 ways (8-way tails measured slower than the model says), and only if the
+                // split tiles then fill at least three quarters of the block slots
+                int ts = (int)(slots / rem);
+                if (ts > 4) ts = 4;
+                if (ts > KB) ts = KB;
+                if (ts >= 2 && rem * ts * 4 >= slots * 3) {
+                    const int tkbs = (KB + ts - 1) / ts;
+                    ts = (KB + tkbs - 1) / tkbs;
+                    const int64_t head = tiles - rem;
+                    double t = (double)(head / 256) * KB * u + (double)((rem * ts + 255) / 256) * tkbs * u;
+                    const double bm_bn = (double)bm * (double)(waves * MMA_NT * FQ_NTILE);
+                    t += 2.0 * ts * (double)rem * bm_bn * 4.0 / 4e6 + 5.0;
+                    if (ts >= 2 && t < best - 1e-9) {
+                        best = t;
+                        p.waves = waves;
+                        p.splits = 1;
+                        p.kb_per_split = KB;
+                        p.tail_tiles = (int)rem;
+                        p.tail_splits = ts;
+                        p.tail_kbs = tkbs;
+                    }
                 }
             }
         }

@@ -85,7 +85,9 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
         // instantiations below
         const int ring = plan.mt == 8 ? (plan.waves == 8 ? 2 : 0) : (plan.mt == 4 ? FQ_RING_MT4 : FQ_RING_MT2);
         const size_t lds = (size_t)(ring ? ring + 1 : 2) * (kblk / 8) * bm * 16;
-        dim3 grid((unsigned)((int64_t)nblocks_n * nblocks_m * plan.splits));
+        const int64_t tiles = (int64_t)nblocks_n * nblocks_m;
+        dim3 grid((unsigned)(plan.tail_tiles > 0 ? tiles - plan.tail_tiles + (int64_t)plan.tail_tiles * plan.tail_splits
+                                                 : tiles * plan.splits));
         fq_group_items none;
         none.count = 0;
 #define FQ_MMA_LAUNCH_SR(MT_, W_, PIPE_, SR_)                                                            \
@@ -103,7 +105,8 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
         hipLaunchKernelGGL(kern, grid, dim3(W_ * 64), lds, stream, (const uint16_t*)A,                  \
                            (const u32x4*)codes, (const uint16_t*)scales, (uint16_t*)C, partial, (int)M, \
                            (int)N, (int)K, g, plan.kb_per_split, plan.splits, nblocks_n, nblocks_m,     \
-                           (int64_t)0, (int64_t)0, none);                                               \
+                           (int64_t)0, (int64_t)0, none, plan.tail_tiles, plan.tail_splits,             \
+                           plan.tail_kbs);                                                              \
     } while (0)
 #define FQ_MMA_LAUNCH(MT_, W_, PIPE_)                                                                   \
     do {                                                                                                \
@@ -122,6 +125,15 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
         }
 #undef FQ_MMA_LAUNCH
 #undef FQ_MMA_LAUNCH_SR
+    }
+    if (plan.kind == 1 && plan.tail_tiles > 0) {
+        const int bm = plan.mt * 16;
+        const int bn_cols = plan.waves * MMA_NT * FQ_NTILE;
+        const int nblocks_n = (ntiles + plan.waves * MMA_NT - 1) / (plan.waves * MMA_NT);
+        const int nblocks_m = (int)((M + bm - 1) / bm);
+        hipLaunchKernelGGL(fq_reduce_tail_kernel<ACT>, dim3((unsigned)plan.tail_tiles), dim3(256), 0, stream,
+                           (const float*)partial, plan.tail_splits, (int)M, (int)N, nblocks_n, nblocks_m,
+                           nblocks_n * nblocks_m - plan.tail_tiles, bm, bn_cols, (uint16_t*)C);
     }
     if (plan.splits > 1) {
         const int64_t MN = M * N;
@@ -172,7 +184,7 @@ int launch_grouped_typed(const void* A, const int32_t* offsets, int E, int64_t N
         hipLaunchKernelGGL(kern, grid, dim3(W_ * 64), lds, stream, (const uint16_t*)A,                  \
                            (const u32x4*)codes, (const uint16_t*)scales, (uint16_t*)C, (float*)nullptr, \
                            0, (int)N, (int)K, g, KB, 1, nblocks_n, items.count, codes_stride16,         \
-                           scales_stride, items);                                                       \
+                           scales_stride, items, 0, 1, 0);                                              \
     } while (0)
 #define FQ_GROUPED_LAUNCH(MT_, W_, PIPE_)                                                               \
     do {                                                                                                \

@@ -608,6 +608,42 @@ __device__ inline uint32_t scale_operand(uint16_t h) {
     }
 }
 
+// Logical tile -> (column block, row block).  Logical tiles walk panels of PW column blocks x all
+// row blocks, so that the blocks resident on an XCD at one time share activation rows and weight
+// columns in its L2.
+__device__ inline void fq_tile_of(int L, int nblocks_n, int nblocks_m, int& bn, int& bm) {
+    const int PW = nblocks_n < 4 ? nblocks_n : 4;
+    const int panel = L / (PW * nblocks_m);
+    const int within = L - panel * PW * nblocks_m;
+    const int pw_here = min(PW, nblocks_n - panel * PW);
+    bm = within / pw_here;
+    bn = panel * PW + within - bm * pw_here;
+}
+
+// Sum of the partial tiles of the last `tail_tiles` logical tiles (fixed order), one block per tile.
+template <int ACT>
+__global__ __launch_bounds__(256) void fq_reduce_tail_kernel(const float* __restrict__ partial, int tail_splits,
+                                                             int M, int N, int nblocks_n, int nblocks_m,
+                                                             int head, int bm_rows, int bn_cols,
+                                                             uint16_t* __restrict__ C) {
+    int bn, bm;
+    fq_tile_of(head + blockIdx.x, nblocks_n, nblocks_m, bn, bm);
+    const int row0 = bm * bm_rows, col0 = bn * bn_cols;
+    const int rows = min(bm_rows, M - row0), cols = min(bn_cols, N - col0);
+    const int quads = cols / 4;                      // N is a multiple of 16
+    const int64_t MN = (int64_t)M * N;
+    for (int i = threadIdx.x; i < rows * quads; i += 256) {
+        const int r = i / quads, q = i - r * quads;
+        const int64_t at = (int64_t)(row0 + r) * N + col0 + q * 4;
+        f32x4 v = *reinterpret_cast<const f32x4*>(partial + at);
+        for (int s = 1; s < tail_splits; ++s) {
+            const f32x4 o = *reinterpret_cast<const f32x4*>(partial + (int64_t)s * MN + at);
+            v[0] += o[0]; v[1] += o[1]; v[2] += o[2]; v[3] += o[3];
+        }
+        *reinterpret_cast<u32x2*>(C + at) = pack4<ACT>(v);
+    }
+}
+
 // s_waitcnt vmcnt(N) only (the other counters left alone); gfx9 encoding: vmcnt in bits 3:0 and 15:14
 template <int N>
 __device__ inline void wait_vmcnt() {
@@ -620,7 +656,7 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
     const uint16_t* __restrict__ A, const u32x4* __restrict__ codes, const uint16_t* __restrict__ scales,
     uint16_t* __restrict__ C, float* __restrict__ partial, int M, int N, int K, int g, int kb_per_split,
     int splits, int nblocks_n, int nblocks_m, int64_t codes_stride16, int64_t scales_stride,
-    fq_group_items items) {
+    fq_group_items items, int tail_tiles, int tail_splits, int tail_kbs) {
     constexpr int KBLK = BITS == 4 ? 128 : 64;
     constexpr int STEPS = KBLK / FQ_KSTEP;
     constexpr int KC = KBLK / 8;
@@ -652,23 +688,42 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
     // each with its own L2; the ids an XCD receives are mapped to one contiguous run of logical
     // tiles, and logical tiles walk panels of PW n-blocks x all m-blocks, so that the blocks
     // resident on an XCD at one time share activation rows and weight columns in its L2.
-    int bn, bm_idx, split;
+    // With tail_tiles > 0 (and splits == 1) the first tiles run over all of K and write C; each of
+    // the last tail_tiles tiles is shared by tail_splits blocks that write binary32 partial tiles
+    // (they take the place of the partly filled last round of blocks).
+    int bn, bm_idx, split, kb0, kb1;
+    bool partial_out;
     {
-        const int per_split = nblocks_n * nblocks_m;
+        const int tiles = nblocks_n * nblocks_m;
         int bid = blockIdx.x;
-        split = bid / per_split;
-        bid -= split * per_split;
-        int L = bid;
-        if ((per_split & 7) == 0) L = (bid & 7) * (per_split >> 3) + (bid >> 3);
-        const int PW = nblocks_n < 4 ? nblocks_n : 4;
-        const int panel = L / (PW * nblocks_m);
-        const int within = L - panel * PW * nblocks_m;
-        const int pw_here = min(PW, nblocks_n - panel * PW);
-        bm_idx = within / pw_here;
-        bn = panel * PW + within - bm_idx * pw_here;
+        int L;
+        auto spread = [](int b, int count) {   // ids an XCD receives -> one contiguous run of logical tiles
+            return (count & 7) == 0 ? (b & 7) * (count >> 3) + (b >> 3) : b;
+        };
+        const int head = tiles - tail_tiles;
+        if (tail_tiles == 0) {
+            split = bid / tiles;
+            bid -= split * tiles;
+            L = spread(bid, tiles);
+            kb0 = split * kb_per_split;
+            kb1 = min(KB, kb0 + kb_per_split);
+            partial_out = splits > 1;
+        } else if (bid < head) {
+            split = 0;
+            L = spread(bid, head);
+            kb0 = 0;
+            kb1 = KB;
+            partial_out = false;
+        } else {
+            const int r = bid - head;
+            L = head + r / tail_splits;
+            split = r - (r / tail_splits) * tail_splits;
+            kb0 = split * tail_kbs;
+            kb1 = min(KB, kb0 + tail_kbs);
+            partial_out = true;
+        }
+        fq_tile_of(L, nblocks_n, nblocks_m, bn, bm_idx);
     }
-    const int kb0 = split * kb_per_split;
-    const int kb1 = min(KB, kb0 + kb_per_split);
 
     int64_t row0;
     int rows;
@@ -984,7 +1039,7 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
         for (int nt = 0; nt < NT; ++nt) {
             if (!tvalid[nt]) continue;
             const int64_t n = (int64_t)(tile0 + nt) * FQ_NTILE + j * 4;
-            if (splits == 1) {
+            if (!partial_out) {
                 *reinterpret_cast<u32x2*>(C + (row0 + row) * N + n) = pack4<ACT>(acc[mt][nt]);
             } else {
                 *reinterpret_cast<f32x4*>(partial + ((int64_t)split * M + row0 + row) * N + n) = acc[mt][nt];

@@ -28,6 +28,9 @@ struct fq_gemm_plan {
     int au;        // small-M kernel: activation units a lane stages per super-block (1, 2 or 4)
     int splits;    // split-K factor (>= 1)
     int kb_per_split;   // k-blocks per grid split (tiled) or per wave (small-M)
+    // tiled kernel, splits == 1 only: the last `tail_tiles` output tiles (the partly filled last round
+    // of blocks) are split `tail_splits` ways along K so that they fill the idle compute units
+    int tail_tiles, tail_splits, tail_kbs;
 };
 fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g);
 int fq_launch_gemm(const void* A, int act, int64_t M, int64_t N, int64_t K, const void* codes,

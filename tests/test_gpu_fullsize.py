@@ -128,3 +128,22 @@ def test_moe_grouped_full_shapes():
         err = np.max(np.abs(C - C_ref))
         _say(f"  moe {tag}: rel err {err / scale:.2e}")
         assert err <= TOL["f16"] * scale
+
+
+@pytest.mark.parametrize("bits,g,K", [(4, 128, 4096), (4, 64, 3072), (8, 0, 4096)])
+def test_split_tail_round_on_sampled_columns(bits, g, K):
+    """QKV-wide products whose output tiles exceed the block slots by a partly filled last round: the plan
+    splits those last tiles along K (checked through the plan's description) and a tail reduction adds
+    their partial tiles.  Columns are sampled from every part of N, the last column blocks included."""
+    from paper_2308_09723_amd import fq
+    W = workloads.opt175b_weight("qkv", seed=6, rows=K)
+    N = W.shape[1]
+    cases = [(768, "f16", 62), (1100, "bf16", 63)]                        # 1100 rows: ragged last row block
+    for M, _, _ in cases:
+        desc = fq.gemm_describe(M, N, K, bits, g)
+        _say(f"  M={M}: {desc}")
+        assert "tail=0x" not in desc, desc
+    cols = _sample_columns(N, 48, seed=15)
+    extra = np.arange(N - 1536, N, 97)                       # the last column blocks (the split tiles)
+    cols = np.array(sorted(set(cols.tolist()) | set(extra.tolist())), dtype=np.int64)
+    _check_layer(W, bits, g, cases, cols, "qkv-tail")

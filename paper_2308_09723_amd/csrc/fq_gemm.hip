@@ -142,12 +142,10 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
             const int64_t slots = 256 * (waves == 8 ? 1 : (p.mt == 2 ? 3 : 2));
             const int64_t rem = tiles % slots;
             if (tiles > slots && rem > 0) {
-                // at most 4 ways (8-way tails measured slower than the model says), and only if the
-                // split tiles then fill at least three quarters of the block slots
                 int ts = (int)(slots / rem);
-                if (ts > 4) ts = 4;
+                if (ts > 8) ts = 8;
                 if (ts > KB) ts = KB;
-                if (ts >= 2 && rem * ts * 4 >= slots * 3) {
+                if (ts >= 2) {
                     const int tkbs = (KB + ts - 1) / ts;
                     ts = (KB + tkbs - 1) / tkbs;
                     const int64_t head = tiles - rem;

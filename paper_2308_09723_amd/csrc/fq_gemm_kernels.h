@@ -620,7 +620,8 @@ __device__ inline void fq_tile_of(int L, int nblocks_n, int nblocks_m, int& bn, 
     bn = panel * PW + within - bm * pw_here;
 }
 
-// Sum of the partial tiles of the last `tail_tiles` logical tiles (fixed order), one block per tile.
+// Sum of the partial tiles of the last `tail_tiles` logical tiles (fixed order); block (x, y) takes rows
+// [16 y, 16 y + 16) of tile x.
 template <int ACT>
 __global__ __launch_bounds__(256) void fq_reduce_tail_kernel(const float* __restrict__ partial, int tail_splits,
                                                              int M, int N, int nblocks_n, int nblocks_m,
@@ -628,8 +629,9 @@ __global__ __launch_bounds__(256) void fq_reduce_tail_kernel(const float* __rest
                                                              uint16_t* __restrict__ C) {
     int bn, bm;
     fq_tile_of(head + blockIdx.x, nblocks_n, nblocks_m, bn, bm);
-    const int row0 = bm * bm_rows, col0 = bn * bn_cols;
-    const int rows = min(bm_rows, M - row0), cols = min(bn_cols, N - col0);
+    const int row0 = bm * bm_rows + 16 * blockIdx.y, col0 = bn * bn_cols;
+    const int rows = min(16, M - row0), cols = min(bn_cols, N - col0);
+    if (rows <= 0) return;
     const int quads = cols / 4;                      // N is a multiple of 16
     const int64_t MN = (int64_t)M * N;
     for (int i = threadIdx.x; i < rows * quads; i += 256) {

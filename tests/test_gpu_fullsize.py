@@ -138,7 +138,7 @@ def test_split_tail_round_on_sampled_columns(bits, g, K):
     from paper_2308_09723_amd import fq
     W = workloads.opt175b_weight("qkv", seed=6, rows=K)
     N = W.shape[1]
-    cases = [(768, "f16", 62), (1100, "bf16", 63)]                        # 1100 rows: ragged last row block
+    cases = [(384, "bf16", 61), (768, "f16", 62), (1100, "bf16", 63)]     # 1100 rows: ragged last row block
     for M, _, _ in cases:
         desc = fq.gemm_describe(M, N, K, bits, g)
         _say(f"  M={M}: {desc}")

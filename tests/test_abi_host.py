@@ -128,3 +128,48 @@ def test_quant_error_argument_checks():
     assert call(N=1032) == fq.FQ_ERR_UNSUPPORTED
     assert call(ws=0) == fq.FQ_ERR_WORKSPACE
     assert call(wsb=64) == fq.FQ_ERR_WORKSPACE
+
+
+def test_plans_are_consistent_over_many_shapes():
+    """The plan (host code) for a seeded sweep of shapes: its description parses, the split of K covers K,
+    a split tail round concerns fewer tiles than there are, and the workspace query matches the number of
+    binary32 partial copies the plan writes."""
+    import re
+    import numpy as np
+    rng = np.random.default_rng(11)
+    seen = set()
+    for _ in range(600):
+        bits = int(rng.choice([4, 8]))
+        kblk = 128 if bits == 4 else 64
+        K = kblk * int(rng.integers(1, 400))
+        N = 16 * int(rng.integers(1, 3200))
+        M = int(rng.choice([1, 3, 8, 16, 17, 32, 33, 64, 65, 100, 128, 129, 256, 384, 512, 777, 1024, 2048, 4096]))
+        gs = [g for g in (32, 64, 128, 256, 0) if g == 0 or K % g == 0]
+        g = int(rng.choice(gs))
+        desc = fq.gemm_describe(M, N, K, bits, g)
+        ws = fq.gemm_workspace_bytes(M, N, K, bits, g)
+        KB = K // kblk
+        if desc.startswith("small-m"):
+            f = dict(re.findall(r"(\w+)=(\d+)", desc))
+            seen.add("small")
+            assert M <= 16
+            assert 1 <= int(f["gp"]) * int(f["kw"]) == int(f["waves"]) <= 12
+            assert int(f["au"]) in (1, 2, 4) and M * (kblk // 8) <= int(f["au"]) * 64 * int(f["gp"])
+            splits = int(f["splits"])
+            assert 1 <= splits <= 8
+            assert ws == (splits * M * N * 4 if splits > 1 else 0)
+        else:
+            m = re.match(r"tiled mt=(\d+) waves=(\d+) splits=(\d+) kb_per_split=(\d+) tail=(\d+)x(\d+)", desc)
+            assert m, desc
+            mt, waves, splits, kbs, tail_tiles, tail_splits = map(int, m.groups())
+            seen.add("tail" if tail_tiles else ("split" if splits > 1 else "tiled"))
+            assert M > 16 and mt in (2, 4, 8) and waves in (4, 8)
+            assert mt * 16 >= min(M, 128) or mt == 8
+            assert splits >= 1 and kbs * splits >= KB and kbs * (splits - 1) < KB
+            tiles = -(-(N // 16) // (waves * 3)) * -(-M // (mt * 16))
+            if tail_tiles:
+                assert splits == 1 and 0 < tail_tiles < tiles and 2 <= tail_splits <= 8
+                assert ws == tail_splits * M * N * 4
+            else:
+                assert ws == (splits * M * N * 4 if splits > 1 else 0)
+    assert {"small", "tiled", "split", "tail"} <= seen, seen

@@ -121,9 +121,17 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
                 const int64_t blocks = nbn * nbm * splits;
                 const int64_t per_cu = (blocks + 255) / 256;
                 double t = (double)per_cu * kbs * u;
-                // two 128-row 4-wave blocks share a compute unit; an odd one left over runs alone
-                // and takes a little more than half the time of a pair
-                if (p.mt == 8 && waves == 4 && (per_cu & 1)) t += 0.13 * u * kbs;
+                if (waves == 4) {
+                    // u is a 4-wave block's share when `cap` of them run together on a compute unit; the
+                    // ones left over run with idle SIMDs and take longer than that share (measured: a
+                    // lone block 1.35x (128 rows) to 1.5x, one added to full groups 1.13x)
+                    const int cap = p.mt == 2 ? 3 : 2;
+                    const int64_t left = per_cu % cap;
+                    if (left > 0) {
+                        const double f = per_cu < cap ? (p.mt == 8 ? 1.35 : 1.48) : (p.mt == 8 ? 1.13 : 1.0);
+                        t += (f - 1.0) * (double)left * kbs * u;
+                    }
+                }
                 // fewer blocks than compute units: the idle ones also pull no weights
                 if (blocks < 256) t *= 256.0 / (double)blocks;
                 if (splits > 1) t += 2.0 * splits * (double)M * (double)N * 4.0 / 4e6 + 5.0;

@@ -84,9 +84,7 @@ __global__ __launch_bounds__(256) void fq_scales_fold_kernel(const uint16_t* __r
 }
 
 // ---------------------------------------------------------------------------------
-// Encode + pack.  One wavefront produces one tile record set (16 columns x KBLK rows =
-// 1 KiB): lane (j, nl) walks the rows it owns, divides, rounds, clamps and assembles its
-// 16 bytes, which are stored with one 16-byte write per lane.
+// Encode: divide (IEEE binary32), round half to even, clamp (Appendix A's q = int(w / s)).
 // ---------------------------------------------------------------------------------
 __device__ inline int encode_one(uint16_t wbits, float s, int qmax) {
     if (s == 0.0f) return 0;
@@ -95,38 +93,118 @@ __device__ inline int encode_one(uint16_t wbits, float s, int qmax) {
     return (int)c;
 }
 
-template <int BITS>
-__global__ __launch_bounds__(256) void fq_encode_kernel(const uint16_t* __restrict__ W, int64_t K,
-                                                        int64_t N, int g,
-                                                        const uint16_t* __restrict__ scales,
-                                                        uint4* __restrict__ codes) {
+// ---------------------------------------------------------------------------------
+// One-pass quantiser for group sizes that divide 128 (32, 64, 128): a block stages a panel of
+// 128 rows x 128 columns of W in LDS with coalesced 16-byte loads, takes the abs-max of every
+// 32-row sub-block, derives the scales of the panel's groups, and encodes and packs the panel
+// from LDS.  W is read from HBM once (the two-pass path reads it twice, the second time with
+// 2-byte loads).  Same arithmetic as the two-pass kernels, hence the same bits.
+// ---------------------------------------------------------------------------------
+#define FQ_QP_ROWS 128
+#define FQ_QP_COLS 128
+#define FQ_QP_PITCH (FQ_QP_COLS + 8)   // binary16 elements per LDS row
+// OWN_SCALES = false: the scales were computed before (groups larger than the panel) and are only read.
+template <int BITS, bool OWN_SCALES>
+__global__ __launch_bounds__(256) void fq_quantize_panel_kernel(const uint16_t* __restrict__ W, int64_t K,
+                                                                int64_t N, int g, float L,
+                                                                uint16_t* __restrict__ scales,
+                                                                uint4* __restrict__ codes) {
     constexpr int KBLK = BITS == 4 ? 128 : 64;
     constexpr int STEPS = KBLK / FQ_KSTEP;
     constexpr int QMAX = BITS == 4 ? 7 : 127;
-    const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
-    const int64_t ntiles = N / FQ_NTILE;
-    const int64_t ntile = (int64_t)blockIdx.x * 4 + wave;   // four neighbouring column tiles per block
-    const int64_t kb = blockIdx.y;
-    if (ntile >= ntiles) return;
-    const int nl = lane & 15, j = lane >> 4;
-    const int64_t n = ntile * FQ_NTILE + nl;
-    uint32_t rec[4] = {0u, 0u, 0u, 0u};
+    __shared__ uint16_t panel[FQ_QP_ROWS * FQ_QP_PITCH];
+    __shared__ uint16_t submax[4][FQ_QP_COLS];      // abs-max bits of the 32-row sub-blocks
+    __shared__ float sub_scale[4][FQ_QP_COLS];      // scale of the group each sub-block belongs to
+    const int tid = threadIdx.x;
+    const int64_t n0 = (int64_t)blockIdx.x * FQ_QP_COLS;
+    const int64_t k0 = (int64_t)blockIdx.y * FQ_QP_ROWS;
+    const int cols = (int)((N - n0) < FQ_QP_COLS ? (N - n0) : FQ_QP_COLS);   // multiple of 16
+    const int rows = (int)((K - k0) < FQ_QP_ROWS ? (K - k0) : FQ_QP_ROWS);   // 128, or 64 at the end (8-bit)
+
+    // stage: thread -> (row = tid / 16 + 16 i, 8 columns starting at 8 (tid % 16))
+    {
+        const int c8 = (tid & 15) * 8;
 #pragma unroll
-    for (int t = 0; t < STEPS; ++t) {
-        const int64_t k0 = kb * KBLK + t * FQ_KSTEP + j * 8;
-        const float s = half_bits_to_float(scales[(k0 / g) * N + n]);   // 8 rows share a group (g % 32 == 0)
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int q = encode_one(W[(k0 + e) * N + n], s, QMAX);
-            if (BITS == 4) {
-                rec[t] |= (uint32_t)(q + 8) << (4 * fq_nibble_slot(e));
-            } else {
-                rec[2 * t + (e >> 2)] |= (uint32_t)(q + 128) << (8 * (e & 3));
-            }
+        for (int i = 0; i < FQ_QP_ROWS / 16; ++i) {
+            const int r = (tid >> 4) + 16 * i;
+            uint4 v = make_uint4(0u, 0u, 0u, 0u);
+            if (r < rows && c8 < cols) v = *reinterpret_cast<const uint4*>(W + (k0 + r) * N + n0 + c8);
+            *reinterpret_cast<uint4*>(&panel[r * FQ_QP_PITCH + c8]) = v;
         }
     }
-    codes[fq_rec(ntile, kb, ntiles, lane)] = make_uint4(rec[0], rec[1], rec[2], rec[3]);
+    __syncthreads();
+    if constexpr (OWN_SCALES) {
+        // abs-max of the 32-row sub-blocks: thread -> column tid % 128, sub-blocks tid / 128 and tid / 128 + 2
+        {
+            const int c = tid & 127;
+    #pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int sb = (tid >> 7) + 2 * h;
+                uint32_t m = 0;
+                for (int r = 0; r < 32; ++r) {
+                    const uint32_t a = panel[(sb * 32 + r) * FQ_QP_PITCH + c] & 0x7fffu;
+                    m = a > m ? a : m;
+                }
+                submax[sb][c] = (uint16_t)m;
+            }
+        }
+        __syncthreads();
+        // scales: one per (group, column); a group is g / 32 consecutive sub-blocks
+        {
+            const int per = g / 32;                 // 1, 2 or 4
+            const int c = tid & 127;
+    #pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int sb = (tid >> 7) + 2 * h;
+                const int first = (sb / per) * per;
+                uint32_t m = 0;
+                for (int i = 0; i < per; ++i) {
+                    const uint32_t a = submax[first + i][c];
+                    m = a > m ? a : m;
+                }
+                const uint32_t sbits = scale_bits_from_absmax_bits(m, L);
+                sub_scale[sb][c] = half_bits_to_float((uint16_t)sbits);
+                if (sb == first && sb * 32 < rows && c < cols) scales[((k0 + sb * 32) / g) * N + n0 + c] = (uint16_t)sbits;
+            }
+        }
+        __syncthreads();
+    } else {
+        const int c = tid & 127;
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int sb = (tid >> 7) + 2 * h;
+            float v = 0.0f;
+            if (sb * 32 < rows && c < cols) v = half_bits_to_float(scales[((k0 + sb * 32) / g) * N + n0 + c]);
+            sub_scale[sb][c] = v;
+        }
+        __syncthreads();
+    }
+    // encode + pack: wave w takes column tiles w, w + 4 of the panel
+    const int lane = tid & 63, wave = tid >> 6;
+    const int nl = lane & 15, j = lane >> 4;
+    const int64_t ntiles = N / FQ_NTILE;
+    for (int tl = wave; tl * FQ_NTILE < cols; tl += 4) {
+        const int c = tl * FQ_NTILE + nl;
+        for (int kb = 0; kb * KBLK < rows; ++kb) {
+            uint32_t rec[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int t = 0; t < STEPS; ++t) {
+                const int r0 = kb * KBLK + t * FQ_KSTEP + j * 8;
+                const float sc = sub_scale[r0 / 32][c];
+#pragma unroll
+                for (int e = 0; e < 8; ++e) {
+                    const int q = encode_one(panel[(r0 + e) * FQ_QP_PITCH + c], sc, QMAX);
+                    if (BITS == 4) {
+                        rec[t] |= (uint32_t)(q + 8) << (4 * fq_nibble_slot(e));
+                    } else {
+                        rec[2 * t + (e >> 2)] |= (uint32_t)(q + 128) << (8 * (e & 3));
+                    }
+                }
+            }
+            const int64_t kblock = (k0 / KBLK) + kb;
+            codes[fq_rec(n0 / FQ_NTILE + tl, kblock, ntiles, lane)] = make_uint4(rec[0], rec[1], rec[2], rec[3]);
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------------
@@ -311,6 +389,16 @@ __global__ __launch_bounds__(256) void fq_quant_error_final_kernel(const double*
 int fq_launch_quantize(const void* W, int64_t K, int64_t N, int bits, int g, void* codes, void* scales,
                        hipStream_t stream) {
     const float L = (float)((1 << bits) - 1);
+    if (g == 32 || g == 64 || g == 128) {
+        dim3 grid((unsigned)((N + FQ_QP_COLS - 1) / FQ_QP_COLS), (unsigned)((K + FQ_QP_ROWS - 1) / FQ_QP_ROWS));
+        if (bits == 4)
+            hipLaunchKernelGGL((fq_quantize_panel_kernel<4, true>), grid, dim3(256), 0, stream, (const uint16_t*)W,
+                               K, N, g, L, (uint16_t*)scales, (uint4*)codes);
+        else
+            hipLaunchKernelGGL((fq_quantize_panel_kernel<8, true>), grid, dim3(256), 0, stream, (const uint16_t*)W,
+                               K, N, g, L, (uint16_t*)scales, (uint4*)codes);
+        return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;
+    }
     if (g >= 1024 && g % 128 == 0) {
         // two stages; the block maxima (K / 128 x N binary16 = K * N / 64 bytes) are parked in the
         // code buffer, which is only written by the encoding pass below
@@ -328,15 +416,14 @@ int fq_launch_quantize(const void* W, int64_t K, int64_t N, int bits, int g, voi
                            (uint16_t*)scales);
     }
     {
-        const int kblk = fq_kblk(bits);
-        dim3 block(256);
-        dim3 grid((unsigned)((N / FQ_NTILE + 3) / 4), (unsigned)(K / kblk));
+        // encoding pass from LDS panels, with the scales just written
+        dim3 grid((unsigned)((N + FQ_QP_COLS - 1) / FQ_QP_COLS), (unsigned)((K + FQ_QP_ROWS - 1) / FQ_QP_ROWS));
         if (bits == 4)
-            hipLaunchKernelGGL(fq_encode_kernel<4>, grid, block, 0, stream, (const uint16_t*)W, K, N, g,
-                               (const uint16_t*)scales, (uint4*)codes);
+            hipLaunchKernelGGL((fq_quantize_panel_kernel<4, false>), grid, dim3(256), 0, stream, (const uint16_t*)W,
+                               K, N, g, L, (uint16_t*)scales, (uint4*)codes);
         else
-            hipLaunchKernelGGL(fq_encode_kernel<8>, grid, block, 0, stream, (const uint16_t*)W, K, N, g,
-                               (const uint16_t*)scales, (uint4*)codes);
+            hipLaunchKernelGGL((fq_quantize_panel_kernel<8, false>), grid, dim3(256), 0, stream, (const uint16_t*)W,
+                               K, N, g, L, (uint16_t*)scales, (uint4*)codes);
     }
     return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;
 }

@@ -17,4 +17,5 @@ from .fq_oracle import (  # noqa: F401
     choose_group,
     bits_per_weight,
     quant_error,
+    bf16_scale_bits,
 )

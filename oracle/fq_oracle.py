@@ -47,6 +47,15 @@ R6  Section 3.3: "range" is the abs-max of a group; a halving step is taken
     2b is an image): the *default* alpha is PARITY UNPINNED; the function
     alpha -> g is pinned by constructed cases.
 
+R7  Scale format.  Appendix B stores the scales in half precision; section
+    4.1 ("GPU kernel implementations") describes kernels whose scales have the
+    data type of the activation, i.e. bfloat16 scales next to bfloat16
+    activations.  ``scale_format="bf16"`` is that variant: the stored scale
+    is the smallest *bfloat16* number s with (2^b - 1) * s >= 2 * max|w|;
+    everything else (binary32 quotient, ties to even, clamp) is unchanged, so
+    |q*s - w| <= s/2 still holds exactly.  Such scales are returned as
+    float32 arrays whose low 16 bits are zero (numpy has no bfloat16).
+
 Pins (tests marked "not gpu"): exact-rational brute force for scales and
 codes, the s/2 reconstruction bound, code range, g = K against an
 independently written per-column quantiser, sign symmetry, power-of-two
@@ -55,7 +64,11 @@ the paper's Table 5, brute-force dot products, one-hot and all-ones GEMM
 special cases, and constructed matrices with a known heuristic answer; for ``quant_error``:
 a hand-computed column, the zero error of exactly representable weights, the
 s/2 bound and the (sum of s^2)/12-per-weight expectation on uniformly spread
-weights.
+weights; for the bfloat16 scale format: exact-rational minimality of every
+scale over all binary16 abs-max values, the bit pattern (low 16 bits zero),
+exact-rational codes on an exhaustive window, the s/2 bound, power-of-two
+equivariance and the bracket f16-format scale <= bf16-format scale < f16-format
+scale * (1 + 2^-7) that the two roundings of one real number must obey.
 """
 from __future__ import annotations
 
@@ -73,6 +86,7 @@ __all__ = [
     "choose_group",
     "bits_per_weight",
     "quant_error",
+    "bf16_scale_bits",
 ]
 
 
@@ -111,17 +125,46 @@ def group_absmax(W: np.ndarray, group_size: int) -> np.ndarray:
     return np.abs(W).reshape(K // g, g, N).max(axis=1)
 
 
-def scale_from_absmax(m: np.ndarray, bits: int) -> np.ndarray:
-    """Smallest float16 ``s >= 0`` with (2^b - 1) * s >= 2 * m  (reading R3).
+def _bf16_step(s: np.ndarray, up: bool) -> np.ndarray:
+    """Neighbouring bfloat16 value of a non-negative bfloat16 held in float32."""
+    b = s.view(np.uint32).astype(np.int64)
+    b = b + 0x10000 if up else b - 0x10000
+    return b.astype(np.uint32).view(np.float32)
+
+
+def scale_from_absmax(m: np.ndarray, bits: int, scale_format: str = "f16") -> np.ndarray:
+    """Smallest storable ``s >= 0`` with (2^b - 1) * s >= 2 * m  (readings R3, R7).
 
     Appendix A gives s = 2*max / (2^b - 1); Appendix B says it is stored in
-    half precision.  The comparison is done in float64, where both sides are
-    exact (an 8-bit integer times an 11-bit significand; a doubling).
+    half precision (``scale_format="f16"``, returned as float16); section 4.1's
+    kernels for bfloat16 activations take bfloat16 scales
+    (``scale_format="bf16"``, returned as float32 with the low 16 bits zero).
+    The comparison is done in float64, where both sides are exact (an 8-bit
+    integer times a significand of at most 11 bits; a doubling).
     """
     if m.dtype != np.float16:
         raise ValueError("abs-max must be float16")
+    if scale_format not in ("f16", "bf16"):
+        raise ValueError("scale_format must be 'f16' or 'bf16'")
     L = float(levels_of(bits))
     target = 2.0 * m.astype(np.float64)
+    if scale_format == "bf16":
+        # any nearby bfloat16 starting guess will do: drop the low half of the binary32 quotient
+        guess = (target / L).astype(np.float32)
+        s = (guess.view(np.uint32) & np.uint32(0xFFFF0000)).view(np.float32)
+        while True:
+            low = L * s.astype(np.float64) < target
+            if not low.any():
+                break
+            s = np.where(low, _bf16_step(s, True), s).astype(np.float32)
+        while True:
+            pos = s > 0
+            p = np.where(pos, _bf16_step(np.where(pos, s, np.float32(1.0)), False), s).astype(np.float32)
+            ok = pos & (L * p.astype(np.float64) >= target)
+            if not ok.any():
+                break
+            s = np.where(ok, p, s).astype(np.float32)
+        return s
     s = (target / L).astype(np.float16)  # any nearby starting guess will do
     pos_inf = np.float16(np.inf)
     neg_inf = np.float16(-np.inf)
@@ -141,16 +184,25 @@ def scale_from_absmax(m: np.ndarray, bits: int) -> np.ndarray:
     return s
 
 
-def quantize(W: np.ndarray, bits: int, group_size: int):
+def bf16_scale_bits(s: np.ndarray) -> np.ndarray:
+    """The 16-bit patterns of bfloat16 scales held in float32 (low halves must be zero)."""
+    b = np.ascontiguousarray(s, dtype=np.float32).view(np.uint32)
+    if np.any(b & np.uint32(0xFFFF)):
+        raise ValueError("not bfloat16 values")
+    return (b >> np.uint32(16)).astype(np.uint16)
+
+
+def quantize(W: np.ndarray, bits: int, group_size: int, scale_format: str = "f16"):
     """Appendix A's encoder on blocks of ``g`` rows per column.
 
-    Returns ``(q, s)``: int8 codes [K, N] and float16 scales [K/g, N].
+    Returns ``(q, s)``: int8 codes [K, N] and scales [K/g, N] (float16, or for
+    ``scale_format="bf16"`` bfloat16 values held in float32).
     ``group_size`` 0 or K means one scale per column.
     """
     g = _check_w(W, group_size)
     K, N = W.shape
     qm = qmax_of(bits)
-    s = scale_from_absmax(group_absmax(W, g), bits)            # [K/g, N] f16
+    s = scale_from_absmax(group_absmax(W, g), bits, scale_format)   # [K/g, N]
     s_rows = np.repeat(s.astype(np.float32), g, axis=0)        # [K, N]   f32
     w32 = W.astype(np.float32)
     with np.errstate(divide="ignore", invalid="ignore"):

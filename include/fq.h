@@ -41,6 +41,17 @@ typedef enum fq_dtype {
     FQ_BF16 = 1 /* bfloat16 activations and output */
 } fq_dtype;
 
+/* Storage format of the scale matrix.  Appendix B stores the scales in half precision; the
+ * kernels of section 4.1 ("GPU kernel implementations") take scales of the activation's data
+ * type, i.e. bfloat16 scales next to bfloat16 activations.  The entry points without a
+ * `scale_format` argument use FQ_SCALE_F16 (for either activation type); the *_sf entry points
+ * take the format explicitly.  FQ_SCALE_BF16 changes the encoding: the quantiser then picks the
+ * smallest BFLOAT16 s with (2^bits - 1) * s >= 2 max|w| and divides by that s. */
+typedef enum fq_scale_format {
+    FQ_SCALE_F16 = 0, /* IEEE binary16 scales */
+    FQ_SCALE_BF16 = 1 /* bfloat16 scales; products accept them with FQ_BF16 activations only */
+} fq_scale_format;
+
 /* Shape limits shared by every call:
  *   bits        4 or 8
  *   N           multiple of 16
@@ -53,7 +64,7 @@ typedef enum fq_dtype {
 /* Size in bytes of the packed code buffer: K*N*bits/8 (no padding).  0 on invalid arguments. */
 size_t fq_codes_bytes(int64_t K, int64_t N, int bits);
 
-/* Size in bytes of the scale matrix [K/g, N] of binary16 values.  0 on invalid arguments. */
+/* Size in bytes of the scale matrix [K/g, N] of 16-bit values (either format).  0 on invalid arguments. */
 size_t fq_scales_bytes(int64_t K, int64_t N, int group_size);
 
 /* Bytes of scratch fq_gemm needs for this problem (split-K partial sums; may be 0).
@@ -81,6 +92,12 @@ size_t fq_gemm_grouped_workspace_bytes(int64_t total_rows, int E, int64_t N, int
  */
 int fq_quantize(const void* W_f16, int64_t K, int64_t N, int bits, int group_size, void* codes,
                 void* scales_f16, void* stream);
+
+/* fq_quantize with the scale matrix stored as `scale_format` (an fq_scale_format); `scales` is
+ * [K/g, N] 16-bit values of that format.  fq_quantize(...) = fq_quantize_sf(..., FQ_SCALE_F16, ...).
+ * Errors: as fq_quantize; FQ_ERR_INVALID_ARG for an unknown format. */
+int fq_quantize_sf(const void* W_f16, int64_t K, int64_t N, int bits, int group_size, int scale_format,
+                   void* codes, void* scales, void* stream);
 
 /*
  * fq_unpack -- inverse of the packing step: writes the logical signed codes q[K, N]
@@ -125,6 +142,11 @@ int fq_quant_error(const void* W_f16, int64_t K, int64_t N, int bits, int group_
                    const void* scales_f16, double* sse_out, double* max_abs_out, void* workspace,
                    size_t workspace_bytes, void* stream);
 
+/* fq_quant_error for scales stored as `scale_format`. */
+int fq_quant_error_sf(const void* W_f16, int64_t K, int64_t N, int bits, int group_size, int scale_format,
+                      const void* codes, const void* scales, double* sse_out, double* max_abs_out,
+                      void* workspace, size_t workspace_bytes, void* stream);
+
 /*
  * fq_gemm -- the fused dequantise-and-multiply product of section 4.1 ("GPU kernel
  * implementations"):  C[m, n] = sum_k A[m, k] * (q[k, n] * s[k / g, n]),
@@ -142,6 +164,13 @@ int fq_quant_error(const void* W_f16, int64_t K, int64_t N, int bits, int group_
 int fq_gemm(const void* A, int act_dtype, int64_t M, int64_t N, int64_t K, const void* codes,
             const void* scales_f16, int bits, int group_size, void* C, void* workspace,
             size_t workspace_bytes, void* stream);
+
+/* fq_gemm with the scale matrix stored as `scale_format`, written by fq_quantize_sf with the same
+ * format (section 4.1: scales of the activation's data type).  FQ_SCALE_BF16 requires
+ * act_dtype = FQ_BF16 (otherwise FQ_ERR_UNSUPPORTED); FQ_SCALE_F16 is fq_gemm itself. */
+int fq_gemm_sf(const void* A, int act_dtype, int64_t M, int64_t N, int64_t K, const void* codes,
+               const void* scales, int scale_format, int bits, int group_size, void* C, void* workspace,
+               size_t workspace_bytes, void* stream);
 
 /*
  * fq_gemm_grouped -- the same product for the expert FFNs of a mixture-of-experts
@@ -162,6 +191,11 @@ int fq_gemm(const void* A, int act_dtype, int64_t M, int64_t N, int64_t K, const
 int fq_gemm_grouped(const void* A, int act_dtype, const int32_t* offsets_host, int E, int64_t N,
                     int64_t K, const void* codes, const void* scales_f16, int bits, int group_size,
                     void* C, void* workspace, size_t workspace_bytes, void* stream);
+
+/* fq_gemm_grouped with the scale matrices stored as `scale_format` (same rule as fq_gemm_sf). */
+int fq_gemm_grouped_sf(const void* A, int act_dtype, const int32_t* offsets_host, int E, int64_t N,
+                       int64_t K, const void* codes, const void* scales, int scale_format, int bits,
+                       int group_size, void* C, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
  * fq_gemm_describe -- writes a short text description of the kernel configuration fq_gemm

@@ -64,13 +64,19 @@ size_t fq_gemm_grouped_workspace_bytes(int64_t total_rows, int E, int64_t N, int
     return 0;
 }
 
-int fq_quantize(const void* W_f16, int64_t K, int64_t N, int bits, int group_size, void* codes,
-                void* scales_f16, void* stream) {
-    if (!W_f16 || !codes || !scales_f16) return FQ_ERR_INVALID_ARG;
+int fq_quantize_sf(const void* W_f16, int64_t K, int64_t N, int bits, int group_size, int scale_format,
+                   void* codes, void* scales, void* stream) {
+    if (!W_f16 || !codes || !scales) return FQ_ERR_INVALID_ARG;
+    if (scale_format != FQ_SCALE_F16 && scale_format != FQ_SCALE_BF16) return FQ_ERR_INVALID_ARG;
     int g = 0;
     const int st = check_shape(K, N, bits, group_size, &g);
     if (st != FQ_OK) return st;
-    return fq_launch_quantize(W_f16, K, N, bits, g, codes, scales_f16, (hipStream_t)stream);
+    return fq_launch_quantize(W_f16, K, N, bits, g, scale_format, codes, scales, (hipStream_t)stream);
+}
+
+int fq_quantize(const void* W_f16, int64_t K, int64_t N, int bits, int group_size, void* codes,
+                void* scales_f16, void* stream) {
+    return fq_quantize_sf(W_f16, K, N, bits, group_size, FQ_SCALE_F16, codes, scales_f16, stream);
 }
 
 int fq_unpack(const void* codes, int64_t K, int64_t N, int bits, int8_t* q, void* stream) {
@@ -126,13 +132,21 @@ size_t fq_quant_error_workspace_bytes(int64_t K, int64_t N) {
 int fq_quant_error(const void* W_f16, int64_t K, int64_t N, int bits, int group_size, const void* codes,
                    const void* scales_f16, double* sse_out, double* max_abs_out, void* workspace,
                    size_t workspace_bytes, void* stream) {
+    return fq_quant_error_sf(W_f16, K, N, bits, group_size, FQ_SCALE_F16, codes, scales_f16, sse_out, max_abs_out,
+                             workspace, workspace_bytes, stream);
+}
+
+int fq_quant_error_sf(const void* W_f16, int64_t K, int64_t N, int bits, int group_size, int scale_format,
+                      const void* codes, const void* scales_f16, double* sse_out, double* max_abs_out,
+                      void* workspace, size_t workspace_bytes, void* stream) {
     if (!W_f16 || !codes || !scales_f16 || !sse_out || !max_abs_out) return FQ_ERR_INVALID_ARG;
+    if (scale_format != FQ_SCALE_F16 && scale_format != FQ_SCALE_BF16) return FQ_ERR_INVALID_ARG;
     int g = 0;
     const int st = check_shape(K, N, bits, group_size, &g);
     if (st != FQ_OK) return st;
     if (!workspace || workspace_bytes < fq_quant_error_workspace_bytes(K, N)) return FQ_ERR_WORKSPACE;
     double out[2] = {0.0, 0.0};
-    const int rc = fq_launch_quant_error(W_f16, K, N, bits, g, codes, scales_f16, out, workspace,
+    const int rc = fq_launch_quant_error(W_f16, K, N, bits, g, scale_format, codes, scales_f16, out, workspace,
                                          (hipStream_t)stream);
     if (rc != FQ_OK) return rc;
     *sse_out = out[0];
@@ -140,27 +154,58 @@ int fq_quant_error(const void* W_f16, int64_t K, int64_t N, int bits, int group_
     return FQ_OK;
 }
 
+// internal activation kind: FQ_F16, FQ_BF16, or 2 = bf16 activations with bf16 scales; -1 = refuse
+static int act_kind(int act_dtype, int scale_format, int* status) {
+    *status = FQ_OK;
+    if (act_dtype != FQ_F16 && act_dtype != FQ_BF16) *status = FQ_ERR_INVALID_ARG;
+    else if (scale_format != FQ_SCALE_F16 && scale_format != FQ_SCALE_BF16) *status = FQ_ERR_INVALID_ARG;
+    else if (scale_format == FQ_SCALE_BF16 && act_dtype != FQ_BF16) *status = FQ_ERR_UNSUPPORTED;
+    if (*status != FQ_OK) return -1;
+    return scale_format == FQ_SCALE_BF16 ? 2 : act_dtype;
+}
+
 int fq_gemm(const void* A, int act_dtype, int64_t M, int64_t N, int64_t K, const void* codes,
             const void* scales_f16, int bits, int group_size, void* C, void* workspace,
             size_t workspace_bytes, void* stream) {
-    if (M < 0 || (act_dtype != FQ_F16 && act_dtype != FQ_BF16)) return FQ_ERR_INVALID_ARG;
+    return fq_gemm_sf(A, act_dtype, M, N, K, codes, scales_f16, FQ_SCALE_F16, bits, group_size, C, workspace,
+                      workspace_bytes, stream);
+}
+
+int fq_gemm_sf(const void* A, int act_dtype, int64_t M, int64_t N, int64_t K, const void* codes,
+               const void* scales_f16, int scale_format, int bits, int group_size, void* C, void* workspace,
+               size_t workspace_bytes, void* stream) {
+    if (M < 0) return FQ_ERR_INVALID_ARG;
+    int kst = FQ_OK;
+    const int kind = act_kind(act_dtype, scale_format, &kst);
+    if (kst == FQ_ERR_INVALID_ARG) return kst;
     int g = 0;
     const int st = check_shape(K, N, bits, group_size, &g);
     if (st != FQ_OK) return st;
+    if (kst != FQ_OK) return kst;
     if (M == 0) return FQ_OK;
     if (!A || !codes || !scales_f16 || !C) return FQ_ERR_INVALID_ARG;
     if (M > (int64_t)1 << 24) return FQ_ERR_UNSUPPORTED;
     const size_t need = fq_gemm_workspace_bytes(M, N, K, bits, group_size);
     if (need > 0 && (!workspace || workspace_bytes < need)) return FQ_ERR_WORKSPACE;
-    return fq_launch_gemm(A, act_dtype, M, N, K, codes, scales_f16, bits, g, C, workspace,
+    return fq_launch_gemm(A, kind, M, N, K, codes, scales_f16, bits, g, C, workspace,
                           (hipStream_t)stream);
 }
 
 int fq_gemm_grouped(const void* A, int act_dtype, const int32_t* offsets_host, int E, int64_t N,
                     int64_t K, const void* codes, const void* scales_f16, int bits, int group_size,
                     void* C, void* workspace, size_t workspace_bytes, void* stream) {
+    return fq_gemm_grouped_sf(A, act_dtype, offsets_host, E, N, K, codes, scales_f16, FQ_SCALE_F16, bits,
+                              group_size, C, workspace, workspace_bytes, stream);
+}
+
+int fq_gemm_grouped_sf(const void* A, int act_dtype, const int32_t* offsets_host, int E, int64_t N,
+                       int64_t K, const void* codes, const void* scales_f16, int scale_format, int bits,
+                       int group_size, void* C, void* workspace, size_t workspace_bytes, void* stream) {
     (void)workspace; (void)workspace_bytes;
-    if (!offsets_host || E < 0 || (act_dtype != FQ_F16 && act_dtype != FQ_BF16)) return FQ_ERR_INVALID_ARG;
+    if (!offsets_host || E < 0) return FQ_ERR_INVALID_ARG;
+    int kst = FQ_OK;
+    const int kind = act_kind(act_dtype, scale_format, &kst);
+    if (kst != FQ_OK) return kst;
     if (E > 256) return FQ_ERR_UNSUPPORTED;
     int g = 0;
     const int st = check_shape(K, N, bits, group_size, &g);
@@ -171,7 +216,7 @@ int fq_gemm_grouped(const void* A, int act_dtype, const int32_t* offsets_host, i
         if (offsets_host[e + 1] < offsets_host[e]) return FQ_ERR_INVALID_ARG;
     if (offsets_host[E] == 0) return FQ_OK;
     if (!A || !codes || !scales_f16 || !C) return FQ_ERR_INVALID_ARG;
-    return fq_launch_gemm_grouped(A, act_dtype, offsets_host, E, N, K, codes, scales_f16, bits, g, C,
+    return fq_launch_gemm_grouped(A, kind, offsets_host, E, N, K, codes, scales_f16, bits, g, C,
                                   (hipStream_t)stream);
 }
 

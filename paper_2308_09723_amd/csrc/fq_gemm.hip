@@ -24,6 +24,8 @@ FQ_DECLARE_GEMM(0, 4)
 FQ_DECLARE_GEMM(0, 8)
 FQ_DECLARE_GEMM(1, 4)
 FQ_DECLARE_GEMM(1, 8)
+FQ_DECLARE_GEMM(2, 4)   // bf16 activations, bf16 scales
+FQ_DECLARE_GEMM(2, 8)
 
 fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
     (void)g;
@@ -183,8 +185,12 @@ int fq_launch_gemm(const void* A, int act, int64_t M, int64_t N, int64_t K, cons
         if (bits == 4) return fq_launch_typed_0_4(A, M, N, K, codes, scales, g, C, workspace, plan, stream);
         return fq_launch_typed_0_8(A, M, N, K, codes, scales, g, C, workspace, plan, stream);
     }
-    if (bits == 4) return fq_launch_typed_1_4(A, M, N, K, codes, scales, g, C, workspace, plan, stream);
-    return fq_launch_typed_1_8(A, M, N, K, codes, scales, g, C, workspace, plan, stream);
+    if (act == FQ_BF16) {
+        if (bits == 4) return fq_launch_typed_1_4(A, M, N, K, codes, scales, g, C, workspace, plan, stream);
+        return fq_launch_typed_1_8(A, M, N, K, codes, scales, g, C, workspace, plan, stream);
+    }
+    if (bits == 4) return fq_launch_typed_2_4(A, M, N, K, codes, scales, g, C, workspace, plan, stream);
+    return fq_launch_typed_2_8(A, M, N, K, codes, scales, g, C, workspace, plan, stream);
 }
 
 // The grouped product launches up to three kernels (row tiles of 128, 64 and 32 rows) that do not
@@ -256,9 +262,12 @@ int fq_launch_gemm_grouped(const void* A, int act, const int32_t* offsets, int E
     if (act == FQ_F16) {
         st = bits == 4 ? fq_launch_grouped_typed_0_4(A, offsets, E, N, K, codes, scales, g, C, streams)
                        : fq_launch_grouped_typed_0_8(A, offsets, E, N, K, codes, scales, g, C, streams);
-    } else {
+    } else if (act == FQ_BF16) {
         st = bits == 4 ? fq_launch_grouped_typed_1_4(A, offsets, E, N, K, codes, scales, g, C, streams)
                        : fq_launch_grouped_typed_1_8(A, offsets, E, N, K, codes, scales, g, C, streams);
+    } else {
+        st = bits == 4 ? fq_launch_grouped_typed_2_4(A, offsets, E, N, K, codes, scales, g, C, streams)
+                       : fq_launch_grouped_typed_2_8(A, offsets, E, N, K, codes, scales, g, C, streams);
     }
     // join even after a failed launch, so that the side streams never run ahead of the caller's
     for (int i = 0; i < 2; ++i) {

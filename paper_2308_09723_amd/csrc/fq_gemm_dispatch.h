@@ -131,14 +131,14 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
         const int bn_cols = plan.waves * MMA_NT * FQ_NTILE;
         const int nblocks_n = (ntiles + plan.waves * MMA_NT - 1) / (plan.waves * MMA_NT);
         const int nblocks_m = (int)((M + bm - 1) / bm);
-        hipLaunchKernelGGL(fq_reduce_tail_kernel<ACT>, dim3((unsigned)plan.tail_tiles, (unsigned)plan.mt), dim3(256), 0, stream,
+        hipLaunchKernelGGL(fq_reduce_tail_kernel<(ACT == FQ_F16 ? FQ_F16 : FQ_BF16)>, dim3((unsigned)plan.tail_tiles, (unsigned)plan.mt), dim3(256), 0, stream,
                            (const float*)partial, plan.tail_splits, (int)M, (int)N, nblocks_n, nblocks_m,
                            nblocks_n * nblocks_m - plan.tail_tiles, bm, bn_cols, (uint16_t*)C);
     }
     if (plan.splits > 1) {
         const int64_t MN = M * N;
         dim3 grid((unsigned)((MN / 4 + 255) / 256));
-        hipLaunchKernelGGL(fq_reduce_kernel<ACT>, grid, dim3(256), 0, stream, (const float*)partial,
+        hipLaunchKernelGGL(fq_reduce_kernel<(ACT == FQ_F16 ? FQ_F16 : FQ_BF16)>, grid, dim3(256), 0, stream, (const float*)partial,
                            plan.splits, MN, (uint16_t*)C);
     }
     return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;

@@ -27,6 +27,10 @@
 
 namespace fqk {
 
+// Third value of the ACT template argument next to FQ_F16 / FQ_BF16: bfloat16 activations whose
+// scale matrix holds bfloat16 values (section 4.1, "GPU kernel implementations": scales of the
+// activation's data type).  It behaves as FQ_BF16 everywhere except where a scale is widened.
+#define FQ_BF16_BS 2
 
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -153,19 +157,13 @@ struct Dequant<FQ_BF16, 8> {
     }
 };
 
+template <int BITS>
+struct Dequant<FQ_BF16_BS, BITS> : Dequant<FQ_BF16, BITS> {};
+
 template <int ACT>
 __device__ inline u32x4 ones_operand() {
     const uint32_t one2 = ACT == FQ_F16 ? 0x3c003c00u : 0x3f803f80u;
     u32x4 r = {one2, one2, one2, one2};
-    return r;
-}
-
-__device__ inline f32x4 scales4(const uint16_t* p) {
-    // four consecutive binary16 scales -> binary32
-    const u32x2 v = *reinterpret_cast<const u32x2*>(p);
-    const f16x2 a = bitcast<f16x2>(v[0]);
-    const f16x2 b = bitcast<f16x2>(v[1]);
-    f32x4 r = {(float)a[0], (float)a[1], (float)b[0], (float)b[1]};
     return r;
 }
 
@@ -235,11 +233,19 @@ struct SkinnyStage {
     u32x4 areg[AU];
 };
 
+// four stored scales -> binary32
+template <int ACT>
 __device__ inline f32x4 scales4(const u32x2& v) {
-    const f16x2 a = bitcast<f16x2>(v[0]);
-    const f16x2 b = bitcast<f16x2>(v[1]);
-    f32x4 r = {(float)a[0], (float)a[1], (float)b[0], (float)b[1]};
-    return r;
+    if constexpr (ACT == FQ_BF16_BS) {
+        f32x4 r = {bitcast<float>(v[0] << 16), bitcast<float>(v[0] & 0xffff0000u),
+                   bitcast<float>(v[1] << 16), bitcast<float>(v[1] & 0xffff0000u)};
+        return r;
+    } else {
+        const f16x2 a = bitcast<f16x2>(v[0]);
+        const f16x2 b = bitcast<f16x2>(v[1]);
+        f32x4 r = {(float)a[0], (float)a[1], (float)b[0], (float)b[1]};
+        return r;
+    }
 }
 
 // value of lane (4 * (lane / 4) + T) for every lane of the quad
@@ -279,7 +285,7 @@ __device__ inline void skinny_block(const SkinnyStage<BITS, NT, PER_STEP, AU>& s
             }
         }
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) flush<ACT, BITS>(acc[nt], p[nt], scales4(sl.sc[nt]), psa[0]);
+        for (int nt = 0; nt < NT; ++nt) flush<ACT, BITS>(acc[nt], p[nt], scales4<ACT>(sl.sc[nt]), psa[0]);
     } else {
 #pragma unroll
         for (int t = 0; t < STEPS; ++t) {
@@ -299,7 +305,7 @@ __device__ inline void skinny_block(const SkinnyStage<BITS, NT, PER_STEP, AU>& s
                 if (t == 1) sq = quad_bcast<1>(sl.sc[nt]);
                 if (STEPS > 2 && t == 2) sq = quad_bcast<2 % STEPS>(sl.sc[nt]);
                 if (STEPS > 2 && t == 3) sq = quad_bcast<3 % STEPS>(sl.sc[nt]);
-                flush<ACT, BITS>(acc[nt], p, scales4(sq), psa[0]);
+                flush<ACT, BITS>(acc[nt], p, scales4<ACT>(sq), psa[0]);
             }
         }
     }
@@ -598,11 +604,16 @@ struct DequantScaled<FQ_BF16, 8> {
     }
 };
 
-// scale (binary16 bits) -> the form DequantScaled wants
+template <int BITS>
+struct DequantScaled<FQ_BF16_BS, BITS> : DequantScaled<FQ_BF16, BITS> {};
+
+// stored scale (16 bits) -> the form DequantScaled wants
 template <int ACT>
 __device__ inline uint32_t scale_operand(uint16_t h) {
     if constexpr (ACT == FQ_F16) {
         return (uint32_t)h | ((uint32_t)h << 16);
+    } else if constexpr (ACT == FQ_BF16_BS) {
+        return (uint32_t)h << 16;
     } else {
         return bitcast<uint32_t>((float)bitcast<_Float16>(h));
     }

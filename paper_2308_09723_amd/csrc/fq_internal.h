@@ -8,12 +8,12 @@
 
 #include "../../include/fq.h"
 
-// quantiser side
-int fq_launch_quantize(const void* W, int64_t K, int64_t N, int bits, int g, void* codes, void* scales,
+// quantiser side (sfmt: an fq_scale_format)
+int fq_launch_quantize(const void* W, int64_t K, int64_t N, int bits, int g, int sfmt, void* codes, void* scales,
                        hipStream_t stream);
 int fq_launch_unpack(const void* codes, int64_t K, int64_t N, int bits, int8_t* q, hipStream_t stream);
 int64_t fq_quant_error_blocks(int64_t K, int64_t N);
-int fq_launch_quant_error(const void* W, int64_t K, int64_t N, int bits, int g, const void* codes,
+int fq_launch_quant_error(const void* W, int64_t K, int64_t N, int bits, int g, int sfmt, const void* codes,
                           const void* scales, double* out_host2, void* workspace, hipStream_t stream);
 int fq_launch_choose_group(const void* W, int64_t K, int64_t N, int g_top, int levels, float alpha,
                            int* flags_host, void* workspace, hipStream_t stream);
@@ -33,6 +33,7 @@ struct fq_gemm_plan {
     int tail_tiles, tail_splits, tail_kbs;
 };
 fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g);
+// act: FQ_F16, FQ_BF16, or 2 = bf16 activations with bf16 scales
 int fq_launch_gemm(const void* A, int act, int64_t M, int64_t N, int64_t K, const void* codes,
                    const void* scales, int bits, int g, void* C, void* workspace, hipStream_t stream);
 int fq_launch_gemm_grouped(const void* A, int act, const int32_t* offsets, int E, int64_t N, int64_t K,

@@ -17,13 +17,22 @@ __device__ inline float half_bits_to_float(uint16_t b) {
     return __half2float(__ushort_as_half(b));
 }
 
+// stored scale (16 bits, binary16 or bfloat16) -> binary32
+__device__ inline float scale_bits_to_float(uint16_t b, int sfmt) {
+    return sfmt == FQ_SCALE_BF16 ? __uint_as_float((uint32_t)b << 16) : half_bits_to_float(b);
+}
+
 // Appendix A's scale for a group whose abs-max has the binary16 bit pattern m:
-// the smallest binary16 s with L * s >= 2 m (L = 2^bits - 1), as a bit pattern.
-__device__ inline uint32_t scale_bits_from_absmax_bits(uint32_t m, float L) {
+// the smallest s of the storage format with L * s >= 2 m (L = 2^bits - 1), as a 16-bit pattern.
+// The candidate is the binary32 quotient rounded to nearest (binary16) or cut (bfloat16: at or
+// below the quotient); the products L * candidate are exact in binary32 (8 x 11 bits at most),
+// so one comparison decides whether the next value up is needed.
+__device__ inline uint32_t scale_bits_from_absmax_bits(uint32_t m, float L, int sfmt) {
     const float two_m = 2.0f * half_bits_to_float((uint16_t)m);
     const float t32 = __fdiv_rn(two_m, L);
-    uint32_t tb = __half_as_ushort(__float2half_rn(t32));
-    if (L * half_bits_to_float((uint16_t)tb) < two_m) tb += 1;   // next binary16 up
+    uint32_t tb = sfmt == FQ_SCALE_BF16 ? (__float_as_uint(t32) >> 16)
+                                        : (uint32_t)__half_as_ushort(__float2half_rn(t32));
+    if (__fmul_rn(L, scale_bits_to_float((uint16_t)tb, sfmt)) < two_m) tb += 1;   // next value up
     return tb;
 }
 
@@ -33,7 +42,7 @@ __device__ inline uint32_t scale_bits_from_absmax_bits(uint32_t m, float L) {
 // y-slices split the block's rows and are combined through LDS.
 // ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void fq_scales_kernel(const uint16_t* __restrict__ W, int64_t K,
-                                                        int64_t N, int g, float L,
+                                                        int64_t N, int g, float L, int sfmt,
                                                         uint16_t* __restrict__ scales) {
     __shared__ uint32_t red[4][64];
     const int tx = threadIdx.x, ty = threadIdx.y;
@@ -59,7 +68,7 @@ __global__ __launch_bounds__(256) void fq_scales_kernel(const uint16_t* __restri
                 const uint32_t v = (red[y][tx] >> (16 * c)) & 0xffffu;
                 m = v > m ? v : m;
             }
-            out |= scale_bits_from_absmax_bits(m, L) << (16 * c);
+            out |= scale_bits_from_absmax_bits(m, L, sfmt) << (16 * c);
         }
         *reinterpret_cast<uint32_t*>(scales + grp * N + n) = out;
     }
@@ -70,7 +79,7 @@ __global__ __launch_bounds__(256) void fq_scales_kernel(const uint16_t* __restri
 // kernel folds the g / 128 block maxima of each group into its scale.  One kernel walking a
 // whole 12288-row column per thread slice leaves most of the GPU idle.
 __global__ __launch_bounds__(256) void fq_scales_fold_kernel(const uint16_t* __restrict__ fine, int64_t N,
-                                                             int per_group, float L,
+                                                             int per_group, float L, int sfmt,
                                                              uint16_t* __restrict__ scales) {
     const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (n >= N) return;
@@ -80,7 +89,7 @@ __global__ __launch_bounds__(256) void fq_scales_fold_kernel(const uint16_t* __r
         const uint32_t v = fine[(grp * per_group + i) * N + n];
         m = v > m ? v : m;
     }
-    scales[grp * N + n] = (uint16_t)scale_bits_from_absmax_bits(m, L);
+    scales[grp * N + n] = (uint16_t)scale_bits_from_absmax_bits(m, L, sfmt);
 }
 
 // ---------------------------------------------------------------------------------
@@ -106,7 +115,7 @@ __device__ inline int encode_one(uint16_t wbits, float s, int qmax) {
 // OWN_SCALES = false: the scales were computed before (groups larger than the panel) and are only read.
 template <int BITS, bool OWN_SCALES>
 __global__ __launch_bounds__(256) void fq_quantize_panel_kernel(const uint16_t* __restrict__ W, int64_t K,
-                                                                int64_t N, int g, float L,
+                                                                int64_t N, int g, float L, int sfmt,
                                                                 uint16_t* __restrict__ scales,
                                                                 uint4* __restrict__ codes) {
     constexpr int KBLK = BITS == 4 ? 128 : 64;
@@ -162,8 +171,8 @@ __global__ __launch_bounds__(256) void fq_quantize_panel_kernel(const uint16_t* 
                     const uint32_t a = submax[first + i][c];
                     m = a > m ? a : m;
                 }
-                const uint32_t sbits = scale_bits_from_absmax_bits(m, L);
-                sub_scale[sb][c] = half_bits_to_float((uint16_t)sbits);
+                const uint32_t sbits = scale_bits_from_absmax_bits(m, L, sfmt);
+                sub_scale[sb][c] = scale_bits_to_float((uint16_t)sbits, sfmt);
                 if (sb == first && sb * 32 < rows && c < cols) scales[((k0 + sb * 32) / g) * N + n0 + c] = (uint16_t)sbits;
             }
         }
@@ -174,7 +183,7 @@ __global__ __launch_bounds__(256) void fq_quantize_panel_kernel(const uint16_t* 
         for (int h = 0; h < 2; ++h) {
             const int sb = (tid >> 7) + 2 * h;
             float v = 0.0f;
-            if (sb * 32 < rows && c < cols) v = half_bits_to_float(scales[((k0 + sb * 32) / g) * N + n0 + c]);
+            if (sb * 32 < rows && c < cols) v = scale_bits_to_float(scales[((k0 + sb * 32) / g) * N + n0 + c], sfmt);
             sub_scale[sb][c] = v;
         }
         __syncthreads();
@@ -316,8 +325,8 @@ template <int BITS>
 __global__ __launch_bounds__(256) void fq_quant_error_kernel(const uint16_t* __restrict__ W,
                                                              const uint32_t* __restrict__ codes,
                                                              const uint16_t* __restrict__ scales, int64_t K,
-                                                             int64_t N, int g, double* __restrict__ part,
-                                                             int64_t nblk) {
+                                                             int64_t N, int g, int sfmt,
+                                                             double* __restrict__ part, int64_t nblk) {
     __shared__ double sh_s[256];
     __shared__ double sh_m[256];
     const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -335,7 +344,7 @@ __global__ __launch_bounds__(256) void fq_quant_error_kernel(const uint16_t* __r
                 q = (int)((w >> (8 * (p.e & 3))) & 0xffu) - 128;
             }
             const double wv = (double)half_bits_to_float(W[k * N + n]);
-            const double sv = (double)half_bits_to_float(scales[(k / g) * N + n]);
+            const double sv = (double)scale_bits_to_float(scales[(k / g) * N + n], sfmt);
             const double e = wv - (double)q * sv;
             sse += e * e;
             mx = fmax(mx, fabs(e));
@@ -386,17 +395,17 @@ __global__ __launch_bounds__(256) void fq_quant_error_final_kernel(const double*
 }  // namespace
 
 // ----------------------------------------------------------------------------- launchers
-int fq_launch_quantize(const void* W, int64_t K, int64_t N, int bits, int g, void* codes, void* scales,
+int fq_launch_quantize(const void* W, int64_t K, int64_t N, int bits, int g, int sfmt, void* codes, void* scales,
                        hipStream_t stream) {
     const float L = (float)((1 << bits) - 1);
     if (g == 32 || g == 64 || g == 128) {
         dim3 grid((unsigned)((N + FQ_QP_COLS - 1) / FQ_QP_COLS), (unsigned)((K + FQ_QP_ROWS - 1) / FQ_QP_ROWS));
         if (bits == 4)
             hipLaunchKernelGGL((fq_quantize_panel_kernel<4, true>), grid, dim3(256), 0, stream, (const uint16_t*)W,
-                               K, N, g, L, (uint16_t*)scales, (uint4*)codes);
+                               K, N, g, L, sfmt, (uint16_t*)scales, (uint4*)codes);
         else
             hipLaunchKernelGGL((fq_quantize_panel_kernel<8, true>), grid, dim3(256), 0, stream, (const uint16_t*)W,
-                               K, N, g, L, (uint16_t*)scales, (uint4*)codes);
+                               K, N, g, L, sfmt, (uint16_t*)scales, (uint4*)codes);
         return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;
     }
     if (g >= 1024 && g % 128 == 0) {
@@ -408,11 +417,11 @@ int fq_launch_quantize(const void* W, int64_t K, int64_t N, int bits, int g, voi
         hipLaunchKernelGGL(fq_fine_absmax_kernel, grid, block, 0, stream, (const uint16_t*)W, N, 128, fine);
         dim3 grid2((unsigned)((N + 255) / 256), (unsigned)(K / g));
         hipLaunchKernelGGL(fq_scales_fold_kernel, grid2, dim3(256), 0, stream, (const uint16_t*)fine, N, g / 128, L,
-                           (uint16_t*)scales);
+                           sfmt, (uint16_t*)scales);
     } else {
         dim3 block(64, 4);
         dim3 grid((unsigned)((N + 127) / 128), (unsigned)(K / g));
-        hipLaunchKernelGGL(fq_scales_kernel, grid, block, 0, stream, (const uint16_t*)W, K, N, g, L,
+        hipLaunchKernelGGL(fq_scales_kernel, grid, block, 0, stream, (const uint16_t*)W, K, N, g, L, sfmt,
                            (uint16_t*)scales);
     }
     {
@@ -420,10 +429,10 @@ int fq_launch_quantize(const void* W, int64_t K, int64_t N, int bits, int g, voi
         dim3 grid((unsigned)((N + FQ_QP_COLS - 1) / FQ_QP_COLS), (unsigned)((K + FQ_QP_ROWS - 1) / FQ_QP_ROWS));
         if (bits == 4)
             hipLaunchKernelGGL((fq_quantize_panel_kernel<4, false>), grid, dim3(256), 0, stream, (const uint16_t*)W,
-                               K, N, g, L, (uint16_t*)scales, (uint4*)codes);
+                               K, N, g, L, sfmt, (uint16_t*)scales, (uint4*)codes);
         else
             hipLaunchKernelGGL((fq_quantize_panel_kernel<8, false>), grid, dim3(256), 0, stream, (const uint16_t*)W,
-                               K, N, g, L, (uint16_t*)scales, (uint4*)codes);
+                               K, N, g, L, sfmt, (uint16_t*)scales, (uint4*)codes);
     }
     return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;
 }
@@ -468,7 +477,7 @@ int64_t fq_quant_error_blocks(int64_t K, int64_t N) {
     return ((N + 255) / 256) * ((K + FQ_QE_ROWS - 1) / FQ_QE_ROWS);
 }
 
-int fq_launch_quant_error(const void* W, int64_t K, int64_t N, int bits, int g, const void* codes,
+int fq_launch_quant_error(const void* W, int64_t K, int64_t N, int bits, int g, int sfmt, const void* codes,
                           const void* scales, double* out_host2, void* workspace, hipStream_t stream) {
     // workspace: [out: 2 doubles][partials: 2 * nblk doubles]
     double* out = (double*)workspace;
@@ -477,10 +486,10 @@ int fq_launch_quant_error(const void* W, int64_t K, int64_t N, int bits, int g, 
     dim3 grid((unsigned)((N + 255) / 256), (unsigned)((K + FQ_QE_ROWS - 1) / FQ_QE_ROWS));
     if (bits == 4)
         hipLaunchKernelGGL(fq_quant_error_kernel<4>, grid, dim3(256), 0, stream, (const uint16_t*)W,
-                           (const uint32_t*)codes, (const uint16_t*)scales, K, N, g, part, nblk);
+                           (const uint32_t*)codes, (const uint16_t*)scales, K, N, g, sfmt, part, nblk);
     else
         hipLaunchKernelGGL(fq_quant_error_kernel<8>, grid, dim3(256), 0, stream, (const uint16_t*)W,
-                           (const uint32_t*)codes, (const uint16_t*)scales, K, N, g, part, nblk);
+                           (const uint32_t*)codes, (const uint16_t*)scales, K, N, g, sfmt, part, nblk);
     hipLaunchKernelGGL(fq_quant_error_final_kernel, dim3(1), dim3(256), 0, stream, (const double*)part, nblk, out);
     if (hipGetLastError() != hipSuccess) return FQ_ERR_HIP;
     if (hipMemcpyAsync(out_host2, out, sizeof(double) * 2, hipMemcpyDeviceToHost, stream) != hipSuccess)

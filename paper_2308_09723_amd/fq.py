@@ -19,6 +19,8 @@ FQ_ERR_WORKSPACE = 3
 FQ_ERR_HIP = 4
 FQ_F16 = 0
 FQ_BF16 = 1
+FQ_SCALE_F16 = 0
+FQ_SCALE_BF16 = 1
 
 _lib = None
 
@@ -57,6 +59,12 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "fq_gemm": (i32, [vp, i32, i64, i64, i64, vp, vp, i32, i32, vp, vp, sz, vp]),
         "fq_gemm_grouped": (i32, [vp, i32, ctypes.POINTER(ctypes.c_int32), i32, i64, i64, vp, vp, i32, i32,
                                   vp, vp, sz, vp]),
+        "fq_quantize_sf": (i32, [vp, i64, i64, i32, i32, i32, vp, vp, vp]),
+        "fq_quant_error_sf": (i32, [vp, i64, i64, i32, i32, i32, vp, vp, ctypes.POINTER(ctypes.c_double),
+                                    ctypes.POINTER(ctypes.c_double), vp, sz, vp]),
+        "fq_gemm_sf": (i32, [vp, i32, i64, i64, i64, vp, vp, i32, i32, i32, vp, vp, sz, vp]),
+        "fq_gemm_grouped_sf": (i32, [vp, i32, ctypes.POINTER(ctypes.c_int32), i32, i64, i64, vp, vp, i32, i32, i32,
+                                     vp, vp, sz, vp]),
         "fq_gemm_describe": (i32, [i64, i64, i64, i32, i32, ctypes.c_char_p, sz]),
         "fq_status_string": (ctypes.c_char_p, [i32]),
         "fq_version": (ctypes.c_char_p, []),
@@ -74,6 +82,7 @@ EXPORTED = [
     "fq_choose_group_workspace_bytes", "fq_quantize", "fq_unpack", "fq_choose_group", "fq_gemm",
     "fq_gemm_grouped", "fq_gemm_describe", "fq_status_string", "fq_version",
     "fq_quant_error_workspace_bytes", "fq_quant_error",
+    "fq_quantize_sf", "fq_quant_error_sf", "fq_gemm_sf", "fq_gemm_grouped_sf",
 ]
 
 
@@ -114,6 +123,10 @@ def quantize_raw(W_ptr, K, N, bits, group_size, codes_ptr, scales_ptr, stream=0)
     return int(load().fq_quantize(W_ptr, K, N, bits, group_size, codes_ptr, scales_ptr, stream))
 
 
+def quantize_sf_raw(W_ptr, K, N, bits, group_size, scale_format, codes_ptr, scales_ptr, stream=0):
+    return int(load().fq_quantize_sf(W_ptr, K, N, bits, group_size, scale_format, codes_ptr, scales_ptr, stream))
+
+
 def unpack_raw(codes_ptr, K, N, bits, q_ptr, stream=0):
     return int(load().fq_unpack(codes_ptr, K, N, bits, q_ptr, stream))
 
@@ -137,10 +150,25 @@ def quant_error_raw(W_ptr, K, N, bits, group_size, codes_ptr, scales_ptr, ws_ptr
     return st, sse.value, mx.value
 
 
+def quant_error_sf_raw(W_ptr, K, N, bits, group_size, scale_format, codes_ptr, scales_ptr, ws_ptr, ws_bytes,
+                       stream=0):
+    sse = ctypes.c_double(-1.0)
+    mx = ctypes.c_double(-1.0)
+    st = int(load().fq_quant_error_sf(W_ptr, K, N, bits, group_size, scale_format, codes_ptr, scales_ptr,
+                                      ctypes.byref(sse), ctypes.byref(mx), ws_ptr, ws_bytes, stream))
+    return st, sse.value, mx.value
+
+
 def gemm_raw(A_ptr, act_dtype, M, N, K, codes_ptr, scales_ptr, bits, group_size, C_ptr, ws_ptr, ws_bytes,
              stream=0):
     return int(load().fq_gemm(A_ptr, act_dtype, M, N, K, codes_ptr, scales_ptr, bits, group_size, C_ptr,
                               ws_ptr, ws_bytes, stream))
+
+
+def gemm_sf_raw(A_ptr, act_dtype, M, N, K, codes_ptr, scales_ptr, scale_format, bits, group_size, C_ptr, ws_ptr,
+                ws_bytes, stream=0):
+    return int(load().fq_gemm_sf(A_ptr, act_dtype, M, N, K, codes_ptr, scales_ptr, scale_format, bits, group_size,
+                                 C_ptr, ws_ptr, ws_bytes, stream))
 
 
 def gemm_grouped_raw(A_ptr, act_dtype, offsets, N, K, codes_ptr, scales_ptr, bits, group_size, C_ptr,
@@ -149,6 +177,14 @@ def gemm_grouped_raw(A_ptr, act_dtype, offsets, N, K, codes_ptr, scales_ptr, bit
     arr = (ctypes.c_int32 * (E + 1))(*[int(o) for o in offsets])
     return int(load().fq_gemm_grouped(A_ptr, act_dtype, arr, E, N, K, codes_ptr, scales_ptr, bits, group_size,
                                       C_ptr, ws_ptr, ws_bytes, stream))
+
+
+def gemm_grouped_sf_raw(A_ptr, act_dtype, offsets, N, K, codes_ptr, scales_ptr, scale_format, bits, group_size,
+                        C_ptr, ws_ptr=None, ws_bytes=0, stream=0):
+    E = len(offsets) - 1
+    arr = (ctypes.c_int32 * (E + 1))(*[int(o) for o in offsets])
+    return int(load().fq_gemm_grouped_sf(A_ptr, act_dtype, arr, E, N, K, codes_ptr, scales_ptr, scale_format, bits,
+                                         group_size, C_ptr, ws_ptr, ws_bytes, stream))
 
 
 # ------------------------------------------------------------------ torch-tensor conveniences
@@ -173,8 +209,20 @@ def _act_code(t):
     raise TypeError("activations must be float16 or bfloat16")
 
 
-def quantize(W, bits, group_size):
-    """W: cuda float16 [K, N] -> (codes uint8 [K*N*bits/8], scales float16 [K/g, N])."""
+def _scale_format_of(scales):
+    """The fq_scale_format a scale tensor's dtype stands for."""
+    import torch
+
+    if scales.dtype == torch.float16:
+        return FQ_SCALE_F16
+    if scales.dtype == torch.bfloat16:
+        return FQ_SCALE_BF16
+    raise TypeError("scales must be float16 or bfloat16")
+
+
+def quantize(W, bits, group_size, scale_format=FQ_SCALE_F16):
+    """W: cuda float16 [K, N] -> (codes uint8 [K*N*bits/8], scales [K/g, N] float16, or bfloat16 for
+    scale_format=FQ_SCALE_BF16)."""
     import torch
 
     assert W.is_cuda and W.dtype == torch.float16 and W.is_contiguous()
@@ -185,9 +233,10 @@ def quantize(W, bits, group_size):
     if nbytes == 0 or sbytes == 0:
         raise FqError(FQ_ERR_INVALID_ARG, "fq_quantize")
     codes = torch.empty(nbytes, dtype=torch.uint8, device=W.device)
-    scales = torch.empty((K // g, N), dtype=torch.float16, device=W.device)
-    _check(quantize_raw(W.data_ptr(), K, N, bits, group_size, codes.data_ptr(), scales.data_ptr(), _stream()),
-           "fq_quantize")
+    sdtype = torch.bfloat16 if scale_format == FQ_SCALE_BF16 else torch.float16
+    scales = torch.empty((K // g, N), dtype=sdtype, device=W.device)
+    _check(quantize_sf_raw(W.data_ptr(), K, N, bits, group_size, scale_format, codes.data_ptr(), scales.data_ptr(),
+                           _stream()), "fq_quantize_sf")
     return codes, scales
 
 
@@ -218,9 +267,9 @@ def quant_error(W, codes, scales, bits, group_size):
     K, N = W.shape
     ws_bytes = quant_error_workspace_bytes(K, N)
     ws = torch.empty(max(ws_bytes, 16), dtype=torch.uint8, device=W.device)
-    st, sse, mx = quant_error_raw(W.data_ptr(), K, N, bits, group_size, codes.data_ptr(), scales.data_ptr(),
-                                  ws.data_ptr(), ws_bytes, _stream())
-    _check(st, "fq_quant_error")
+    st, sse, mx = quant_error_sf_raw(W.data_ptr(), K, N, bits, group_size, _scale_format_of(scales),
+                                     codes.data_ptr(), scales.data_ptr(), ws.data_ptr(), ws_bytes, _stream())
+    _check(st, "fq_quant_error_sf")
     return sse, mx
 
 
@@ -237,8 +286,9 @@ def gemm(A, codes, scales, bits, group_size, out=None, workspace=None):
         workspace = torch.empty(need, dtype=torch.uint8, device=A.device)
     ws_ptr = workspace.data_ptr() if workspace is not None else None
     ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
-    _check(gemm_raw(A.data_ptr(), _act_code(A), M, N, K, codes.data_ptr(), scales.data_ptr(), bits, group_size,
-                    C.data_ptr(), ws_ptr, ws_bytes, _stream()), "fq_gemm")
+    _check(gemm_sf_raw(A.data_ptr(), _act_code(A), M, N, K, codes.data_ptr(), scales.data_ptr(),
+                       _scale_format_of(scales), bits, group_size, C.data_ptr(), ws_ptr, ws_bytes, _stream()),
+           "fq_gemm_sf")
     return C
 
 
@@ -248,6 +298,7 @@ def gemm_grouped(A, offsets, codes, scales, bits, group_size, N, out=None):
 
     rows, K = A.shape
     C = out if out is not None else torch.empty((rows, N), dtype=A.dtype, device=A.device)
-    _check(gemm_grouped_raw(A.data_ptr(), _act_code(A), offsets, N, K, codes.data_ptr(), scales.data_ptr(), bits,
-                            group_size, C.data_ptr(), None, 0, _stream()), "fq_gemm_grouped")
+    _check(gemm_grouped_sf_raw(A.data_ptr(), _act_code(A), offsets, N, K, codes.data_ptr(), scales.data_ptr(),
+                               _scale_format_of(scales), bits, group_size, C.data_ptr(), None, 0, _stream()),
+           "fq_gemm_grouped_sf")
     return C

@@ -108,6 +108,38 @@ def test_grouped_and_heuristic_argument_checks():
     assert fq.status_string(99) == "FQ_ERR_UNKNOWN"
 
 
+def test_scale_format_argument_checks():
+    """The *_sf entry points: unknown formats are invalid, bf16 scales go with bf16 activations only, and
+    the plain entry points are the binary16 format."""
+    F16, BF16 = fq.FQ_SCALE_F16, fq.FQ_SCALE_BF16
+    assert fq.quantize_sf_raw(16, 1024, 1024, 4, 128, 2, 16, 16) == fq.FQ_ERR_INVALID_ARG
+    assert fq.quantize_sf_raw(16, 1024, 1024, 4, 128, -1, 16, 16) == fq.FQ_ERR_INVALID_ARG
+    assert fq.quantize_sf_raw(None, 1024, 1024, 4, 128, BF16, 16, 16) == fq.FQ_ERR_INVALID_ARG
+    assert fq.quantize_sf_raw(16, 1024, 1000, 4, 128, BF16, 16, 16) == fq.FQ_ERR_UNSUPPORTED
+
+    def gemm(act, sf, **kw):
+        a = dict(A=16, M=4, N=1024, K=1024, codes=16, scales=16, bits=4, g=128, C=16)
+        a.update(kw)
+        return fq.gemm_sf_raw(a["A"] or None, act, a["M"], a["N"], a["K"], a["codes"], a["scales"], sf, a["bits"],
+                              a["g"], a["C"], 16, 1 << 30)
+
+    assert gemm(fq.FQ_F16, BF16) == fq.FQ_ERR_UNSUPPORTED
+    assert gemm(fq.FQ_F16, BF16, M=0) == fq.FQ_ERR_UNSUPPORTED        # refused whatever the size
+    assert gemm(fq.FQ_BF16, 5) == fq.FQ_ERR_INVALID_ARG
+    assert gemm(9, F16) == fq.FQ_ERR_INVALID_ARG
+    assert gemm(fq.FQ_BF16, BF16, A=0) == fq.FQ_ERR_INVALID_ARG
+    assert gemm(fq.FQ_BF16, BF16, M=0, A=0) == fq.FQ_OK
+    assert gemm(fq.FQ_BF16, BF16, g=96) == fq.FQ_ERR_INVALID_ARG
+    st = fq.gemm_grouped_sf_raw(16, fq.FQ_F16, [0, 4], 1024, 1024, 16, 16, BF16, 4, 64, 16)
+    assert st == fq.FQ_ERR_UNSUPPORTED
+    st = fq.gemm_grouped_sf_raw(16, fq.FQ_BF16, [0, 4, 2], 1024, 1024, 16, 16, BF16, 4, 64, 16)
+    assert st == fq.FQ_ERR_INVALID_ARG
+    st = fq.gemm_grouped_sf_raw(None, fq.FQ_BF16, [0, 0], 1024, 1024, 16, 16, BF16, 4, 64, None)
+    assert st == fq.FQ_OK
+    assert fq.quant_error_sf_raw(16, 1024, 1024, 4, 128, 3, 16, 16, 16, 1 << 20)[0] == fq.FQ_ERR_INVALID_ARG
+    assert fq.quant_error_sf_raw(16, 1024, 1024, 4, 128, BF16, 16, 16, None, 0)[0] == fq.FQ_ERR_WORKSPACE
+
+
 def test_quant_error_argument_checks():
     """Validation precedes every launch, so these calls never touch a GPU."""
     assert fq.quant_error_workspace_bytes(0, 16) == 0

@@ -92,7 +92,8 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
         none.count = 0;
 #define FQ_MMA_LAUNCH_SR(MT_, W_, PIPE_, SR_)                                                            \
     do {                                                                                                \
-        auto kern = fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, SR_, false, PIPE_>;                 \
+        auto kern = fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, SR_, false, PIPE_,                  \
+                                       use_post(ACT, BITS, MT_, SR_, PIPE_)>;                                 \
         if (lds > 65536) {                                                                              \
             static bool raised = false;                                                                 \
             if (!raised) {                                                                              \
@@ -171,7 +172,8 @@ int launch_grouped_typed(const void* A, const int32_t* offsets, int E, int64_t N
             dim3 grid((unsigned)((int64_t)nblocks_n * items.count));
 #define FQ_GROUPED_LAUNCH_SR(MT_, W_, PIPE_, SR_)                                                        \
     do {                                                                                                \
-        auto kern = fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, SR_, true, PIPE_>;                  \
+        auto kern = fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, SR_, true, PIPE_,                   \
+                                       use_post(ACT, BITS, MT_, SR_, PIPE_)>;                                 \
         if (lds > 65536) {                                                                              \
             static bool raised = false;                                                                 \
             if (!raised) {                                                                              \

@@ -21,6 +21,7 @@
 
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <type_traits>
 
 #include "fq_internal.h"
 #include "fq_layout.h"
@@ -664,8 +665,8 @@ __device__ inline void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
-template <int ACT, int BITS, int MT, int NT, int WAVES, int SR, bool GROUPED, int PIPE>
-__global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
+template <int ACT, int BITS, int MT, int NT, int WAVES, int SR, bool GROUPED, int PIPE, bool POST = false>
+__global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT == FQ_F16) ? 3 : 1) void fq_gemm_mma_kernel(
     const uint16_t* __restrict__ A, const u32x4* __restrict__ codes, const uint16_t* __restrict__ scales,
     uint16_t* __restrict__ C, float* __restrict__ partial, int M, int N, int K, int g, int kb_per_split,
     int splits, int nblocks_n, int nblocks_m, int64_t codes_stride16, int64_t scales_stride,
@@ -789,16 +790,31 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
     u32x4 wq[NT], wq_n[NT], areg[UPT];
     // Scale registers: one per (scale row, column tile), or, with four scale rows per k-block,
     // two rows per register (low / high half, filled by 16-bit loads into register halves).
-    constexpr int SPK = SROWS >= 4 ? 2 : 1;      // scale rows packed per register
+    // POST (few rows per block, where the conversion and not the matrix pipe sets the pace): the codes
+    // are converted without their scale (half the vector instructions for bf16), each scale group
+    // is accumulated apart and folded into the result as acc += s * (p - OFFSET * rowsum), the row
+    // sums of the activations coming from one more MFMA against an all-ones operand.  A lane then
+    // needs the scales of its four output columns 4j .. 4j+3: one 8-byte register pair per (scale
+    // row, column tile).
+    static_assert(!POST || PIPE > 0, "the post-scaled form exists in the pipelined kernel only");
+    constexpr int SPK = (!POST && SROWS >= 4) ? 2 : 1;      // scale rows packed per register
     constexpr int SREG = SROWS / SPK;
     typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
-    uint32_t sc[SREG][NT], sc_n[SREG][NT];
-    auto load_w = [&](u32x4 (&q)[NT], uint32_t (&s)[SREG][NT], int kb) {
+    typedef typename std::conditional<POST, u32x2, uint32_t>::type SC;
+    SC sc[SREG][NT], sc_n[SREG][NT];
+    auto load_q = [&](u32x4 (&q)[NT], int kb) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) q[nt] = (wbase[nt] + (int64_t)kb * kb_stride)[lane];
+    };
+    auto load_s = [&](SC (&s)[SREG][NT], int kb) {
 #pragma unroll
         for (int r = 0; r < SREG; ++r) {
-            if constexpr (SPK == 1) {
+            if constexpr (POST) {
+                const int64_t srow = (int64_t)((kb * KBLK + r * (KBLK / SROWS)) / g) * N;
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    s[r][nt] = *reinterpret_cast<const u32x2*>(sbase[nt] + srow + 4 * j);
+            } else if constexpr (SPK == 1) {
                 const int64_t srow = (int64_t)((kb * KBLK + r * (KBLK / SROWS)) / g) * N;
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) s[r][nt] = sbase[nt][srow + ml];
@@ -815,6 +831,10 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
             }
         }
     };
+    auto load_w = [&](u32x4 (&q)[NT], SC (&s)[SREG][NT], int kb) {
+        load_q(q, kb);
+        load_s(s, kb);
+    };
     auto load_a = [&](int kb) {
         const uint16_t* base = Arow + (int64_t)kb * KBLK;
 #pragma unroll
@@ -828,18 +848,25 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
         for (int r = 0; r < UPT; ++r)
             if (a_dst[r] >= 0) dst[a_dst[r]] = a_ok[r] ? areg[r] : zero4;
     };
-    auto convert = [&](const u32x4 (&q)[NT], const uint32_t (&s)[SREG][NT], int t, int nt) -> u32x4 {
-        // opaque until here: otherwise the widening of the scale is moved to the end of the previous
-        // k-block, and with it the wait for the scale's load
-        const int srow = t / (STEPS / SROWS);
-        uint32_t h = s[srow / SPK][nt];
-        asm volatile("" : "+v"(h));
-        if (SPK == 2 && (srow & 1)) h >>= 16;
-        const uint32_t s2 = scale_operand<ACT>((uint16_t)h);
-        if (t == 0) return DequantScaled<ACT, BITS>::template run<0>(q[nt], magic, s2);
-        if (t == 1) return DequantScaled<ACT, BITS>::template run<1>(q[nt], magic, s2);
-        if (STEPS > 2 && t == 2) return DequantScaled<ACT, BITS>::template run<2 % STEPS>(q[nt], magic, s2);
-        return DequantScaled<ACT, BITS>::template run<3 % STEPS>(q[nt], magic, s2);
+    auto convert = [&](const u32x4 (&q)[NT], const SC (&s)[SREG][NT], int t, int nt) -> u32x4 {
+        if constexpr (POST) {
+            if (t == 0) return Dequant<ACT, BITS>::template run<0>(q[nt], magic);
+            if (t == 1) return Dequant<ACT, BITS>::template run<1>(q[nt], magic);
+            if (STEPS > 2 && t == 2) return Dequant<ACT, BITS>::template run<2 % STEPS>(q[nt], magic);
+            return Dequant<ACT, BITS>::template run<3 % STEPS>(q[nt], magic);
+        } else {
+            // opaque until here: otherwise the widening of the scale is moved to the end of the previous
+            // k-block, and with it the wait for the scale's load
+            const int srow = t / (STEPS / SROWS);
+            uint32_t h = s[srow / SPK][nt];
+            asm volatile("" : "+v"(h));
+            if (SPK == 2 && (srow & 1)) h >>= 16;
+            const uint32_t s2 = scale_operand<ACT>((uint16_t)h);
+            if (t == 0) return DequantScaled<ACT, BITS>::template run<0>(q[nt], magic, s2);
+            if (t == 1) return DequantScaled<ACT, BITS>::template run<1>(q[nt], magic, s2);
+            if (STEPS > 2 && t == 2) return DequantScaled<ACT, BITS>::template run<2 % STEPS>(q[nt], magic, s2);
+            return DequantScaled<ACT, BITS>::template run<3 % STEPS>(q[nt], magic, s2);
+        }
     };
 
     constexpr int NFR = STEPS * MT;
@@ -919,16 +946,23 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
         for (int t = 0; t < STEPS; ++t) a_rd[t] = ml * KC + ((4 * t + j) ^ swz(ml));
 
         u32x4 wqs[D][NT];
-        uint32_t scs[D][SREG][NT];
+        SC scs[D][SREG][NT];
+        // POST: partial sums of the scale group at hand and the activations' row sums over it
+        f32x4 pg[POST ? MT : 1][POST ? NT : 1], rsum[POST ? MT : 1];
+        const f32x4 fzero = {0.f, 0.f, 0.f, 0.f};
+        constexpr int GSTEPS = STEPS / SROWS;           // k-steps per scale row
         int cur = 0;
         if (kb0 < kb1) {
             // same issue order as inside the loop, so that the wait counts below hold from the start
+            // (POST: the codes are reloaded at W_SLOT, the scales after the last fold of the k-block)
 #pragma unroll
             for (int u = 0; u < D; ++u) {
                 const int kbu = kb0 + u < kb1 ? kb0 + u : kb1 - 1;
-                if (W_FIRST) load_w(wqs[u], scs[u], kbu);
+                if (W_FIRST) load_q(wqs[u], kbu);
+                if (W_FIRST && !POST) load_s(scs[u], kbu);
                 load_a_lds(kbu, u);
-                if (!W_FIRST) load_w(wqs[u], scs[u], kbu);
+                if (!W_FIRST) load_q(wqs[u], kbu);
+                if (!W_FIRST || POST) load_s(scs[u], kbu);
             }
             wait_vmcnt<(D - 1) * (NWLOADS + DPT)>();   // tile 0 and weight set 0 have landed
             __syncthreads();
@@ -938,8 +972,15 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
             for (int nt = 0; nt < NT; ++nt) w[0][nt] = convert(wqs[0], scs[0], 0, nt);
         }
         // one k-block; (qa, sa) hold its weights, (qb, sb) those of the next one
-        auto kblock = [&](int kb, u32x4 (&qa)[NT], uint32_t (&sa)[SREG][NT], u32x4 (&qb)[NT],
-                          uint32_t (&sb)[SREG][NT]) {
+        auto fold = [&](const SC (&sa)[SREG][NT], int srow, int mt) {
+            if constexpr (POST) {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    flush<ACT, BITS>(acc[mt][nt], pg[mt][nt], scales4<ACT>(sa[srow][nt]), rsum[mt][0]);
+            }
+        };
+        auto kblock = [&](int kb, u32x4 (&qa)[NT], SC (&sa)[SREG][NT], u32x4 (&qb)[NT],
+                          SC (&sb)[SREG][NT]) {
             const int nxt = cur == D ? 0 : cur + 1;
             const int last = cur == 0 ? D : cur - 1;     // the tile read during kb - 1
             const u32x4* abuf = lds + cur * abuf_units;
@@ -950,7 +991,10 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
 #pragma unroll
                 for (int mt = 0; mt < MT; ++mt) {
                     const int i = t * MT + mt;
-                    if (i == W_SLOT) load_w(qa, sa, kb + D < kb1 ? kb + D : kb1 - 1);
+                    if (i == W_SLOT) {
+                        if constexpr (POST) load_q(qa, kb + D < kb1 ? kb + D : kb1 - 1);
+                        else load_w(qa, sa, kb + D < kb1 ? kb + D : kb1 - 1);
+                    }
                     if (i == BAR_SLOT) {
                         // this wave's share of tile kb + 1 has landed once at most the loads issued
                         // after it are still in flight
@@ -973,9 +1017,28 @@ __global__ __launch_bounds__(WAVES * 64) void fq_gemm_mma_kernel(
                     // sinks them next to their uses and every fragment is then waited for
                     __builtin_amdgcn_sched_barrier(0);
                     const u32x4 a = afr[i % (APD + 1)];
+                    if constexpr (POST) {
+                        const bool first = t % GSTEPS == 0;
 #pragma unroll
-                    for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = mfma16x16x32<ACT>(w[t & 1][nt], a, acc[mt][nt]);
+                        for (int nt = 0; nt < NT; ++nt)
+                            pg[mt][nt] = mfma16x16x32<ACT>(w[t & 1][nt], a, first ? fzero : pg[mt][nt]);
+                        if constexpr (Dequant<ACT, BITS>::OFFSET != 0.0f)
+                            rsum[mt] = mfma16x16x32<ACT>(ones_operand<ACT>(), a, first ? fzero : rsum[mt]);
+                        // the group that ended in the slot before this one is folded in now, behind this
+                        // slot's MFMAs, so that the fold does not wait for the matrix pipe
+                        if (i > 0) {
+                            const int tp = (i - 1) / MT, mp = (i - 1) % MT;
+                            if ((tp + 1) % GSTEPS == 0) fold(sa, tp / GSTEPS, mp);
+                        }
+                    } else {
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = mfma16x16x32<ACT>(w[t & 1][nt], a, acc[mt][nt]);
+                    }
                 }
+            }
+            if constexpr (POST) {
+                fold(sa, SROWS - 1, MT - 1);
+                load_s(sa, kb + D < kb1 ? kb + D : kb1 - 1);
             }
             cur = nxt;
         };

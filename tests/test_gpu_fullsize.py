@@ -78,6 +78,8 @@ def test_opt175b_prefill_full_size_bf16():
     _check_layer(W, 4, g_pick, cases, cols, "out_proj")
     _check_layer(W, 8, 0, cases[1:3], cols, "out_proj")
     _check_layer(W, 4, 256 if g_pick != 256 else 128, [(512, "bf16", 35)], cols, "out_proj")
+    # the 32- and 64-row blocks in their post-scaled form (one scale row per k-block), both activation types
+    _check_layer(W, 4, 128, [(32, "f16", 36), (64, "f16", 37), (32, "bf16", 38), (64, "bf16", 39)], cols, "out_proj")
 
 
 def test_heavy_tailed_stress_layer_full_size():

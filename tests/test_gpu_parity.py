@@ -330,7 +330,8 @@ def _grouped_case(dtype, bits, g, K, N, rows, seed, shared_weights=False):
             assert_gemm_close(C[sl], C_ref[sl], dtype, f"expert {e} ({rows[e]} rows)")
 
 
-@pytest.mark.parametrize("dtype,bits,g", [("f16", 4, 64), ("bf16", 4, 128), ("bf16", 8, 32), ("f16", 8, 0)])
+@pytest.mark.parametrize("dtype,bits,g", [("f16", 4, 64), ("bf16", 4, 128), ("bf16", 8, 32), ("f16", 8, 0),
+                                          ("f16", 4, 128), ("bf16", 4, 64), ("f16", 4, 0)])
 def test_grouped_gemm_tile_boundaries(dtype, bits, g):
     """Row counts on both sides of every row-tile size (32 / 64 / 128) and several column blocks with a
     ragged last one for both the 4-wave (192 columns) and the 8-wave (384 columns) block shapes."""

@@ -258,6 +258,7 @@ def main():
         out["extra_moe"] = moe_section(torch, fq, workloads)
         out["extra_stress"] = stress_section(torch, fq, workloads)
         out["extra_quantize"] = quantize_section(torch, fq, workloads)
+        out["extra_bf16_scales"] = bf16_scales_section(torch, fq, workloads)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
@@ -380,6 +381,42 @@ def quantize_section(torch, fq, workloads):
     t0 = time.perf_counter()
     gsel = fq.choose_group(W, 0, 32, 0.9)
     res["choose_group_alpha0.9"] = {"ms": round((time.perf_counter() - t0) * 1e3, 4), "group_size": gsel}
+    return res
+
+
+def bf16_scales_section(torch, fq, workloads):
+    """The bfloat16 scale format (scales of the activation's type) on the QKV-shaped int4 matrix with bf16
+    activations, next to the binary16 format: quantiser time and products at M = 8, 32 and 2048."""
+    K, N = workloads.OPT175B_LAYERS["qkv"]
+    W = make_weight(torch, K, N, 100)
+    stream = torch.cuda.current_stream().cuda_stream
+    res = {}
+    for tag, sf in (("f16_scales", fq.FQ_SCALE_F16), ("bf16_scales", fq.FQ_SCALE_BF16)):
+        codes = torch.empty(fq.codes_bytes(K, N, BITS), dtype=torch.uint8, device="cuda")
+        scales = torch.empty((K // GROUP, N), dtype=torch.bfloat16 if sf else torch.float16, device="cuda")
+
+        def quant():
+            st = fq.quantize_sf_raw(W.data_ptr(), K, N, BITS, GROUP, sf, codes.data_ptr(), scales.data_ptr(), stream)
+            if st != fq.FQ_OK:
+                raise fq.FqError(st, "fq_quantize_sf")
+        res[f"quantize_{tag}"] = {"ms": round(_timed(torch, quant), 4)}
+        sse, mx = fq.quant_error(W, codes, scales, BITS, GROUP)
+        res[f"quantize_{tag}"]["mse"] = sse / (K * N)
+        for M in (8, 32, 2048):
+            A = torch.randn((M, K), device="cuda", dtype=torch.float32).to(torch.bfloat16)
+            C = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)
+            need = fq.gemm_workspace_bytes(M, N, K, BITS, GROUP)
+            ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+
+            def run():
+                st = fq.gemm_sf_raw(A.data_ptr(), fq.FQ_BF16, M, N, K, codes.data_ptr(), scales.data_ptr(), sf, BITS,
+                                    GROUP, C.data_ptr(), ws.data_ptr(), ws.numel(), stream)
+                if st != fq.FQ_OK:
+                    raise fq.FqError(st, "fq_gemm_sf")
+            ms = _timed(torch, run)
+            wbytes = codes.numel() + scales.numel() * 2
+            res[f"M{M}_{tag}"] = {"us": round(ms * 1e3, 2), "weight_TBps": round(wbytes / ms / 1e9, 3),
+                                  "TFLOPs": round(2.0 * M * N * K / ms / 1e9, 1)}
     return res
 
 

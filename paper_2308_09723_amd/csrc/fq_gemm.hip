@@ -28,7 +28,6 @@ FQ_DECLARE_GEMM(2, 4)   // bf16 activations, bf16 scales
 FQ_DECLARE_GEMM(2, 8)
 
 fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
-    (void)g;
     fq_gemm_plan p = {};
     const int kblk = fq_kblk(bits);
     const int KB = (int)(K / kblk);
@@ -93,83 +92,109 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
         }
         p.kb_per_split = 0;
     } else {
-        // Tiled MFMA kernel: BM = 16 * mt rows per block, 48 columns per wave, 4 or 8 waves, and
-        // optionally a split of K over `splits` blocks whose binary32 partial tiles a second kernel
-        // adds.  The block shape is the one that minimises a measured cost model:
+        // Tiled MFMA kernel: BM = 16 * mt rows per block (mt = 2, 4 or 8), 48 columns per wave, 4 or 8
+        // waves, and optionally a split of K over `splits` blocks whose binary32 partial tiles a second
+        // kernel adds.  The block shape is the one that minimises a measured cost model:
         //   time = ceil(blocks / 256) * k-blocks per block * u(mt, waves)  +  cost of the partials
         // where u is the time one block spends on one k-block of 128 rows of K when every compute
-        // unit holds its share of blocks (microseconds, fitted to sweeps over the OPT-175B shapes at
-        // M = 32 ... 2048), and the partials cost their write plus read at ~4 TB/s plus a launch.
+        // unit holds its share of blocks (microseconds), and the partials cost their write plus read
+        // at ~5 TB/s plus a launch.  The constants are a least-squares fit (of log time; rms error
+        // 9 - 11 %) to exhaustive sweeps of (mt, waves, splits) over the OPT-175B shapes at M = 17 ...
+        // 256, both activation types, separately for the four kinds of kernels the dispatch
+        // distinguishes (4-bit codes with 1, 2 or 4 scale rows per k-block, of which only the first
+        // runs post-scaled at every small shape; 8-bit codes): the model's choice is 0.5 - 2 % slower
+        // than the sweep's best on average, 15 % at worst.
+        // Up to 256 rows the smaller blocks compete with the 128-row ones (several row blocks, each
+        // converting the weights again) and often win there, e.g. QKV at M = 128 in two 64-row blocks
+        // and no split of K; beyond 256 rows only the 128-row shapes are candidates.
         p.kind = 1;
-        p.mt = M <= 32 ? 2 : (M <= 64 ? 4 : 8);
-        const int bm = p.mt * 16;
-        const int64_t nbm = (M + bm - 1) / bm;
-        const double u8 = p.mt == 8 ? 2.6 : (p.mt == 4 ? 1.7 : 1.3);
-        const double u4 = p.mt == 8 ? 1.43 : (p.mt == 4 ? 0.92 : 0.77);
-        const double kscale = (double)kblk / 128.0;
+        //   u8(mt=2) u4(mt=2) u8(mt=4) u4(mt=4) u8(mt=8) u4(mt=8)  lone 4-wave block factor (mt < 8, mt = 8)
+        static const double consts[4][8] = {
+            {0.99, 0.506, 1.43, 0.83, 2.33, 1.43, 1.2, 1.2},     // 4-bit, one scale row per k-block
+            {1.17, 0.634, 1.60, 0.884, 2.34, 1.46, 1.2, 1.2},    // 4-bit, two scale rows
+            {1.64, 0.731, 2.16, 1.29, 2.70, 1.57, 1.5, 1.35},    // 4-bit, four scale rows
+            {1.73, 0.77, 1.73, 1.035, 2.50, 1.47, 1.2, 1.35}};   // 8-bit
+        const int sr4 = g % 128 == 0 ? 1 : (128 % g == 0 ? 128 / g : 4);
+        const double* cs = consts[bits == 8 ? 3 : (sr4 == 1 ? 0 : (sr4 == 2 ? 1 : 2))];
         const int split_opts[6] = {1, 2, 3, 4, 6, 8};
+        const double kscale = (double)kblk / 128.0;
         double best = 1e30;
         p.tail_tiles = 0;
         p.tail_splits = 1;
         p.tail_kbs = 0;
-        for (int waves = 8; waves >= 4; waves -= 4) {
-            const int64_t nbn = (ntiles + waves * MMA_NT - 1) / (waves * MMA_NT);
-            const double u = (waves == 8 ? u8 : u4) * kscale;
-            for (int si = 0; si < 6; ++si) {
-                int splits = split_opts[si];
-                if (splits > KB) break;
-                const int kbs = (KB + splits - 1) / splits;
-                splits = (KB + kbs - 1) / kbs;
-                const int64_t blocks = nbn * nbm * splits;
-                const int64_t per_cu = (blocks + 255) / 256;
-                double t = (double)per_cu * kbs * u;
-                if (waves == 4) {
-                    // u is a 4-wave block's share when `cap` of them run together on a compute unit; the
-                    // ones left over run with idle SIMDs and take longer than that share (measured: a
-                    // lone block 1.35x (128 rows) to 1.5x, one added to full groups 1.13x)
-                    const int cap = p.mt == 2 ? 3 : 2;
-                    const int64_t left = per_cu % cap;
-                    if (left > 0) {
-                        const double f = per_cu < cap ? (p.mt == 8 ? 1.35 : 1.48) : (p.mt == 8 ? 1.13 : 1.0);
-                        t += (f - 1.0) * (double)left * kbs * u;
+        for (int mt = 8; mt >= 2; mt /= 2) {
+            // a block shape is a candidate when the matrix has more rows than half its height (the
+            // smallest always is), and the small ones only up to 256 rows
+            if (mt > 2 && (int64_t)mt * 8 >= M) continue;
+            if (mt < 8 && M > 256) continue;
+            const int bm = mt * 16;
+            const int64_t nbm = (M + bm - 1) / bm;
+            const double u8 = mt == 8 ? cs[4] : (mt == 4 ? cs[2] : cs[0]);
+            const double u4 = mt == 8 ? cs[5] : (mt == 4 ? cs[3] : cs[1]);
+            for (int waves = 8; waves >= 4; waves -= 4) {
+                const int64_t nbn = (ntiles + waves * MMA_NT - 1) / (waves * MMA_NT);
+                const double u = (waves == 8 ? u8 : u4) * kscale;
+                for (int si = 0; si < 6; ++si) {
+                    int splits = split_opts[si];
+                    if (splits > KB) break;
+                    const int kbs = (KB + splits - 1) / splits;
+                    splits = (KB + kbs - 1) / kbs;
+                    const int64_t blocks = nbn * nbm * splits;
+                    const int64_t per_cu = (blocks + 255) / 256;
+                    double t = (double)per_cu * kbs * u;
+                    if (waves == 4) {
+                        // u is a 4-wave block's share when `cap` of them run together on a compute unit; the
+                        // ones left over run with idle SIMDs and take longer than that share
+                        const int cap = mt == 2 ? 3 : 2;
+                        const int64_t left = per_cu % cap;
+                        if (left > 0) {
+                            const double f = per_cu < cap ? (mt == 8 ? cs[7] : cs[6]) : (mt == 8 ? 1.13 : 1.0);
+                            t += (f - 1.0) * (double)left * kbs * u;
+                        }
+                    }
+                    // (with fewer blocks than compute units a block takes as long as in a full grid)
+                    if (splits > 1) t += 2.0 * splits * (double)M * (double)N * 4.0 / 5e6 + 5.0;
+                    if (t < best - 1e-9) {
+                        best = t;
+                        p.mt = mt;
+                        p.waves = waves;
+                        p.splits = splits;
+                        p.kb_per_split = kbs;
+                        p.tail_tiles = 0;
+                        p.tail_splits = 1;
+                        p.tail_kbs = 0;
                     }
                 }
-                // fewer blocks than compute units: the idle ones also pull no weights
-                if (blocks < 256) t *= 256.0 / (double)blocks;
-                if (splits > 1) t += 2.0 * splits * (double)M * (double)N * 4.0 / 4e6 + 5.0;
-                if (t < best - 1e-9) {
-                    best = t;
-                    p.waves = waves;
-                    p.splits = splits;
-                    p.kb_per_split = kbs;
-                    p.tail_tiles = 0;
-                }
-            }
-            // No uniform split, but the tiles of the partly filled last round are split along K so
-            // that they occupy every block slot once more: the last round then lasts 1 / tail_splits
-            // of a full one, at the price of partial tiles for those tiles only.
-            const int64_t tiles = nbn * nbm;
-            const int64_t slots = 256 * (waves == 8 ? 1 : (p.mt == 2 ? 3 : 2));
-            const int64_t rem = tiles % slots;
-            if (tiles > slots && rem > 0) {
-                int ts = (int)(slots / rem);
-                if (ts > 8) ts = 8;
-                if (ts > KB) ts = KB;
-                if (ts >= 2) {
-                    const int tkbs = (KB + ts - 1) / ts;
-                    ts = (KB + tkbs - 1) / tkbs;
-                    const int64_t head = tiles - rem;
-                    double t = (double)(head / 256) * KB * u + (double)((rem * ts + 255) / 256) * tkbs * u;
-                    const double bm_bn = (double)bm * (double)(waves * MMA_NT * FQ_NTILE);
-                    t += 2.0 * ts * (double)rem * bm_bn * 4.0 / 4e6 + 5.0;
-                    if (ts >= 2 && t < best - 1e-9) {
-                        best = t;
-                        p.waves = waves;
-                        p.splits = 1;
-                        p.kb_per_split = KB;
-                        p.tail_tiles = (int)rem;
-                        p.tail_splits = ts;
-                        p.tail_kbs = tkbs;
+                // No uniform split, but the tiles of the partly filled last round are split along K so
+                // that they occupy every block slot once more: the last round then lasts 1 / tail_splits
+                // of a full one, at the price of partial tiles for those tiles only.
+                const int64_t tiles = nbn * nbm;
+                const int64_t slots = 256 * (waves == 8 ? 1 : (mt == 2 ? 3 : 2));
+                const int64_t rem = tiles % slots;
+                if (tiles > slots && rem > 0) {
+                    int ts = (int)(slots / rem);
+                    if (ts > 8) ts = 8;
+                    if (ts > KB) ts = KB;
+                    if (ts >= 2) {
+                        const int tkbs = (KB + ts - 1) / ts;
+                        ts = (KB + tkbs - 1) / tkbs;
+                        const int64_t head = tiles - rem;
+                        double t = (double)(head / 256) * KB * u + (double)((rem * ts + 255) / 256) * tkbs * u;
+                        const double bm_bn = (double)bm * (double)(waves * MMA_NT * FQ_NTILE);
+                        t += 2.0 * ts * (double)rem * bm_bn * 4.0 / 5e6 + 5.0;
+                        // for the small shapes the model is 10 % optimistic about this form (QKV at M = 256:
+                        // 221 us predicted, 244 measured), so it has to win by that much
+                        if (mt < 8) t *= 1.10;
+                        if (ts >= 2 && t < best - 1e-9) {
+                            best = t;
+                            p.mt = mt;
+                            p.waves = waves;
+                            p.splits = 1;
+                            p.kb_per_split = KB;
+                            p.tail_tiles = (int)rem;
+                            p.tail_splits = ts;
+                            p.tail_kbs = tkbs;
+                        }
                     }
                 }
             }

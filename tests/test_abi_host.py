@@ -196,7 +196,8 @@ def test_plans_are_consistent_over_many_shapes():
             mt, waves, splits, kbs, tail_tiles, tail_splits = map(int, m.groups())
             seen.add("tail" if tail_tiles else ("split" if splits > 1 else "tiled"))
             assert M > 16 and mt in (2, 4, 8) and waves in (4, 8)
-            assert mt * 16 >= min(M, 128) or mt == 8
+            assert mt == 8 or M <= 256                     # the small block shapes compete up to 256 rows only
+            assert mt == 2 or mt * 8 < M                   # no block more than twice as tall as the matrix
             assert splits >= 1 and kbs * splits >= KB and kbs * (splits - 1) < KB
             tiles = -(-(N // 16) // (waves * 3)) * -(-M // (mt * 16))
             if tail_tiles:

@@ -47,6 +47,12 @@ R6  Section 3.3: "range" is the abs-max of a group; a halving step is taken
     2b is an image): the *default* alpha is PARITY UNPINNED; the function
     alpha -> g is pinned by constructed cases.
 
+R8  Code widths.  Appendix A is written for any bit width b; section 4.2 and
+    Table 5 evaluate 8, 4 and 3 bits (3 bits for accuracy only, the paper has
+    no 3-bit kernel).  b = 3 gives codes in [-3, 3] and the denominator 7; the
+    footprints Table 5 prints for its int3 rows follow from 3 + 16/g bits per
+    weight, i.e. from a true 3-bit packing.
+
 R7  Scale format.  Appendix B stores the scales in half precision; section
     4.1 ("GPU kernel implementations") describes kernels whose scales have the
     data type of the activation, i.e. bfloat16 scales next to bfloat16
@@ -91,16 +97,16 @@ __all__ = [
 
 
 def qmax_of(bits: int) -> int:
-    """Largest code magnitude, 2^(b-1) - 1 (7 for int4, 127 for int8)."""
-    if bits not in (4, 8):
-        raise ValueError("bits must be 4 or 8")
+    """Largest code magnitude, 2^(b-1) - 1 (3 for int3, 7 for int4, 127 for int8)."""
+    if bits not in (3, 4, 8):
+        raise ValueError("bits must be 3, 4 or 8")
     return (1 << (bits - 1)) - 1
 
 
 def levels_of(bits: int) -> int:
     """The denominator 2^b - 1 of Appendix A's scale equation."""
-    if bits not in (4, 8):
-        raise ValueError("bits must be 4 or 8")
+    if bits not in (3, 4, 8):
+        raise ValueError("bits must be 3, 4 or 8")
     return (1 << bits) - 1
 
 

@@ -5,6 +5,7 @@
 
 #include <math.h>
 #include <stdint.h>
+#include <atomic>
 
 #include "fq_gemm_config.h"
 #include "fq_gemm_kernels.h"
@@ -13,8 +14,18 @@ namespace fqd {
 
 using namespace fqk;
 
-
-using namespace fqk;
+// Kernels that need more than the default 64 KiB of dynamic LDS have their limit raised to the
+// 160 KiB of a compute unit, once per (kernel instantiation, device): `done` holds one bit per device.
+inline int raise_lds_limit(const void* kern, std::atomic<uint64_t>& done) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return FQ_ERR_HIP;
+    const uint64_t bit = (uint64_t)1 << (dev & 63);
+    if (done.load(std::memory_order_acquire) & bit) return FQ_OK;
+    if (hipFuncSetAttribute(kern, hipFuncAttributeMaxDynamicSharedMemorySize, 160 * 1024) != hipSuccess)
+        return FQ_ERR_HIP;
+    done.fetch_or(bit, std::memory_order_release);
+    return FQ_OK;
+}
 
 template <int ACT, int BITS, int NT, int DEPTH, int MAXW, int AU>
 int launch_skinny(const void* A, int64_t M, int64_t N, int64_t K, const void* codes, const void* scales, int g,
@@ -35,13 +46,8 @@ int launch_skinny(const void* A, int64_t M, int64_t N, int64_t K, const void* co
     if (lds > 65536) {
         // more than the default dynamic LDS limit: raise it for this kernel (up to the 160 KiB of a CU)
         if (lds > 160 * 1024) return FQ_ERR_UNSUPPORTED;
-        static bool raised[2] = {false, false};   // per instantiation: [per_step]
-        if (!raised[per_step ? 1 : 0]) {
-            if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
-                                    160 * 1024) != hipSuccess)
-                return FQ_ERR_HIP;
-            raised[per_step ? 1 : 0] = true;
-        }
+        static std::atomic<uint64_t> raised[2];   // per instantiation: [per_step]
+        if (raise_lds_limit((const void*)kern, raised[per_step ? 1 : 0]) != FQ_OK) return FQ_ERR_HIP;
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)(bgroups * plan.splits)), dim3((unsigned)(plan.gp * plan.kw * 64)),
                        lds, stream, (const uint16_t*)A, (const u32x4*)codes, (const uint16_t*)scales,
@@ -95,13 +101,8 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
         auto kern = fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, SR_, false, PIPE_,                  \
                                        use_post(ACT, BITS, MT_, SR_, PIPE_)>;                                 \
         if (lds > 65536) {                                                                              \
-            static bool raised = false;                                                                 \
-            if (!raised) {                                                                              \
-                if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,  \
-                                        160 * 1024) != hipSuccess)                                      \
-                    return FQ_ERR_HIP;                                                                  \
-                raised = true;                                                                          \
-            }                                                                                           \
+            static std::atomic<uint64_t> raised;                                                        \
+            if (raise_lds_limit((const void*)kern, raised) != FQ_OK) return FQ_ERR_HIP;                 \
         }                                                                                               \
         hipLaunchKernelGGL(kern, grid, dim3(W_ * 64), lds, stream, (const uint16_t*)A,                  \
                            (const u32x4*)codes, (const uint16_t*)scales, (uint16_t*)C, partial, (int)M, \
@@ -175,13 +176,8 @@ int launch_grouped_typed(const void* A, const int32_t* offsets, int E, int64_t N
         auto kern = fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, SR_, true, PIPE_,                   \
                                        use_post(ACT, BITS, MT_, SR_, PIPE_)>;                                 \
         if (lds > 65536) {                                                                              \
-            static bool raised = false;                                                                 \
-            if (!raised) {                                                                              \
-                if (hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,  \
-                                        160 * 1024) != hipSuccess)                                      \
-                    return FQ_ERR_HIP;                                                                  \
-                raised = true;                                                                          \
-            }                                                                                           \
+            static std::atomic<uint64_t> raised;                                                        \
+            if (raise_lds_limit((const void*)kern, raised) != FQ_OK) return FQ_ERR_HIP;                 \
         }                                                                                               \
         hipLaunchKernelGGL(kern, grid, dim3(W_ * 64), lds, stream, (const uint16_t*)A,                  \
                            (const u32x4*)codes, (const uint16_t*)scales, (uint16_t*)C, (float*)nullptr, \

@@ -82,7 +82,7 @@ def _rand_w(K, N, seed, sigma=0.02, outliers=True):
 # --------------------------------------------------------------------------
 # exact-rational brute force
 # --------------------------------------------------------------------------
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", [3, 4, 8])
 @pytest.mark.parametrize("g", [4, 8, 32])
 def test_matches_exact_rational_small(bits, g):
     W = _rand_w(32, 12, seed=100 + bits + g)
@@ -98,7 +98,7 @@ def test_matches_exact_rational_small(bits, g):
     assert np.array_equal(q.astype(np.int64), qe)
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", [3, 4, 8])
 def test_division_in_binary32_equals_exact_on_exhaustive_window(bits):
     """Reading R4: for half-precision w and s, rne(fl32(w/s)) equals exact rne(w/s), ties included.
 
@@ -149,7 +149,7 @@ def test_division_in_binary32_equals_exact_on_exhaustive_window(bits):
 # --------------------------------------------------------------------------
 # invariants
 # --------------------------------------------------------------------------
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", [3, 4, 8])
 @pytest.mark.parametrize("g", [32, 128, 0])
 def test_code_range_and_half_step_bound(bits, g):
     W = _rand_w(512, 96, seed=7 * bits + (g or 1))
@@ -169,7 +169,7 @@ def test_code_range_and_half_step_bound(bits, g):
     assert np.all(qmax_per_group[m > 0] == qm)
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", [3, 4, 8])
 def test_scale_is_minimal_half(bits):
     W = _rand_w(256, 64, seed=3 + bits)
     m = oracle.group_absmax(W, 64)
@@ -188,7 +188,7 @@ def test_zero_and_subnormal_groups():
     W[:, 1] = np.float16(6e-8)              # 2^-24, smallest subnormal
     W[5, 2] = np.float16(-6e-8)
     W[:32, 3] = np.float16(1.0)
-    for bits in (4, 8):
+    for bits in (3, 4, 8):
         q, s = oracle.quantize(W, bits, 32)
         qm = oracle.qmax_of(bits)
         assert s[0, 0] == 0 and s[1, 0] == 0 and np.all(q[:, 0] == 0)
@@ -218,7 +218,7 @@ def _per_column_quantizer(W, bits):
     return q, s
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", [3, 4, 8])
 def test_group_size_K_is_per_column(bits):
     W = _rand_w(384, 40, seed=11 + bits)
     q0, s0 = oracle.quantize(W, bits, 0)
@@ -228,7 +228,7 @@ def test_group_size_K_is_per_column(bits):
     assert np.array_equal(q0, qc) and np.array_equal(s0.view(np.uint16), sc.view(np.uint16))
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", [3, 4, 8])
 def test_groups_are_contiguous_rows_of_a_column(bits):
     """Quantising with group g equals quantising each block of g rows as its own matrix."""
     W = _rand_w(256, 24, seed=21 + bits)
@@ -243,7 +243,7 @@ def test_groups_are_contiguous_rows_of_a_column(bits):
     assert np.array_equal(q[:, 5:6], q1) and np.array_equal(s[:, 5:6].view(np.uint16), s1.view(np.uint16))
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", [3, 4, 8])
 def test_sign_symmetry_and_power_of_two_equivariance(bits):
     W = _rand_w(256, 32, seed=31 + bits, sigma=1.0)
     tiny = np.abs(W) < np.float16(0.01)                  # keep every element normal after scaling by 2^-3
@@ -262,7 +262,7 @@ def test_sign_symmetry_and_power_of_two_equivariance(bits):
         assert np.array_equal(q2[rows_ok], q[rows_ok])
 
 
-@pytest.mark.parametrize("bits", [4, 8])
+@pytest.mark.parametrize("bits", [3, 4, 8])
 def test_child_scale_never_exceeds_parent_scale(bits):
     W = _rand_w(512, 48, seed=41 + bits)
     prev = None
@@ -288,6 +288,16 @@ def test_known_tiny_example_by_hand():
     q8, s8 = oracle.quantize(col8, 8, 0)
     assert s8[0, 0] == np.float16(1.0)
     assert q8[:, 0].tolist() == [127, 126, 0, 100, -127]
+
+
+def test_hand_worked_int3_column():
+    """b = 3: seven levels -3 .. 3; max |w| = 3.5 gives s = 2 * 3.5 / 7 = 1 exactly."""
+    W = np.array([[3.5], [-3.5], [2.5], [1.5], [0.5], [-0.5], [0.49], [-2.51]], dtype=np.float16)
+    q, s = oracle.quantize(W, 3, 0)
+    assert float(s[0, 0]) == 1.0
+    # 3.5 -> clamp(round(3.5) = 4) = 3; 2.5 and 0.5 are ties and go to the even code; 1.5 -> 2
+    assert q[:, 0].tolist() == [3, -3, 2, 2, 0, 0, 0, -3]
+    assert oracle.bits_per_weight(3, 64) == 3.25
 
 
 def test_scale_rounds_up_not_to_nearest():
@@ -319,19 +329,24 @@ def test_bits_per_weight_reproduces_table5(model, int8_g):
     """b bits of code + one 16-bit scale per group of g weights.
 
     The fp16 and int8 rows determine how many weights are quantised; every
-    int4 row printed for that model must then follow from the closed form.
+    int4 and int3 row printed for that model must then follow from the closed form.
     """
     t = _table5()[model]
     fp16_gb = t[(16, 0)]
     n_quant = (fp16_gb - t[(8, int8_g)]) / (2.0 - oracle.bits_per_weight(8, int8_g) / 8.0)   # in 1e9 weights
     checked = 0
     for (bits, g), gb in t.items():
-        if bits != 4:
+        if bits not in (3, 4):
             continue
-        pred = fp16_gb - n_quant * (2.0 - oracle.bits_per_weight(4, g) / 8.0)
+        pred = fp16_gb - n_quant * (2.0 - oracle.bits_per_weight(bits, g) / 8.0)
         assert abs(pred - gb) < 0.03, (model, bits, g, pred, gb)
         checked += 1
     assert checked >= 2
+    if model == "opt-iml-30b":
+        assert checked == 6                          # three int4 rows and three int3 rows
+        # int3 codes held in 4-bit containers would miss the printed int3 footprints
+        wrong3 = fp16_gb - n_quant * (2.0 - (4 + 16.0 / 64) / 8.0)
+        assert abs(wrong3 - t[(3, 64)]) > 0.5
     # a 32-bit scale, or a scale per g*g weights, would miss the printed numbers
     wrong = fp16_gb - n_quant * (2.0 - (4 + 32.0 / 64) / 8.0)
     assert abs(wrong - t[(4, 64)]) > 0.5

@@ -53,9 +53,10 @@ typedef enum fq_scale_format {
 } fq_scale_format;
 
 /* Shape limits shared by every call:
- *   bits        4 or 8
+ *   bits        3, 4 or 8 (3-bit codes: the paper evaluates them for accuracy, section 4.2 and
+ *               Table 5, whose int3 footprints are 3 + 16/g bits per weight)
  *   N           multiple of 16
- *   K           multiple of 128 (bits = 4) or 64 (bits = 8)
+ *   K           multiple of 128 (bits = 3, 4) or 64 (bits = 8)
  *   group_size  0 or K (one scale per column), or a multiple of 32 that divides K
  *               (the paper plans "any power of 2 group size greater than 16",
  *               section 5; multiples of 32 cover that from 32 up).

@@ -1,6 +1,6 @@
 """Builds libfq.so for gfx950 with hipcc (cross-compiles without a GPU).
 
-Every translation unit is compiled to an object file in parallel (the six product-kernel
+Every translation unit is compiled to an object file in parallel (the nine product-kernel
 instantiations dominate the build time), then linked into paper_2308_09723_amd/libfq.so.
 """
 from __future__ import annotations
@@ -24,6 +24,9 @@ SOURCES = [
     "fq_gemm_bf16_8.hip",
     "fq_gemm_bf16s_4.hip",
     "fq_gemm_bf16s_8.hip",
+    "fq_gemm_f16_3.hip",
+    "fq_gemm_bf16_3.hip",
+    "fq_gemm_bf16s_3.hip",
 ]
 
 HIPCC_FLAGS = [

@@ -9,7 +9,7 @@
 
 namespace {
 
-bool bits_ok(int bits) { return bits == 4 || bits == 8; }
+bool bits_ok(int bits) { return bits == 3 || bits == 4 || bits == 8; }
 
 // Returns FQ_OK and the effective group size in *g_eff, or an error status.
 int check_shape(int64_t K, int64_t N, int bits, int group_size, int* g_eff) {

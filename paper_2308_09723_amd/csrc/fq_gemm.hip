@@ -26,6 +26,9 @@ FQ_DECLARE_GEMM(1, 4)
 FQ_DECLARE_GEMM(1, 8)
 FQ_DECLARE_GEMM(2, 4)   // bf16 activations, bf16 scales
 FQ_DECLARE_GEMM(2, 8)
+FQ_DECLARE_GEMM(0, 3)   // 3-bit codes
+FQ_DECLARE_GEMM(1, 3)
+FQ_DECLARE_GEMM(2, 3)
 
 fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
     fq_gemm_plan p = {};
@@ -206,16 +209,14 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
 int fq_launch_gemm(const void* A, int act, int64_t M, int64_t N, int64_t K, const void* codes,
                    const void* scales, int bits, int g, void* C, void* workspace, hipStream_t stream) {
     const fq_gemm_plan plan = fq_plan_gemm(M, N, K, bits, g);
-    if (act == FQ_F16) {
-        if (bits == 4) return fq_launch_typed_0_4(A, M, N, K, codes, scales, g, C, workspace, plan, stream);
-        return fq_launch_typed_0_8(A, M, N, K, codes, scales, g, C, workspace, plan, stream);
-    }
-    if (act == FQ_BF16) {
-        if (bits == 4) return fq_launch_typed_1_4(A, M, N, K, codes, scales, g, C, workspace, plan, stream);
-        return fq_launch_typed_1_8(A, M, N, K, codes, scales, g, C, workspace, plan, stream);
-    }
-    if (bits == 4) return fq_launch_typed_2_4(A, M, N, K, codes, scales, g, C, workspace, plan, stream);
-    return fq_launch_typed_2_8(A, M, N, K, codes, scales, g, C, workspace, plan, stream);
+#define FQ_PICK(ACT)                                                                                        \
+    (bits == 3   ? fq_launch_typed_##ACT##_3(A, M, N, K, codes, scales, g, C, workspace, plan, stream)      \
+     : bits == 4 ? fq_launch_typed_##ACT##_4(A, M, N, K, codes, scales, g, C, workspace, plan, stream)      \
+                 : fq_launch_typed_##ACT##_8(A, M, N, K, codes, scales, g, C, workspace, plan, stream))
+    if (act == FQ_F16) return FQ_PICK(0);
+    if (act == FQ_BF16) return FQ_PICK(1);
+    return FQ_PICK(2);
+#undef FQ_PICK
 }
 
 // The grouped product launches up to three kernels (row tiles of 128, 64 and 32 rows) that do not
@@ -284,16 +285,14 @@ int fq_launch_gemm_grouped(const void* A, int act, const int32_t* offsets, int E
         }
     }
     int st;
-    if (act == FQ_F16) {
-        st = bits == 4 ? fq_launch_grouped_typed_0_4(A, offsets, E, N, K, codes, scales, g, C, streams)
-                       : fq_launch_grouped_typed_0_8(A, offsets, E, N, K, codes, scales, g, C, streams);
-    } else if (act == FQ_BF16) {
-        st = bits == 4 ? fq_launch_grouped_typed_1_4(A, offsets, E, N, K, codes, scales, g, C, streams)
-                       : fq_launch_grouped_typed_1_8(A, offsets, E, N, K, codes, scales, g, C, streams);
-    } else {
-        st = bits == 4 ? fq_launch_grouped_typed_2_4(A, offsets, E, N, K, codes, scales, g, C, streams)
-                       : fq_launch_grouped_typed_2_8(A, offsets, E, N, K, codes, scales, g, C, streams);
-    }
+#define FQ_PICK(ACT)                                                                                        \
+    (bits == 3   ? fq_launch_grouped_typed_##ACT##_3(A, offsets, E, N, K, codes, scales, g, C, streams)     \
+     : bits == 4 ? fq_launch_grouped_typed_##ACT##_4(A, offsets, E, N, K, codes, scales, g, C, streams)     \
+                 : fq_launch_grouped_typed_##ACT##_8(A, offsets, E, N, K, codes, scales, g, C, streams))
+    if (act == FQ_F16) st = FQ_PICK(0);
+    else if (act == FQ_BF16) st = FQ_PICK(1);
+    else st = FQ_PICK(2);
+#undef FQ_PICK
     // join even after a failed launch, so that the side streams never run ahead of the caller's
     for (int i = 0; i < 2; ++i) {
         if (!forked[i]) continue;

@@ -1,0 +1,4 @@
+// Instantiation of the product kernels for bf16 activations and 3-bit codes.
+#include "fq_gemm_dispatch.h"
+
+FQ_INSTANTIATE_GEMM(1, 3)

@@ -18,15 +18,15 @@ constexpr int MMA_NT = 3;       // column tiles per wave of the large-M kernel
 #endif
 
 // Post-scaled form of the large-M kernel (codes converted without their scale, one fold per scale
-// group and output tile): used where the conversion, not the matrix pipe, sets the pace, i.e. 4-bit
-// codes and at most 64 rows per block.  Measured on the OPT-175B shapes (M = 32 / 64, us, pre- ->
+// group and output tile): used where the conversion, not the matrix pipe, sets the pace, i.e. 3- and
+// 4-bit codes and at most 64 rows per block.  Measured on the OPT-175B shapes (M = 32 / 64, us, pre- ->
 // post-scaled): bf16 needs 23 vector instructions per 8 weights pre-scaled and 7 post-scaled (no packed
 // bf16 arithmetic), QKV M=32 63 -> 52, FC1 89 -> 68, and at 64 rows with one scale row per k-block FC1
 // 112 -> 100; with two scale rows per k-block the folds eat the gain at 64 rows (93 -> 127) but not at
 // 32 (65 -> 62).  fp16 (13 -> 9 instructions) gains with one scale row only: FC1 M=32 74 -> 66, M=64
 // 100 -> 94; with two it loses (54 -> 60).  8-bit codes gain nothing (M=32) or lose (M=64: 114 -> 127).
 constexpr bool use_post(int act, int bits, int mt, int sr, int pipe) {
-    if (pipe == 0 || bits != 4) return false;
+    if (pipe == 0 || bits == 8) return false;
     if (act == 0) return sr == 1 && mt <= 4;
     return (mt <= 2 && sr <= 2) || (mt == 4 && sr == 1);
 }

@@ -114,7 +114,7 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
     do {                                                                                                \
         if (sr == 1) FQ_MMA_LAUNCH_SR(MT_, W_, PIPE_, 1);                                               \
         else if (sr == 2) FQ_MMA_LAUNCH_SR(MT_, W_, PIPE_, 2);                                          \
-        else if constexpr (BITS == 4) FQ_MMA_LAUNCH_SR(MT_, W_, PIPE_, 4);                              \
+        else if constexpr (BITS != 8) FQ_MMA_LAUNCH_SR(MT_, W_, PIPE_, 4);                              \
     } while (0)
         if (plan.waves == 8) {
             if (plan.mt == 2) FQ_MMA_LAUNCH(2, 8, FQ_RING_MT2);
@@ -188,7 +188,7 @@ int launch_grouped_typed(const void* A, const int32_t* offsets, int E, int64_t N
     do {                                                                                                \
         if (sr == 1) FQ_GROUPED_LAUNCH_SR(MT_, W_, PIPE_, 1);                                           \
         else if (sr == 2) FQ_GROUPED_LAUNCH_SR(MT_, W_, PIPE_, 2);                                      \
-        else if constexpr (BITS == 4) FQ_GROUPED_LAUNCH_SR(MT_, W_, PIPE_, 4);                          \
+        else if constexpr (BITS != 8) FQ_GROUPED_LAUNCH_SR(MT_, W_, PIPE_, 4);                          \
     } while (0)
             if (mt == 8) FQ_GROUPED_LAUNCH(8, 8, 2);
             else if (mt == 4) FQ_GROUPED_LAUNCH(4, 4, FQ_RING_MT4);

@@ -1,19 +1,21 @@
 // Fused dequantise-and-multiply kernels for gfx950 (section 4.1, "GPU kernel
 // implementations": int4/int8 weights with a matrix of scales, fp16/bf16 activations,
-// floating-point matrix-core math, output in the activation type).
+// floating-point matrix-core math, output in the activation type; 3-bit codes, which the
+// paper evaluates for accuracy only, run through the same kernels).
 //
 // Orientation: every product is computed as 16x16 tiles of C^T with
 // v_mfma_f32_16x16x32_{f16,bf16}.  The WEIGHTS are the first MFMA operand (its 16 rows are
 // 16 output columns n), the ACTIVATIONS the second (its 16 columns are 16 rows m of A).
-// A lane's 16-byte record of the packed layout is, after the integer->float step, directly
+// A lane's record of the packed layout (16 bytes; 12 for 3-bit codes) is, after the integer->float step, directly
 // its slice of the first operand: weights never pass through LDS.  The result tile leaves
 // lane l with C[m = l % 16][n = 4 (l / 16) + 0..3], i.e. four consecutive columns of one row.
 //
-// Numerics: the integer codes are converted EXACTLY to the activation type (bf16 carries
-// them with a constant offset that is removed in binary32), multiplied on the matrix cores
-// with binary32 accumulation over one scale group (or one k-block), and the group's scale
-// is applied to that partial sum in binary32.  Nothing is rounded to 16 bits before the
-// final store.
+// Numerics, small-M kernel and the post-scaled form of the large-M kernel: the integer codes are
+// converted EXACTLY to the activation type (bf16 carries them with a constant offset that is
+// removed in binary32), multiplied on the matrix cores with binary32 accumulation over one scale
+// group (or one k-block), and the group's scale is applied to that partial sum in binary32;
+// nothing is rounded to 16 bits before the final store.  The pre-scaled form of the large-M kernel
+// rounds q * s once to the activation type before the MFMA (the paper's order).
 //
 // (device code; included by the per-type translation units through fq_gemm_dispatch.h)
 #ifndef FQ_GEMM_KERNELS_H_
@@ -44,6 +46,23 @@ template <typename T, typename F>
 __device__ inline T bitcast(const F& f) {
     static_assert(sizeof(T) == sizeof(F), "size mismatch");
     return __builtin_bit_cast(T, f);
+}
+
+// One lane record of packed codes: 16 bytes, or 12 bytes (three dwords, the fourth left zero) for
+// 3-bit codes.  Either way a single vector load.
+template <int BITS, bool NONTEMPORAL>
+__device__ inline u32x4 load_rec(const char* p) {
+    if constexpr (BITS == 3) {
+        typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
+        u32x3 v;
+        __builtin_memcpy(&v, p, 12);
+        u32x4 r = {v[0], v[1], v[2], 0u};
+        return r;
+    } else if constexpr (NONTEMPORAL) {
+        return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
+    } else {
+        return *reinterpret_cast<const u32x4*>(p);
+    }
 }
 
 template <int ACT>
@@ -79,21 +98,37 @@ __device__ inline uint32_t and_or(uint32_t x, uint32_t mask, uint32_t magic_v) {
 template <int ACT, int BITS>
 struct Dequant;
 
-template <>
-struct Dequant<FQ_F16, 4> {
+// The 32-bit word that holds the eight stored values of k-step T of a sub-byte record, one per
+// nibble.  4-bit: dword T as it is.  3-bit: dwords 0..2 as they are (the values sit in the low three
+// bits of the nibbles; the fourth bit belongs to step 3 and is dropped by the conversion masks), and
+// step 3 is gathered from those fourth bits.
+template <int SB, int T>
+__device__ inline uint32_t code_word(const u32x4& rec) {
+    if constexpr (SB == 3 && T == 3) {
+        return ((rec[0] >> 3) & 0x11111111u) | ((rec[1] >> 2) & 0x22222222u) | ((rec[2] >> 1) & 0x44444444u);
+    } else {
+        return rec[T];
+    }
+}
+
+// SB-bit codes (SB = 3 or 4), stored value u = q + 2^(SB-1) in the low SB bits of a nibble
+template <int SB>
+struct DequantF16Sub {
     static constexpr float OFFSET = 0.0f;
+    static constexpr uint32_t MLO = SB == 4 ? 0x000f000fu : 0x00070007u;
+    static constexpr float BIAS = SB == 4 ? 8.0f : 4.0f;
     static __device__ inline uint32_t init() { return vgpr_const(0x64006400u); }
     template <int T>
     static __device__ inline u32x4 run(const u32x4& rec, uint32_t MAGIC) {
-        const uint32_t w = rec[T];
+        const uint32_t w = code_word<SB, T>(rec);
         const uint32_t w8 = w >> 8;
-        const f16x2 lo0 = bitcast<f16x2>(and_or(w, 0x000f000fu, MAGIC));
-        const f16x2 hi0 = bitcast<f16x2>(and_or(w, 0x00f000f0u, MAGIC));
-        const f16x2 lo1 = bitcast<f16x2>(and_or(w8, 0x000f000fu, MAGIC));
-        const f16x2 hi1 = bitcast<f16x2>(and_or(w8, 0x00f000f0u, MAGIC));
-        const f16x2 sub = {(_Float16)1032.0f, (_Float16)1032.0f};
+        const f16x2 lo0 = bitcast<f16x2>(and_or(w, MLO, MAGIC));
+        const f16x2 hi0 = bitcast<f16x2>(and_or(w, MLO << 4, MAGIC));
+        const f16x2 lo1 = bitcast<f16x2>(and_or(w8, MLO, MAGIC));
+        const f16x2 hi1 = bitcast<f16x2>(and_or(w8, MLO << 4, MAGIC));
+        const f16x2 sub = {(_Float16)(1024.0f + BIAS), (_Float16)(1024.0f + BIAS)};
         const f16x2 sc = {(_Float16)0.0625f, (_Float16)0.0625f};
-        const f16x2 off = {(_Float16)-72.0f, (_Float16)-72.0f};
+        const f16x2 off = {(_Float16)(-64.0f - BIAS), (_Float16)(-64.0f - BIAS)};
         u32x4 r;
         r[0] = bitcast<uint32_t>(lo0 - sub);                                 // elements 0,1
         r[1] = bitcast<uint32_t>(__builtin_elementwise_fma(hi0, sc, off));   // elements 2,3
@@ -102,6 +137,10 @@ struct Dequant<FQ_F16, 4> {
         return r;
     }
 };
+template <>
+struct Dequant<FQ_F16, 4> : DequantF16Sub<4> {};
+template <>
+struct Dequant<FQ_F16, 3> : DequantF16Sub<3> {};
 
 template <>
 struct Dequant<FQ_F16, 8> {
@@ -120,21 +159,26 @@ struct Dequant<FQ_F16, 8> {
     }
 };
 
-template <>
-struct Dequant<FQ_BF16, 4> {
-    static constexpr float OFFSET = 136.0f;
+template <int SB>
+struct DequantBF16Sub {
+    static constexpr float OFFSET = SB == 4 ? 136.0f : 132.0f;     // 128 + the storage bias
+    static constexpr uint32_t MLO = SB == 4 ? 0x000f000fu : 0x00070007u;
     static __device__ inline uint32_t init() { return vgpr_const(0x43004300u); }
     template <int T>
     static __device__ inline u32x4 run(const u32x4& rec, uint32_t MAGIC) {
-        const uint32_t w = rec[T];
+        const uint32_t w = code_word<SB, T>(rec);
         u32x4 r;
-        r[0] = and_or(w, 0x000f000fu, MAGIC);
-        r[1] = and_or(w >> 4, 0x000f000fu, MAGIC);
-        r[2] = and_or(w >> 8, 0x000f000fu, MAGIC);
-        r[3] = and_or(w >> 12, 0x000f000fu, MAGIC);
+        r[0] = and_or(w, MLO, MAGIC);
+        r[1] = and_or(w >> 4, MLO, MAGIC);
+        r[2] = and_or(w >> 8, MLO, MAGIC);
+        r[3] = and_or(w >> 12, MLO, MAGIC);
         return r;
     }
 };
+template <>
+struct Dequant<FQ_BF16, 4> : DequantBF16Sub<4> {};
+template <>
+struct Dequant<FQ_BF16, 3> : DequantBF16Sub<3> {};
 
 template <>
 struct Dequant<FQ_BF16, 8> {
@@ -223,7 +267,7 @@ __device__ inline void flush(f32x4& acc, const f32x4& p, const f32x4& s, float r
 // AU = activation units (16 B) a lane fetches per super-block: M * KC <= AU * 64 * GP.
 template <int BITS, int NT, bool PER_STEP, int AU_>
 struct SkinnyStage {
-    static constexpr int STEPS = (BITS == 4 ? 128 : 64) / FQ_KSTEP;
+    static constexpr int STEPS = fq_kblk(BITS) / FQ_KSTEP;
     static constexpr int AU = AU_;
     u32x4 wq[NT];
     // four scales (output columns 4j .. 4j+3) of one scale row.  PER_STEP: the lane holds the row of
@@ -322,7 +366,7 @@ __global__ __launch_bounds__(MAXW * 64) void fq_gemm_skinny_kernel(
     const uint16_t* __restrict__ A, const u32x4* __restrict__ codes, const uint16_t* __restrict__ scales,
     uint16_t* __restrict__ C, float* __restrict__ partial, int M, int N, int K, uint32_t g32,
     uint32_t g32_recip, int gp, int kw_n, int grid_splits) {
-    constexpr int KBLK = BITS == 4 ? 128 : 64;
+    constexpr int KBLK = fq_kblk(BITS);
     constexpr int STEPS = KBLK / FQ_KSTEP;
     constexpr int KC = KBLK / 8;                    // 16-byte activation units per row and k-block
     typedef SkinnyStage<BITS, NT, PER_STEP, AU> Stage;
@@ -351,7 +395,8 @@ __global__ __launch_bounds__(MAXW * 64) void fq_gemm_skinny_kernel(
     const int abuf_units = kw_n * KC * FQ_SK_PITCH;
 
     // Wave-uniform bases (scalar registers) plus one per-lane offset each.
-    const u32x4* wbase[NT];
+    constexpr int RB = fq_rec_bytes(BITS);
+    const char* wbase[NT];
     const uint16_t* sbase[NT];
     bool tvalid[NT];
 #pragma unroll
@@ -359,7 +404,7 @@ __global__ __launch_bounds__(MAXW * 64) void fq_gemm_skinny_kernel(
         const int tile = ng * NT + nt;
         tvalid[nt] = gvalid && tile < ntiles;
         const int tc = tvalid[nt] ? tile : 0;
-        wbase[nt] = codes + fq_rec(tc, 0, ntiles, 0);
+        wbase[nt] = reinterpret_cast<const char*>(codes) + fq_rec(tc, 0, ntiles, 0) * RB;
         sbase[nt] = scales + tc * FQ_NTILE;
     }
     const uint32_t s_off = (uint32_t)j * 4u;
@@ -400,7 +445,7 @@ __global__ __launch_bounds__(MAXW * 64) void fq_gemm_skinny_kernel(
         int kb = (gsplit + it * grid_splits) * kw_n + kw;
         kb = kb < KB ? kb : KB - 1;                      // tail super-block: idle workers re-read the last block
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) sl.wq[nt] = __builtin_nontemporal_load(wbase[nt] + (int64_t)kb * kb_stride + lane);
+        for (int nt = 0; nt < NT; ++nt) sl.wq[nt] = load_rec<BITS, true>(wbase[nt] + ((int64_t)kb * kb_stride + lane) * RB);
         {
             // scale row of a 32-row k-step: an exact division by g / 32 done as a multiplication by
             // its rounded-up reciprocal (valid while the step index < 2^32 / (g/32)).  PER_STEP: the
@@ -531,12 +576,12 @@ struct fq_group_items {
 template <int ACT, int BITS>
 struct DequantScaled;
 
-template <>
-struct DequantScaled<FQ_F16, 4> {
+template <int SB>
+struct DequantScaledF16Sub {
     // s2 = (s, s) as packed fp16
     template <int T>
     static __device__ inline u32x4 run(const u32x4& rec, uint32_t MAGIC, uint32_t s2) {
-        const u32x4 q = Dequant<FQ_F16, 4>::template run<T>(rec, MAGIC);
+        const u32x4 q = Dequant<FQ_F16, SB>::template run<T>(rec, MAGIC);
         const f16x2 s = bitcast<f16x2>(s2);
         u32x4 r;
 #pragma unroll
@@ -544,6 +589,10 @@ struct DequantScaled<FQ_F16, 4> {
         return r;
     }
 };
+template <>
+struct DequantScaled<FQ_F16, 4> : DequantScaledF16Sub<4> {};
+template <>
+struct DequantScaled<FQ_F16, 3> : DequantScaledF16Sub<3> {};
 
 template <>
 struct DequantScaled<FQ_F16, 8> {
@@ -564,16 +613,17 @@ __device__ inline uint32_t pack_bf16x2(float lo, float hi) {
     return bitcast<uint32_t>(v);
 }
 
-template <>
-struct DequantScaled<FQ_BF16, 4> {
+template <int SB>
+struct DequantScaledBF16Sub {
     // s2 = binary32 bits of the scale
     template <int T>
     static __device__ inline u32x4 run(const u32x4& rec, uint32_t, uint32_t s2) {
-        const uint32_t w = rec[T];
+        const uint32_t w = code_word<SB, T>(rec);
         const float s = bitcast<float>(s2);
-        const float b = -8.0f * s;
-        uint32_t lo = w & 0x0f0f0f0fu;          // nibbles 0,2,4,6 = elements 0,4,1,5
-        uint32_t hi = (w >> 4) & 0x0f0f0f0fu;   // nibbles 1,3,5,7 = elements 2,6,3,7
+        const float b = (SB == 4 ? -8.0f : -4.0f) * s;
+        constexpr uint32_t M = SB == 4 ? 0x0f0f0f0fu : 0x07070707u;
+        uint32_t lo = w & M;          // nibbles 0,2,4,6 = elements 0,4,1,5
+        uint32_t hi = (w >> 4) & M;   // nibbles 1,3,5,7 = elements 2,6,3,7
         // opaque to the optimiser: byte k of lo / hi then converts with one v_cvt_f32_ubyte<k>
         // instead of a bit-field extract plus a conversion
         asm("" : "+v"(lo));
@@ -587,6 +637,10 @@ struct DequantScaled<FQ_BF16, 4> {
         return r;
     }
 };
+template <>
+struct DequantScaled<FQ_BF16, 4> : DequantScaledBF16Sub<4> {};
+template <>
+struct DequantScaled<FQ_BF16, 3> : DequantScaledBF16Sub<3> {};
 
 template <>
 struct DequantScaled<FQ_BF16, 8> {
@@ -671,7 +725,7 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
     uint16_t* __restrict__ C, float* __restrict__ partial, int M, int N, int K, int g, int kb_per_split,
     int splits, int nblocks_n, int nblocks_m, int64_t codes_stride16, int64_t scales_stride,
     fq_group_items items, int tail_tiles, int tail_splits, int tail_kbs) {
-    constexpr int KBLK = BITS == 4 ? 128 : 64;
+    constexpr int KBLK = fq_kblk(BITS);
     constexpr int STEPS = KBLK / FQ_KSTEP;
     constexpr int KC = KBLK / 8;
     constexpr int BM = MT * 16;
@@ -752,7 +806,8 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
         rows = (int)min((int64_t)BM, (int64_t)M - row0);
     }
 
-    const u32x4* wbase[NT];
+    constexpr int RB = fq_rec_bytes(BITS);
+    const char* wbase[NT];
     const uint16_t* sbase[NT];
     bool tvalid[NT];
     const int tile0 = (bn * WAVES + wave) * NT;
@@ -761,7 +816,7 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
         const int tile = tile0 + nt;
         tvalid[nt] = tile < ntiles;
         const int tc = tvalid[nt] ? tile : 0;
-        wbase[nt] = codes + fq_rec(tc, 0, ntiles, 0);
+        wbase[nt] = reinterpret_cast<const char*>(codes) + fq_rec(tc, 0, ntiles, 0) * RB;
         sbase[nt] = scales + tc * FQ_NTILE;
     }
 
@@ -804,7 +859,7 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
     SC sc[SREG][NT], sc_n[SREG][NT];
     auto load_q = [&](u32x4 (&q)[NT], int kb) {
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) q[nt] = (wbase[nt] + (int64_t)kb * kb_stride)[lane];
+        for (int nt = 0; nt < NT; ++nt) q[nt] = load_rec<BITS, false>(wbase[nt] + ((int64_t)kb * kb_stride + lane) * RB);
     };
     auto load_s = [&](SC (&s)[SREG][NT], int kb) {
 #pragma unroll

@@ -117,10 +117,10 @@ template <int BITS, bool OWN_SCALES>
 __global__ __launch_bounds__(256) void fq_quantize_panel_kernel(const uint16_t* __restrict__ W, int64_t K,
                                                                 int64_t N, int g, float L, int sfmt,
                                                                 uint16_t* __restrict__ scales,
-                                                                uint4* __restrict__ codes) {
-    constexpr int KBLK = BITS == 4 ? 128 : 64;
+                                                                uint32_t* __restrict__ codes) {
+    constexpr int KBLK = fq_kblk(BITS);
     constexpr int STEPS = KBLK / FQ_KSTEP;
-    constexpr int QMAX = BITS == 4 ? 7 : 127;
+    constexpr int QMAX = (1 << (BITS - 1)) - 1;
     __shared__ uint16_t panel[FQ_QP_ROWS * FQ_QP_PITCH];
     __shared__ uint16_t submax[4][FQ_QP_COLS];      // abs-max bits of the 32-row sub-blocks
     __shared__ float sub_scale[4][FQ_QP_COLS];      // scale of the group each sub-block belongs to
@@ -205,13 +205,33 @@ __global__ __launch_bounds__(256) void fq_quantize_panel_kernel(const uint16_t* 
                     const int q = encode_one(panel[(r0 + e) * FQ_QP_PITCH + c], sc, QMAX);
                     if (BITS == 4) {
                         rec[t] |= (uint32_t)(q + 8) << (4 * fq_nibble_slot(e));
+                    } else if (BITS == 3) {
+                        // steps 0..2: low three bits of the nibble; step 3: bit b of the value goes to
+                        // the fourth bit of the same nibble of dword b
+                        const uint32_t u = (uint32_t)(q + 4);
+                        const int p = 4 * fq_nibble_slot(e);
+                        if (t < 3) {
+                            rec[t] |= u << p;
+                        } else {
+                            rec[0] |= (u & 1u) << (p + 3);
+                            rec[1] |= ((u >> 1) & 1u) << (p + 3);
+                            rec[2] |= ((u >> 2) & 1u) << (p + 3);
+                        }
                     } else {
                         rec[2 * t + (e >> 2)] |= (uint32_t)(q + 128) << (8 * (e & 3));
                     }
                 }
             }
             const int64_t kblock = (k0 / KBLK) + kb;
-            codes[fq_rec(n0 / FQ_NTILE + tl, kblock, ntiles, lane)] = make_uint4(rec[0], rec[1], rec[2], rec[3]);
+            const int64_t at = fq_rec(n0 / FQ_NTILE + tl, kblock, ntiles, lane);
+            if (BITS == 3) {
+                uint32_t* dst = codes + at * 3;
+                dst[0] = rec[0];
+                dst[1] = rec[1];
+                dst[2] = rec[2];
+            } else {
+                *reinterpret_cast<uint4*>(codes + at * 4) = make_uint4(rec[0], rec[1], rec[2], rec[3]);
+            }
         }
     }
 }
@@ -230,6 +250,8 @@ __global__ __launch_bounds__(256) void fq_unpack_kernel(const uint32_t* __restri
         if (BITS == 4) {
             const uint32_t w = codes[p.rec * 4 + p.t];
             v = (int)((w >> (4 * fq_nibble_slot(p.e))) & 0xfu) - 8;
+        } else if (BITS == 3) {
+            v = (int)fq_get3(codes + p.rec * 3, p.t, p.e) - 4;
         } else {
             const uint32_t w = codes[p.rec * 4 + 2 * p.t + (p.e >> 2)];
             v = (int)((w >> (8 * (p.e & 3))) & 0xffu) - 128;
@@ -339,6 +361,8 @@ __global__ __launch_bounds__(256) void fq_quant_error_kernel(const uint16_t* __r
             if (BITS == 4) {
                 const uint32_t w = codes[p.rec * 4 + p.t];
                 q = (int)((w >> (4 * fq_nibble_slot(p.e))) & 0xfu) - 8;
+            } else if (BITS == 3) {
+                q = (int)fq_get3(codes + p.rec * 3, p.t, p.e) - 4;
             } else {
                 const uint32_t w = codes[p.rec * 4 + 2 * p.t + (p.e >> 2)];
                 q = (int)((w >> (8 * (p.e & 3))) & 0xffu) - 128;
@@ -395,17 +419,25 @@ __global__ __launch_bounds__(256) void fq_quant_error_final_kernel(const double*
 }  // namespace
 
 // ----------------------------------------------------------------------------- launchers
+#define FQ_LAUNCH_PANEL(OWN)                                                                                  \
+    do {                                                                                                      \
+        if (bits == 3)                                                                                        \
+            hipLaunchKernelGGL((fq_quantize_panel_kernel<3, OWN>), grid, dim3(256), 0, stream,                \
+                               (const uint16_t*)W, K, N, g, L, sfmt, (uint16_t*)scales, (uint32_t*)codes);    \
+        else if (bits == 4)                                                                                   \
+            hipLaunchKernelGGL((fq_quantize_panel_kernel<4, OWN>), grid, dim3(256), 0, stream,                \
+                               (const uint16_t*)W, K, N, g, L, sfmt, (uint16_t*)scales, (uint32_t*)codes);    \
+        else                                                                                                  \
+            hipLaunchKernelGGL((fq_quantize_panel_kernel<8, OWN>), grid, dim3(256), 0, stream,                \
+                               (const uint16_t*)W, K, N, g, L, sfmt, (uint16_t*)scales, (uint32_t*)codes);    \
+    } while (0)
+
 int fq_launch_quantize(const void* W, int64_t K, int64_t N, int bits, int g, int sfmt, void* codes, void* scales,
                        hipStream_t stream) {
     const float L = (float)((1 << bits) - 1);
     if (g == 32 || g == 64 || g == 128) {
         dim3 grid((unsigned)((N + FQ_QP_COLS - 1) / FQ_QP_COLS), (unsigned)((K + FQ_QP_ROWS - 1) / FQ_QP_ROWS));
-        if (bits == 4)
-            hipLaunchKernelGGL((fq_quantize_panel_kernel<4, true>), grid, dim3(256), 0, stream, (const uint16_t*)W,
-                               K, N, g, L, sfmt, (uint16_t*)scales, (uint4*)codes);
-        else
-            hipLaunchKernelGGL((fq_quantize_panel_kernel<8, true>), grid, dim3(256), 0, stream, (const uint16_t*)W,
-                               K, N, g, L, sfmt, (uint16_t*)scales, (uint4*)codes);
+        FQ_LAUNCH_PANEL(true);
         return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;
     }
     if (g >= 1024 && g % 128 == 0) {
@@ -427,12 +459,7 @@ int fq_launch_quantize(const void* W, int64_t K, int64_t N, int bits, int g, int
     {
         // encoding pass from LDS panels, with the scales just written
         dim3 grid((unsigned)((N + FQ_QP_COLS - 1) / FQ_QP_COLS), (unsigned)((K + FQ_QP_ROWS - 1) / FQ_QP_ROWS));
-        if (bits == 4)
-            hipLaunchKernelGGL((fq_quantize_panel_kernel<4, false>), grid, dim3(256), 0, stream, (const uint16_t*)W,
-                               K, N, g, L, sfmt, (uint16_t*)scales, (uint4*)codes);
-        else
-            hipLaunchKernelGGL((fq_quantize_panel_kernel<8, false>), grid, dim3(256), 0, stream, (const uint16_t*)W,
-                               K, N, g, L, sfmt, (uint16_t*)scales, (uint4*)codes);
+        FQ_LAUNCH_PANEL(false);
     }
     return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;
 }
@@ -440,7 +467,9 @@ int fq_launch_quantize(const void* W, int64_t K, int64_t N, int bits, int g, int
 int fq_launch_unpack(const void* codes, int64_t K, int64_t N, int bits, int8_t* q, hipStream_t stream) {
     dim3 block(256);
     dim3 grid((unsigned)((N + 255) / 256), (unsigned)(K < 16384 ? K : 16384));
-    if (bits == 4)
+    if (bits == 3)
+        hipLaunchKernelGGL(fq_unpack_kernel<3>, grid, block, 0, stream, (const uint32_t*)codes, K, N, q);
+    else if (bits == 4)
         hipLaunchKernelGGL(fq_unpack_kernel<4>, grid, block, 0, stream, (const uint32_t*)codes, K, N, q);
     else
         hipLaunchKernelGGL(fq_unpack_kernel<8>, grid, block, 0, stream, (const uint32_t*)codes, K, N, q);
@@ -484,7 +513,10 @@ int fq_launch_quant_error(const void* W, int64_t K, int64_t N, int bits, int g, 
     double* part = out + 2;
     const int64_t nblk = fq_quant_error_blocks(K, N);
     dim3 grid((unsigned)((N + 255) / 256), (unsigned)((K + FQ_QE_ROWS - 1) / FQ_QE_ROWS));
-    if (bits == 4)
+    if (bits == 3)
+        hipLaunchKernelGGL(fq_quant_error_kernel<3>, grid, dim3(256), 0, stream, (const uint16_t*)W,
+                           (const uint32_t*)codes, (const uint16_t*)scales, K, N, g, sfmt, part, nblk);
+    else if (bits == 4)
         hipLaunchKernelGGL(fq_quant_error_kernel<4>, grid, dim3(256), 0, stream, (const uint16_t*)W,
                            (const uint32_t*)codes, (const uint16_t*)scales, K, N, g, sfmt, part, nblk);
     else

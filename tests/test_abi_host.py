@@ -29,7 +29,8 @@ def test_library_exports_every_declared_symbol():
 def test_size_queries():
     assert fq.codes_bytes(1024, 1024, 4) == 1024 * 1024 // 2
     assert fq.codes_bytes(1024, 1024, 8) == 1024 * 1024
-    assert fq.codes_bytes(1024, 1024, 3) == 0
+    assert fq.codes_bytes(1024, 1024, 3) == 1024 * 1024 * 3 // 8
+    assert fq.codes_bytes(1024, 1024, 5) == 0
     assert fq.scales_bytes(1024, 1024, 128) == 8 * 1024 * 2
     assert fq.scales_bytes(1024, 1024, 0) == 1024 * 2
     assert fq.scales_bytes(1024, 1024, 1024) == 1024 * 2
@@ -46,7 +47,8 @@ def test_size_queries():
     (dict(W=0), fq.FQ_ERR_INVALID_ARG),
     (dict(codes=0), fq.FQ_ERR_INVALID_ARG),
     (dict(scales=0), fq.FQ_ERR_INVALID_ARG),
-    (dict(bits=3), fq.FQ_ERR_INVALID_ARG),
+    (dict(bits=5), fq.FQ_ERR_INVALID_ARG),
+    (dict(bits=2), fq.FQ_ERR_INVALID_ARG),
     (dict(bits=16), fq.FQ_ERR_INVALID_ARG),
     (dict(g=100), fq.FQ_ERR_INVALID_ARG),          # does not divide K
     (dict(g=-1), fq.FQ_ERR_INVALID_ARG),
@@ -155,7 +157,7 @@ def test_quant_error_argument_checks():
     assert call(W=0) == fq.FQ_ERR_INVALID_ARG
     assert call(codes=0) == fq.FQ_ERR_INVALID_ARG
     assert call(scales=0) == fq.FQ_ERR_INVALID_ARG
-    assert call(bits=3) == fq.FQ_ERR_INVALID_ARG
+    assert call(bits=5) == fq.FQ_ERR_INVALID_ARG
     assert call(g=96) == fq.FQ_ERR_INVALID_ARG
     assert call(N=1032) == fq.FQ_ERR_UNSUPPORTED
     assert call(ws=0) == fq.FQ_ERR_WORKSPACE
@@ -171,8 +173,8 @@ def test_plans_are_consistent_over_many_shapes():
     rng = np.random.default_rng(11)
     seen = set()
     for _ in range(600):
-        bits = int(rng.choice([4, 8]))
-        kblk = 128 if bits == 4 else 64
+        bits = int(rng.choice([3, 4, 8]))
+        kblk = 64 if bits == 8 else 128
         K = kblk * int(rng.integers(1, 400))
         N = 16 * int(rng.integers(1, 3200))
         M = int(rng.choice([1, 3, 8, 16, 17, 32, 33, 64, 65, 100, 128, 129, 256, 384, 512, 777, 1024, 2048, 4096]))

@@ -259,6 +259,7 @@ def main():
         out["extra_stress"] = stress_section(torch, fq, workloads)
         out["extra_quantize"] = quantize_section(torch, fq, workloads)
         out["extra_bf16_scales"] = bf16_scales_section(torch, fq, workloads)
+        out["extra_int3"] = int3_section(torch, fq, workloads)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
@@ -417,6 +418,38 @@ def bf16_scales_section(torch, fq, workloads):
             wbytes = codes.numel() + scales.numel() * 2
             res[f"M{M}_{tag}"] = {"us": round(ms * 1e3, 2), "weight_TBps": round(wbytes / ms / 1e9, 3),
                                   "TFLOPs": round(2.0 * M * N * K / ms / 1e9, 1)}
+    return res
+
+
+def int3_section(torch, fq, workloads):
+    """3-bit codes (group 128) on the four OPT-175B shapes: decode products at M = 1 and 8 (fp16), and the
+    QKV-shaped prefill product at M = 2048 (bf16)."""
+    stream = torch.cuda.current_stream().cuda_stream
+    res = {}
+    for name, (K, N) in workloads.OPT175B_LAYERS.items():
+        W = make_weight(torch, K, N, 100)
+        codes, scales = fq.quantize(W, 3, GROUP)
+        del W
+        wbytes = codes.numel() + scales.numel() * 2
+        cases = [(1, torch.float16, fq.FQ_F16), (8, torch.float16, fq.FQ_F16)]
+        if name == "qkv":
+            cases.append((2048, torch.bfloat16, fq.FQ_BF16))
+        for M, dt, act in cases:
+            A = torch.randn((M, K), device="cuda", dtype=torch.float32).to(dt)
+            C = torch.empty((M, N), device="cuda", dtype=dt)
+            need = fq.gemm_workspace_bytes(M, N, K, 3, GROUP)
+            ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+
+            def run():
+                st = fq.gemm_raw(A.data_ptr(), act, M, N, K, codes.data_ptr(), scales.data_ptr(), 3, GROUP,
+                                 C.data_ptr(), ws.data_ptr(), ws.numel(), stream)
+                if st != fq.FQ_OK:
+                    raise fq.FqError(st, "fq_gemm")
+            ms = _timed(torch, run)
+            res[f"{name}_M{M}"] = {"us": round(ms * 1e3, 2), "weight_TBps": round(wbytes / ms / 1e9, 3),
+                                   "TFLOPs": round(2.0 * M * N * K / ms / 1e9, 1),
+                                   "plan": fq.gemm_describe(M, N, K, 3, GROUP)}
+        del codes, scales
     return res
 
 

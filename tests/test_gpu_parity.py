@@ -339,6 +339,14 @@ def test_grouped_gemm_tile_boundaries(dtype, bits, g):
     _grouped_case(dtype, bits, g, 256, 400, [32, 33, 64, 65, 128, 129, 0, 193, 40, 161, 1], seed=31)
 
 
+@pytest.mark.parametrize("dtype,bits,g", [("f16", 4, 64), ("bf16", 4, 128), ("f16", 8, 0), ("bf16", 3, 64)])
+def test_grouped_gemm_wide_matrix_uses_eight_wave_blocks_for_every_tile_size(dtype, bits, g):
+    """49 column tiles: two full 8-wave column blocks and one with a single tile, for the 32-, 64- and
+    128-row tiles alike."""
+    _say(f"grouped wide {dtype} int{bits} g={g}")
+    _grouped_case(dtype, bits, g, 256, 784, [31, 33, 64, 0, 130, 1, 97], seed=33)
+
+
 def test_grouped_gemm_more_tiles_than_one_launch_holds():
     """260 row tiles of 128 rows: the by-value tile list holds 256, so a second launch takes the rest."""
     _say("grouped 130 experts x 256 rows")

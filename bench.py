@@ -266,31 +266,34 @@ def main():
 
 
 def profile_prefill(torch, fq, workloads, reps, settle):
-    """QKV-shaped product at M = 2048 with bf16 activations: `settle` seconds of launches, then `reps` more
-    (for rocprofv3; the last `reps` records of the kernel trace are the settled ones)."""
+    """QKV-shaped product at M = 2048, first with bf16 and then with fp16 activations: `settle` seconds of
+    launches each, then `reps` more (for rocprofv3; the last records of each kernel in the trace are the
+    settled ones)."""
     K, N = workloads.OPT175B_LAYERS["qkv"]
     M = 2048
     W = make_weight(torch, K, N, 100)
     codes, scales = fq.quantize(W, BITS, GROUP)
     del W
-    A = torch.randn((M, K), device="cuda", dtype=torch.float32).to(torch.bfloat16)
-    C = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)
     need = fq.gemm_workspace_bytes(M, N, K, BITS, GROUP)
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
-    def run():
-        st = fq.gemm_raw(A.data_ptr(), fq.FQ_BF16, M, N, K, codes.data_ptr(), scales.data_ptr(), BITS, GROUP,
-                         C.data_ptr(), ws.data_ptr(), ws.numel(), stream)
-        if st != fq.FQ_OK:
-            raise fq.FqError(st, "fq_gemm")
-    t_end = time.perf_counter() + settle
-    while time.perf_counter() < t_end:
-        for _ in range(4):
+    for act, dt in ((fq.FQ_BF16, torch.bfloat16), (fq.FQ_F16, torch.float16)):
+        A = torch.randn((M, K), device="cuda", dtype=torch.float32).to(dt)
+        C = torch.empty((M, N), device="cuda", dtype=dt)
+
+        def run():
+            st = fq.gemm_raw(A.data_ptr(), act, M, N, K, codes.data_ptr(), scales.data_ptr(), BITS, GROUP,
+                             C.data_ptr(), ws.data_ptr(), ws.numel(), stream)
+            if st != fq.FQ_OK:
+                raise fq.FqError(st, "fq_gemm")
+        t_end = time.perf_counter() + settle
+        while time.perf_counter() < t_end:
+            for _ in range(4):
+                run()
+            torch.cuda.synchronize()
+        for _ in range(max(1, min(reps, 20))):
             run()
         torch.cuda.synchronize()
-    for _ in range(max(1, min(reps, 20))):
-        run()
-    torch.cuda.synchronize()
 
 
 def _timed(torch, run, settle=0.3, reps=20):

@@ -674,6 +674,64 @@ __device__ inline uint32_t scale_operand(uint16_t h) {
     }
 }
 
+// The same pre-scaled conversion cut into eight stages of about three vector instructions, so that
+// the large-M loop can put one stage behind each MFMA instead of one whole conversion (23 instructions
+// for bf16) in front of three of them: a wave's vector instructions issue while its own MFMA
+// occupies the matrix pipe, but only two or three per MFMA fit there.  Available for sub-byte codes with
+// bf16 activations (the fp16 conversion is short enough not to matter); `available` tells the kernel.
+template <int ACT, int BITS>
+struct StagedScaled {
+    static constexpr bool available = false;
+    struct State {};
+    template <int S, int T>
+    static __device__ inline void run(State&, u32x4&, const u32x4&, uint32_t) {}
+};
+template <int SB>
+struct StagedScaledBF16Sub {
+    static constexpr bool available = true;
+    struct State {
+        uint32_t lo, hi;
+        float s, b;
+    };
+    static __device__ inline float cv(uint32_t v, int byte) { return (float)((v >> (8 * byte)) & 0xffu); }
+    // one operand register: elements (2 k, 2 k + 1) of the k-step = bytes `b0`, `b1` of `v`
+    static __device__ inline uint32_t pair(const State& x, uint32_t v, int b0, int b1) {
+        return pack_bf16x2(__builtin_fmaf(cv(v, b0), x.s, x.b), __builtin_fmaf(cv(v, b1), x.s, x.b));
+    }
+    // stage S (0..7) of the conversion of k-step T of `rec` into the operand `out`; s2 = binary32 bits of
+    // the scale (read in stage 0).  Stages 0, 1, 3, 5, 7 hold 4 - 5 instructions, the others none, so that
+    // nothing but the masked code words, the scale and its offset lives across a stage boundary.
+    template <int S, int T>
+    static __device__ inline void run(State& x, u32x4& out, const u32x4& rec, uint32_t s2) {
+        constexpr uint32_t M = SB == 4 ? 0x0f0f0f0fu : 0x07070707u;
+        if constexpr (S == 0) {
+            const uint32_t w = code_word<SB, T>(rec);
+            x.lo = w & M;          // nibbles 0,2,4,6 = elements 0,4,1,5
+            x.hi = (w >> 4) & M;   // nibbles 1,3,5,7 = elements 2,6,3,7
+            asm("" : "+v"(x.lo));
+            asm("" : "+v"(x.hi));
+            x.s = bitcast<float>(s2);
+            x.b = (SB == 4 ? -8.0f : -4.0f) * x.s;
+        } else if constexpr (S == 1) {
+            out[0] = pair(x, x.lo, 0, 2);
+        } else if constexpr (S == 3) {
+            out[1] = pair(x, x.hi, 0, 2);
+        } else if constexpr (S == 5) {
+            out[2] = pair(x, x.lo, 1, 3);
+        } else if constexpr (S == 7) {
+            out[3] = pair(x, x.hi, 1, 3);
+        }
+    }
+};
+template <>
+struct StagedScaled<FQ_BF16, 4> : StagedScaledBF16Sub<4> {};
+template <>
+struct StagedScaled<FQ_BF16, 3> : StagedScaledBF16Sub<3> {};
+template <>
+struct StagedScaled<FQ_BF16_BS, 4> : StagedScaledBF16Sub<4> {};
+template <>
+struct StagedScaled<FQ_BF16_BS, 3> : StagedScaledBF16Sub<3> {};
+
 // Logical tile -> (column block, row block).  Logical tiles walk panels of PW column blocks x all
 // row blocks, so that the blocks resident on an XCD at one time share activation rows and weight
 // columns in its L2.
@@ -962,7 +1020,14 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
                       "every wave issues the same number of direct loads, or none");
         static_assert(D >= 2, "");
         constexpr int BAR_SLOT = NFR - APD - 1;
-        constexpr int W_SLOT = (STEPS - 2) * MT + (NT < MT ? NT : MT);   // after the last conversion from the set
+        // STAGED: the conversion of the next k-step's column tile c is spread over the MT MFMAs with
+        // index c * MT ... c * MT + MT - 1 of this k-step (MFMA index = mt * NT + nt), one stage behind each
+        typedef StagedScaled<ACT, BITS> Staged;
+        constexpr bool STAGED = !POST && Staged::available && MT == 8 && STEPS >= 2 && SROWS == 1;
+        // slot after which the weight set of this k-block is no longer read: after the last conversion
+        // from it (STAGED: after stage 0 of the last column tile, which reads code word and scale)
+        constexpr int W_SLOT = STAGED ? (STEPS - 2) * MT + ((NT - 1) * MT) / NT + 1
+                                      : (STEPS - 2) * MT + (NT < MT ? NT : MT);
         constexpr bool W_FIRST = W_SLOT <= BAR_SLOT;    // order of the two issue points inside a k-block
         constexpr int NWLOADS = NT + SREG * SPK * NT;   // vector loads of one load_w
         // loads issued after those of tile kb + 1 and before the barrier of k-block kb
@@ -1034,6 +1099,26 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
                     flush<ACT, BITS>(acc[mt][nt], pg[mt][nt], scales4<ACT>(sa[srow][nt]), rsum[mt][0]);
             }
         };
+        typename Staged::State cst;   // one conversion is under way at a time
+        // stage sg of the conversion of k-step T of column tile c (STAGED only; T, sg are constants after unrolling)
+        auto staged_step = [&](u32x4& out, const u32x4& rec, const SC (&s)[SREG][NT], int T, int c, int sg) {
+            if constexpr (STAGED) {
+                uint32_t s2 = 0;
+                if (sg == 0) {
+                    // opaque until here, as in convert(): keeps the wait for the scale's load out of earlier code
+                    const int srow = T / (STEPS / SROWS);
+                    uint32_t h = s[srow / SPK][c];
+                    asm volatile("" : "+v"(h));
+                    if (SPK == 2 && (srow & 1)) h >>= 16;
+                    s2 = scale_operand<ACT>((uint16_t)h);
+                }
+#define FQ_STAGE_T(S_, T_) if (sg == S_ && T == T_) Staged::template run<S_, T_ % STEPS>(cst, out, rec, s2);
+#define FQ_STAGE(S_) FQ_STAGE_T(S_, 0) FQ_STAGE_T(S_, 1) FQ_STAGE_T(S_, 2) FQ_STAGE_T(S_, 3)
+                FQ_STAGE(0) FQ_STAGE(1) FQ_STAGE(2) FQ_STAGE(3) FQ_STAGE(4) FQ_STAGE(5) FQ_STAGE(6) FQ_STAGE(7)
+#undef FQ_STAGE
+#undef FQ_STAGE_T
+            }
+        };
         auto kblock = [&](int kb, u32x4 (&qa)[NT], SC (&sa)[SREG][NT], u32x4 (&qb)[NT],
                           SC (&sb)[SREG][NT]) {
             const int nxt = cur == D ? 0 : cur + 1;
@@ -1063,10 +1148,12 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
                     } else {
                         afr[ip % (APD + 1)] = nbuf[a_rd[(ip - NFR) / MT] + ((ip - NFR) % MT) * 16 * KC];
                     }
+                    if constexpr (!STAGED) {
 #pragma unroll
-                    for (int nt = mt; nt < NT; nt += MT) {
-                        if (t + 1 < STEPS) w[(t + 1) & 1][nt] = convert(qa, sa, t + 1, nt);
-                        else w[0][nt] = convert(qb, sb, 0, nt);
+                        for (int nt = mt; nt < NT; nt += MT) {
+                            if (t + 1 < STEPS) w[(t + 1) & 1][nt] = convert(qa, sa, t + 1, nt);
+                            else w[0][nt] = convert(qb, sb, 0, nt);
+                        }
                     }
                     // keep the read and the conversion above where they are: without this the scheduler
                     // sinks them next to their uses and every fragment is then waited for
@@ -1084,6 +1171,16 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
                         if (i > 0) {
                             const int tp = (i - 1) / MT, mp = (i - 1) % MT;
                             if ((tp + 1) % GSTEPS == 0) fold(sa, tp / GSTEPS, mp);
+                        }
+                    } else if constexpr (STAGED) {
+#pragma unroll
+                        for (int nt = 0; nt < NT; ++nt) {
+                            acc[mt][nt] = mfma16x16x32<ACT>(w[t & 1][nt], a, acc[mt][nt]);
+                            // one stage of the next k-step's conversion behind this MFMA
+                            const int m = mt * NT + nt, c = m / MT, sg = m % MT;
+                            if (t + 1 < STEPS) staged_step(w[(t + 1) & 1][c], qa[c], sa, t + 1, c, sg);
+                            else staged_step(w[0][c], qb[c], sb, 0, c, sg);
+                            __builtin_amdgcn_sched_barrier(0);
                         }
                     } else {
 #pragma unroll

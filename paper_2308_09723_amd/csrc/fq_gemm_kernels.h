@@ -48,20 +48,38 @@ __device__ inline T bitcast(const F& f) {
     return __builtin_bit_cast(T, f);
 }
 
+// A wave-uniform pointer pinned in scalar registers and hidden from the optimiser: an address formed as
+// (this) + (32-bit lane offset) is then taken by a global load as scalar base + vector offset; left
+// alone, the compiler folds the lane offset into a 64-bit vector base outside the loop and adds the
+// loop-dependent uniform part with vector instructions at every load.
+// (The round trip through integers drops the address space, hence the explicit global one.)
+#define FQ_GLOBAL __attribute__((address_space(1)))
+template <typename T>
+__device__ inline const FQ_GLOBAL T* scalar_ptr(const T* p) {
+    uint32_t lo = (uint32_t)(uintptr_t)p, hi = (uint32_t)((uintptr_t)p >> 32);
+    asm volatile("" : "+s"(lo), "+s"(hi));
+    return reinterpret_cast<const FQ_GLOBAL T*>(((uintptr_t)hi << 32) | (uintptr_t)lo);
+}
+
 // One lane record of packed codes: 16 bytes, or 12 bytes (three dwords, the fourth left zero) for
 // 3-bit codes.  Either way a single vector load.
-template <int BITS, bool NONTEMPORAL>
-__device__ inline u32x4 load_rec(const char* p) {
+template <int BITS, bool NONTEMPORAL, typename P>   // P: const char* in the generic or the global address space
+__device__ inline u32x4 load_rec(P p) {
     if constexpr (BITS == 3) {
+        // three dwords with 4-byte alignment (one 12-byte load)
         typedef uint32_t u32x3 __attribute__((ext_vector_type(3)));
-        u32x3 v;
-        __builtin_memcpy(&v, p, 12);
+        typedef u32x3 __attribute__((aligned(4))) u32x3a;
+        typedef typename std::conditional<std::is_same<P, const char*>::value, const u32x3a*, const FQ_GLOBAL u32x3a*>::type R;
+        const u32x3 v = *reinterpret_cast<R>(p);
         u32x4 r = {v[0], v[1], v[2], 0u};
         return r;
-    } else if constexpr (NONTEMPORAL) {
-        return __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(p));
     } else {
-        return *reinterpret_cast<const u32x4*>(p);
+        typedef typename std::conditional<std::is_same<P, const char*>::value, const u32x4*, const FQ_GLOBAL u32x4*>::type R;
+        if constexpr (NONTEMPORAL) {
+            return __builtin_nontemporal_load(reinterpret_cast<R>(p));
+        } else {
+            return *reinterpret_cast<R>(p);
+        }
     }
 }
 
@@ -674,64 +692,6 @@ __device__ inline uint32_t scale_operand(uint16_t h) {
     }
 }
 
-// The same pre-scaled conversion cut into eight stages of about three vector instructions, so that
-// the large-M loop can put one stage behind each MFMA instead of one whole conversion (23 instructions
-// for bf16) in front of three of them: a wave's vector instructions issue while its own MFMA
-// occupies the matrix pipe, but only two or three per MFMA fit there.  Available for sub-byte codes with
-// bf16 activations (the fp16 conversion is short enough not to matter); `available` tells the kernel.
-template <int ACT, int BITS>
-struct StagedScaled {
-    static constexpr bool available = false;
-    struct State {};
-    template <int S, int T>
-    static __device__ inline void run(State&, u32x4&, const u32x4&, uint32_t) {}
-};
-template <int SB>
-struct StagedScaledBF16Sub {
-    static constexpr bool available = true;
-    struct State {
-        uint32_t lo, hi;
-        float s, b;
-    };
-    static __device__ inline float cv(uint32_t v, int byte) { return (float)((v >> (8 * byte)) & 0xffu); }
-    // one operand register: elements (2 k, 2 k + 1) of the k-step = bytes `b0`, `b1` of `v`
-    static __device__ inline uint32_t pair(const State& x, uint32_t v, int b0, int b1) {
-        return pack_bf16x2(__builtin_fmaf(cv(v, b0), x.s, x.b), __builtin_fmaf(cv(v, b1), x.s, x.b));
-    }
-    // stage S (0..7) of the conversion of k-step T of `rec` into the operand `out`; s2 = binary32 bits of
-    // the scale (read in stage 0).  Stages 0, 1, 3, 5, 7 hold 4 - 5 instructions, the others none, so that
-    // nothing but the masked code words, the scale and its offset lives across a stage boundary.
-    template <int S, int T>
-    static __device__ inline void run(State& x, u32x4& out, const u32x4& rec, uint32_t s2) {
-        constexpr uint32_t M = SB == 4 ? 0x0f0f0f0fu : 0x07070707u;
-        if constexpr (S == 0) {
-            const uint32_t w = code_word<SB, T>(rec);
-            x.lo = w & M;          // nibbles 0,2,4,6 = elements 0,4,1,5
-            x.hi = (w >> 4) & M;   // nibbles 1,3,5,7 = elements 2,6,3,7
-            asm("" : "+v"(x.lo));
-            asm("" : "+v"(x.hi));
-            x.s = bitcast<float>(s2);
-            x.b = (SB == 4 ? -8.0f : -4.0f) * x.s;
-        } else if constexpr (S == 1) {
-            out[0] = pair(x, x.lo, 0, 2);
-        } else if constexpr (S == 3) {
-            out[1] = pair(x, x.hi, 0, 2);
-        } else if constexpr (S == 5) {
-            out[2] = pair(x, x.lo, 1, 3);
-        } else if constexpr (S == 7) {
-            out[3] = pair(x, x.hi, 1, 3);
-        }
-    }
-};
-template <>
-struct StagedScaled<FQ_BF16, 4> : StagedScaledBF16Sub<4> {};
-template <>
-struct StagedScaled<FQ_BF16, 3> : StagedScaledBF16Sub<3> {};
-template <>
-struct StagedScaled<FQ_BF16_BS, 4> : StagedScaledBF16Sub<4> {};
-template <>
-struct StagedScaled<FQ_BF16_BS, 3> : StagedScaledBF16Sub<3> {};
-
 // Logical tile -> (column block, row block).  Logical tiles walk panels of PW column blocks x all
 // row blocks, so that the blocks resident on an XCD at one time share activation rows and weight
 // columns in its L2.
@@ -915,9 +875,20 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
     typedef uint16_t u16x2 __attribute__((ext_vector_type(2)));
     typedef typename std::conditional<POST, u32x2, uint32_t>::type SC;
     SC sc[SREG][NT], sc_n[SREG][NT];
+    // addresses are formed as (wave-uniform 64-bit base) + (32-bit lane offset), which the loads take as
+    // they are (scalar base + vector offset), instead of 64-bit vector arithmetic per load
+    // (used by the 128-row shapes; in the lower ones it costs registers they do not have)
+    constexpr bool SADDR = MT == 8;
+    const uint32_t lane_rec = (uint32_t)lane * RB;
     auto load_q = [&](u32x4 (&q)[NT], int kb) {
+        if constexpr (SADDR) {
+            const int64_t kb_bytes = (int64_t)kb * kb_stride * RB;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) q[nt] = load_rec<BITS, false>(wbase[nt] + ((int64_t)kb * kb_stride + lane) * RB);
+            for (int nt = 0; nt < NT; ++nt) q[nt] = load_rec<BITS, false>(scalar_ptr(wbase[nt] + kb_bytes) + lane_rec);
+        } else {
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) q[nt] = load_rec<BITS, false>(wbase[nt] + ((int64_t)kb * kb_stride + lane) * RB);
+        }
     };
     auto load_s = [&](SC (&s)[SREG][NT], int kb) {
 #pragma unroll
@@ -930,15 +901,15 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
             } else if constexpr (SPK == 1) {
                 const int64_t srow = (int64_t)((kb * KBLK + r * (KBLK / SROWS)) / g) * N;
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt) s[r][nt] = sbase[nt][srow + ml];
+                for (int nt = 0; nt < NT; ++nt) s[r][nt] = SADDR ? scalar_ptr(sbase[nt] + srow)[(uint32_t)ml] : sbase[nt][srow + ml];
             } else {
                 const int64_t srow0 = (int64_t)((kb * KBLK + (2 * r) * (KBLK / SROWS)) / g) * N;
                 const int64_t srow1 = (int64_t)((kb * KBLK + (2 * r + 1) * (KBLK / SROWS)) / g) * N;
 #pragma unroll
                 for (int nt = 0; nt < NT; ++nt) {
                     u16x2 pr;
-                    pr[0] = sbase[nt][srow0 + ml];
-                    pr[1] = sbase[nt][srow1 + ml];
+                    pr[0] = SADDR ? scalar_ptr(sbase[nt] + srow0)[(uint32_t)ml] : sbase[nt][srow0 + ml];
+                    pr[1] = SADDR ? scalar_ptr(sbase[nt] + srow1)[(uint32_t)ml] : sbase[nt][srow1 + ml];
                     s[r][nt] = bitcast<uint32_t>(pr);
                 }
             }
@@ -961,6 +932,7 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
         for (int r = 0; r < UPT; ++r)
             if (a_dst[r] >= 0) dst[a_dst[r]] = a_ok[r] ? areg[r] : zero4;
     };
+    uint32_t s2c[NT];   // widened scale of the scale row under way, per column tile
     auto convert = [&](const u32x4 (&q)[NT], const SC (&s)[SREG][NT], int t, int nt) -> u32x4 {
         if constexpr (POST) {
             if (t == 0) return Dequant<ACT, BITS>::template run<0>(q[nt], magic);
@@ -968,13 +940,18 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
             if (STEPS > 2 && t == 2) return Dequant<ACT, BITS>::template run<2 % STEPS>(q[nt], magic);
             return Dequant<ACT, BITS>::template run<3 % STEPS>(q[nt], magic);
         } else {
-            // opaque until here: otherwise the widening of the scale is moved to the end of the previous
-            // k-block, and with it the wait for the scale's load
+            // The scale is widened once per scale row and column tile (the k-steps of a row come one
+            // after the other, the first of them first) and kept in s2c.  Its stored form stays opaque
+            // until then: otherwise the widening is moved to the end of the previous k-block, and with
+            // it the wait for the scale's load.
             const int srow = t / (STEPS / SROWS);
-            uint32_t h = s[srow / SPK][nt];
-            asm volatile("" : "+v"(h));
-            if (SPK == 2 && (srow & 1)) h >>= 16;
-            const uint32_t s2 = scale_operand<ACT>((uint16_t)h);
+            if (t % (STEPS / SROWS) == 0) {
+                uint32_t h = s[srow / SPK][nt];
+                asm volatile("" : "+v"(h));
+                if (SPK == 2 && (srow & 1)) h >>= 16;
+                s2c[nt] = scale_operand<ACT>((uint16_t)h);
+            }
+            const uint32_t s2 = s2c[nt];
             if (t == 0) return DequantScaled<ACT, BITS>::template run<0>(q[nt], magic, s2);
             if (t == 1) return DequantScaled<ACT, BITS>::template run<1>(q[nt], magic, s2);
             if (STEPS > 2 && t == 2) return DequantScaled<ACT, BITS>::template run<2 % STEPS>(q[nt], magic, s2);
@@ -1020,14 +997,7 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
                       "every wave issues the same number of direct loads, or none");
         static_assert(D >= 2, "");
         constexpr int BAR_SLOT = NFR - APD - 1;
-        // STAGED: the conversion of the next k-step's column tile c is spread over the MT MFMAs with
-        // index c * MT ... c * MT + MT - 1 of this k-step (MFMA index = mt * NT + nt), one stage behind each
-        typedef StagedScaled<ACT, BITS> Staged;
-        constexpr bool STAGED = !POST && Staged::available && MT == 8 && STEPS >= 2 && SROWS == 1;
-        // slot after which the weight set of this k-block is no longer read: after the last conversion
-        // from it (STAGED: after stage 0 of the last column tile, which reads code word and scale)
-        constexpr int W_SLOT = STAGED ? (STEPS - 2) * MT + ((NT - 1) * MT) / NT + 1
-                                      : (STEPS - 2) * MT + (NT < MT ? NT : MT);
+        constexpr int W_SLOT = (STEPS - 2) * MT + (NT < MT ? NT : MT);   // after the last conversion from the set
         constexpr bool W_FIRST = W_SLOT <= BAR_SLOT;    // order of the two issue points inside a k-block
         constexpr int NWLOADS = NT + SREG * SPK * NT;   // vector loads of one load_w
         // loads issued after those of tile kb + 1 and before the barrier of k-block kb
@@ -1099,26 +1069,6 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
                     flush<ACT, BITS>(acc[mt][nt], pg[mt][nt], scales4<ACT>(sa[srow][nt]), rsum[mt][0]);
             }
         };
-        typename Staged::State cst;   // one conversion is under way at a time
-        // stage sg of the conversion of k-step T of column tile c (STAGED only; T, sg are constants after unrolling)
-        auto staged_step = [&](u32x4& out, const u32x4& rec, const SC (&s)[SREG][NT], int T, int c, int sg) {
-            if constexpr (STAGED) {
-                uint32_t s2 = 0;
-                if (sg == 0) {
-                    // opaque until here, as in convert(): keeps the wait for the scale's load out of earlier code
-                    const int srow = T / (STEPS / SROWS);
-                    uint32_t h = s[srow / SPK][c];
-                    asm volatile("" : "+v"(h));
-                    if (SPK == 2 && (srow & 1)) h >>= 16;
-                    s2 = scale_operand<ACT>((uint16_t)h);
-                }
-#define FQ_STAGE_T(S_, T_) if (sg == S_ && T == T_) Staged::template run<S_, T_ % STEPS>(cst, out, rec, s2);
-#define FQ_STAGE(S_) FQ_STAGE_T(S_, 0) FQ_STAGE_T(S_, 1) FQ_STAGE_T(S_, 2) FQ_STAGE_T(S_, 3)
-                FQ_STAGE(0) FQ_STAGE(1) FQ_STAGE(2) FQ_STAGE(3) FQ_STAGE(4) FQ_STAGE(5) FQ_STAGE(6) FQ_STAGE(7)
-#undef FQ_STAGE
-#undef FQ_STAGE_T
-            }
-        };
         auto kblock = [&](int kb, u32x4 (&qa)[NT], SC (&sa)[SREG][NT], u32x4 (&qb)[NT],
                           SC (&sb)[SREG][NT]) {
             const int nxt = cur == D ? 0 : cur + 1;
@@ -1148,12 +1098,10 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
                     } else {
                         afr[ip % (APD + 1)] = nbuf[a_rd[(ip - NFR) / MT] + ((ip - NFR) % MT) * 16 * KC];
                     }
-                    if constexpr (!STAGED) {
 #pragma unroll
-                        for (int nt = mt; nt < NT; nt += MT) {
-                            if (t + 1 < STEPS) w[(t + 1) & 1][nt] = convert(qa, sa, t + 1, nt);
-                            else w[0][nt] = convert(qb, sb, 0, nt);
-                        }
+                    for (int nt = mt; nt < NT; nt += MT) {
+                        if (t + 1 < STEPS) w[(t + 1) & 1][nt] = convert(qa, sa, t + 1, nt);
+                        else w[0][nt] = convert(qb, sb, 0, nt);
                     }
                     // keep the read and the conversion above where they are: without this the scheduler
                     // sinks them next to their uses and every fragment is then waited for
@@ -1171,16 +1119,6 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
                         if (i > 0) {
                             const int tp = (i - 1) / MT, mp = (i - 1) % MT;
                             if ((tp + 1) % GSTEPS == 0) fold(sa, tp / GSTEPS, mp);
-                        }
-                    } else if constexpr (STAGED) {
-#pragma unroll
-                        for (int nt = 0; nt < NT; ++nt) {
-                            acc[mt][nt] = mfma16x16x32<ACT>(w[t & 1][nt], a, acc[mt][nt]);
-                            // one stage of the next k-step's conversion behind this MFMA
-                            const int m = mt * NT + nt, c = m / MT, sg = m % MT;
-                            if (t + 1 < STEPS) staged_step(w[(t + 1) & 1][c], qa[c], sa, t + 1, c, sg);
-                            else staged_step(w[0][c], qb[c], sb, 0, c, sg);
-                            __builtin_amdgcn_sched_barrier(0);
                         }
                     } else {
 #pragma unroll

@@ -187,7 +187,8 @@ int fq_gemm_sf(const void* A, int act_dtype, int64_t M, int64_t N, int64_t K, co
  * Experts are cut into row tiles of up to three sizes and each size is one kernel; these
  * independent kernels run on `stream` and on two streams the library creates (once per
  * device, default priority, never destroyed), forked from and joined back to `stream` with
- * events, so the call still behaves as one asynchronous operation on `stream`.
+ * events, so the call still behaves as one asynchronous operation on `stream`.  Calls from several host
+ * threads are serialised on the host while they enqueue (the side streams and events are shared).
  */
 int fq_gemm_grouped(const void* A, int act_dtype, const int32_t* offsets_host, int E, int64_t N,
                     int64_t K, const void* codes, const void* scales_f16, int bits, int group_size,

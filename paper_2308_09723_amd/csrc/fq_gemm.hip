@@ -231,7 +231,8 @@ struct fq_side {
     hipStream_t s[2];
     hipEvent_t fork, join[2];
 };
-std::mutex g_side_mutex;
+std::mutex g_side_mutex;    // guards the creation of the side streams
+std::mutex g_fork_mutex;    // serialises fork ... join sequences: the events are shared by all callers on a device
 fq_side g_side[64];
 
 fq_side* side_streams() {
@@ -269,6 +270,9 @@ int fq_launch_gemm_grouped(const void* A, int act, const int32_t* offsets, int E
     }
     hipStream_t streams[3] = {stream, stream, stream};
     fq_side* side = (int)has[0] + (int)has[1] + (int)has[2] > 1 ? side_streams() : nullptr;
+    // host threads that fork at the same time would record and wait on each other's events
+    std::unique_lock<std::mutex> fork_lock(g_fork_mutex, std::defer_lock);
+    if (side) fork_lock.lock();
     bool forked[2] = {false, false};
     if (side) {
         // the first tile size present stays on the caller's stream, the others go to the side streams

@@ -68,9 +68,15 @@ size_t fq_codes_bytes(int64_t K, int64_t N, int bits);
 /* Size in bytes of the scale matrix [K/g, N] of 16-bit values (either format).  0 on invalid arguments. */
 size_t fq_scales_bytes(int64_t K, int64_t N, int group_size);
 
-/* Bytes of scratch fq_gemm needs for this problem (split-K partial sums; may be 0).
- * The value is an upper bound that depends only on the arguments. */
+/* Bytes of scratch fq_gemm needs for this problem (split-K partial sums, rewritten activations; may be
+ * 0).  The value is an upper bound that depends only on the arguments. */
 size_t fq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits, int group_size);
+
+/* The exact need of fq_gemm / fq_gemm_sf for one activation type (an fq_dtype) and scale format (an
+ * fq_scale_format); fq_gemm_workspace_bytes() is the largest of these.  (bfloat16 activations of wide
+ * matrices are rewritten row by row before the product, which takes M*K*2 + M*4 bytes more.) */
+size_t fq_gemm_workspace_bytes_for(int64_t M, int64_t N, int64_t K, int bits, int group_size, int act_dtype,
+                                   int scale_format);
 
 /* Same for fq_gemm_grouped, with total_rows = offsets[E]. */
 size_t fq_gemm_grouped_workspace_bytes(int64_t total_rows, int E, int64_t N, int64_t K, int bits,
@@ -151,7 +157,10 @@ int fq_quant_error_sf(const void* W_f16, int64_t K, int64_t N, int bits, int gro
 /*
  * fq_gemm -- the fused dequantise-and-multiply product of section 4.1 ("GPU kernel
  * implementations"):  C[m, n] = sum_k A[m, k] * (q[k, n] * s[k / g, n]),
- * accumulated in binary32, written in the activation's data type.
+ * accumulated in binary32, written in the activation's data type.  (For bfloat16 activations and
+ * wide matrices with many rows the product is evaluated on the fp16 matrix path after each
+ * activation row has been divided by a power of two that fits it into binary16; the result is
+ * rescaled exactly and rounded to bfloat16 once.)
  *
  *   A           in   [M, K] row-major, act_dtype
  *   codes       in   packed codes written by fq_quantize for the same (K, N, bits)

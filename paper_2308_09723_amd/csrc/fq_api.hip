@@ -50,12 +50,19 @@ size_t fq_scales_bytes(int64_t K, int64_t N, int group_size) {
     return (size_t)((K / g) * N * 2);
 }
 
-size_t fq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits, int group_size) {
+size_t fq_gemm_workspace_bytes_for(int64_t M, int64_t N, int64_t K, int bits, int group_size, int act_dtype,
+                                   int scale_format) {
     int g = 0;
     if (M <= 0 || check_shape(K, N, bits, group_size, &g) != FQ_OK) return 0;
     const fq_gemm_plan plan = fq_plan_gemm(M, N, K, bits, g);
-    const int parts = plan.splits > 1 ? plan.splits : (plan.tail_tiles > 0 ? plan.tail_splits : 0);
-    return (size_t)parts * (size_t)M * (size_t)N * sizeof(float);
+    size_t need = fq_partial_bytes(plan, M, N);
+    if (fq_via_f16(act_dtype, scale_format, plan, N)) need += fq_a16_bytes(M, K) + (size_t)M * sizeof(float);
+    return need;
+}
+
+size_t fq_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K, int bits, int group_size) {
+    // the largest need over the activation types and scale formats
+    return fq_gemm_workspace_bytes_for(M, N, K, bits, group_size, FQ_BF16, FQ_SCALE_F16);
 }
 
 size_t fq_gemm_grouped_workspace_bytes(int64_t total_rows, int E, int64_t N, int64_t K, int bits,
@@ -185,7 +192,7 @@ int fq_gemm_sf(const void* A, int act_dtype, int64_t M, int64_t N, int64_t K, co
     if (M == 0) return FQ_OK;
     if (!A || !codes || !scales_f16 || !C) return FQ_ERR_INVALID_ARG;
     if (M > (int64_t)1 << 24) return FQ_ERR_UNSUPPORTED;
-    const size_t need = fq_gemm_workspace_bytes(M, N, K, bits, group_size);
+    const size_t need = fq_gemm_workspace_bytes_for(M, N, K, bits, group_size, act_dtype, scale_format);
     if (need > 0 && (!workspace || workspace_bytes < need)) return FQ_ERR_WORKSPACE;
     return fq_launch_gemm(A, kind, M, N, K, codes, scales_f16, bits, g, C, workspace,
                           (hipStream_t)stream);

@@ -96,27 +96,44 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
                                                  : tiles * plan.splits));
         fq_group_items none;
         none.count = 0;
-#define FQ_MMA_LAUNCH_SR(MT_, W_, PIPE_, SR_)                                                            \
+#define FQ_MMA_LAUNCH_SR(ACT_, A_, RS_, MT_, W_, PIPE_, SR_)                                              \
     do {                                                                                                \
-        auto kern = fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, SR_, false, PIPE_,                  \
-                                       use_post(ACT, BITS, MT_, SR_, PIPE_)>;                                 \
+        auto kern = fq_gemm_mma_kernel<ACT_, BITS, MT_, MMA_NT, W_, SR_, false, PIPE_,                 \
+                                       use_post(ACT_, BITS, MT_, SR_, PIPE_)>;                          \
         if (lds > 65536) {                                                                              \
             static std::atomic<uint64_t> raised;                                                        \
             if (raise_lds_limit((const void*)kern, raised) != FQ_OK) return FQ_ERR_HIP;                 \
         }                                                                                               \
-        hipLaunchKernelGGL(kern, grid, dim3(W_ * 64), lds, stream, (const uint16_t*)A,                  \
+        hipLaunchKernelGGL(kern, grid, dim3(W_ * 64), lds, stream, (const uint16_t*)(A_),               \
                            (const u32x4*)codes, (const uint16_t*)scales, (uint16_t*)C, partial, (int)M, \
                            (int)N, (int)K, g, plan.kb_per_split, plan.splits, nblocks_n, nblocks_m,     \
                            (int64_t)0, (int64_t)0, none, plan.tail_tiles, plan.tail_splits,             \
-                           plan.tail_kbs);                                                              \
+                           plan.tail_kbs, (const float*)(RS_));                                         \
     } while (0)
-#define FQ_MMA_LAUNCH(MT_, W_, PIPE_)                                                                   \
+#define FQ_MMA_LAUNCH_ACT(ACT_, A_, RS_, MT_, W_, PIPE_)                                                \
     do {                                                                                                \
-        if (sr == 1) FQ_MMA_LAUNCH_SR(MT_, W_, PIPE_, 1);                                               \
-        else if (sr == 2) FQ_MMA_LAUNCH_SR(MT_, W_, PIPE_, 2);                                          \
-        else if constexpr (BITS != 8) FQ_MMA_LAUNCH_SR(MT_, W_, PIPE_, 4);                              \
+        if (sr == 1) FQ_MMA_LAUNCH_SR(ACT_, A_, RS_, MT_, W_, PIPE_, 1);                                \
+        else if (sr == 2) FQ_MMA_LAUNCH_SR(ACT_, A_, RS_, MT_, W_, PIPE_, 2);                           \
+        else if constexpr (BITS != 8) FQ_MMA_LAUNCH_SR(ACT_, A_, RS_, MT_, W_, PIPE_, 4);               \
     } while (0)
-        if (plan.waves == 8) {
+#define FQ_MMA_LAUNCH(MT_, W_, PIPE_) FQ_MMA_LAUNCH_ACT(ACT, A, nullptr, MT_, W_, PIPE_)
+        bool launched = false;
+        if constexpr (ACT == FQ_BF16) {
+            if (fq_via_f16(FQ_BF16, FQ_SCALE_F16, plan, N)) {
+                // bf16 activations on the fp16 matrix path: rows rewritten as binary16 first (the
+                // buffers sit behind the split-K partials in the workspace)
+                char* extra = (char*)workspace + fq_partial_bytes(plan, M, N);
+                uint16_t* A16 = (uint16_t*)extra;
+                float* rs = (float*)(extra + fq_a16_bytes(M, K));
+                hipLaunchKernelGGL(fq_rows_to_f16_kernel<256>, dim3((unsigned)M), dim3(256), 0, stream,
+                                   (const uint16_t*)A, (int)K, A16, rs);
+                if (plan.waves == 8) FQ_MMA_LAUNCH_ACT(FQ_BF16_VIA_F16, A16, rs, 8, 8, 2);
+                else FQ_MMA_LAUNCH_ACT(FQ_BF16_VIA_F16, A16, rs, 8, 4, 0);
+                launched = true;
+            }
+        }
+        if (launched) {
+        } else if (plan.waves == 8) {
             if (plan.mt == 2) FQ_MMA_LAUNCH(2, 8, FQ_RING_MT2);
             else if (plan.mt == 4) FQ_MMA_LAUNCH(4, 8, FQ_RING_MT4);
             else FQ_MMA_LAUNCH(8, 8, 2);
@@ -126,6 +143,7 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
             else FQ_MMA_LAUNCH(8, 4, 0);
         }
 #undef FQ_MMA_LAUNCH
+#undef FQ_MMA_LAUNCH_ACT
 #undef FQ_MMA_LAUNCH_SR
     }
     if (plan.kind == 1 && plan.tail_tiles > 0) {
@@ -184,7 +202,7 @@ int launch_grouped_typed(const void* A, const int32_t* offsets, int E, int64_t N
         hipLaunchKernelGGL(kern, grid, dim3(W_ * 64), lds, stream, (const uint16_t*)A,                  \
                            (const u32x4*)codes, (const uint16_t*)scales, (uint16_t*)C, (float*)nullptr, \
                            0, (int)N, (int)K, g, KB, 1, nblocks_n, items.count, codes_stride16,         \
-                           scales_stride, items, 0, 1, 0);                                              \
+                           scales_stride, items, 0, 1, 0, (const float*)nullptr);                       \
     } while (0)
 #define FQ_GROUPED_LAUNCH(MT_, W_, PIPE_)                                                               \
     do {                                                                                                \

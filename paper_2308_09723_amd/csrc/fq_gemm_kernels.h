@@ -34,6 +34,15 @@ namespace fqk {
 // scale matrix holds bfloat16 values (section 4.1, "GPU kernel implementations": scales of the
 // activation's data type).  It behaves as FQ_BF16 everywhere except where a scale is widened.
 #define FQ_BF16_BS 2
+// Fourth value: bfloat16 activations and output, computed on the fp16 matrix path.  A small kernel
+// first rewrites the activation rows as binary16, each row divided by a power of two that brings its
+// largest element into [2^14, 2^15) (exact for every element within 2^-29 of the row's largest; what
+// lies further below loses low bits or vanishes, 2^-25 of the row's scale at most); the weights are
+// dequantised to binary16 (three more significand bits than bfloat16), and the epilogue multiplies the
+// binary32 sums by the row's power of two before rounding to bfloat16.  The fp16 conversion of the
+// codes is packed (13 vector instructions per 8 weights against 23 for bf16), which is what the large-M
+// loop is short of.  Used by the 128-row shapes only.
+#define FQ_BF16_VIA_F16 3
 
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -85,7 +94,7 @@ __device__ inline u32x4 load_rec(P p) {
 
 template <int ACT>
 __device__ inline f32x4 mfma16x16x32(const u32x4& w, const u32x4& a, const f32x4& c) {
-    if constexpr (ACT == FQ_F16) {
+    if constexpr (ACT == FQ_F16 || ACT == FQ_BF16_VIA_F16) {
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(bitcast<f16x8>(w), bitcast<f16x8>(a), c, 0, 0, 0);
     } else {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(bitcast<bf16x8>(w), bitcast<bf16x8>(a), c, 0, 0, 0);
@@ -222,6 +231,8 @@ struct Dequant<FQ_BF16, 8> {
 
 template <int BITS>
 struct Dequant<FQ_BF16_BS, BITS> : Dequant<FQ_BF16, BITS> {};
+template <int BITS>
+struct Dequant<FQ_BF16_VIA_F16, BITS> : Dequant<FQ_F16, BITS> {};
 
 template <int ACT>
 __device__ inline u32x4 ones_operand() {
@@ -679,11 +690,13 @@ struct DequantScaled<FQ_BF16, 8> {
 
 template <int BITS>
 struct DequantScaled<FQ_BF16_BS, BITS> : DequantScaled<FQ_BF16, BITS> {};
+template <int BITS>
+struct DequantScaled<FQ_BF16_VIA_F16, BITS> : DequantScaled<FQ_F16, BITS> {};
 
 // stored scale (16 bits) -> the form DequantScaled wants
 template <int ACT>
 __device__ inline uint32_t scale_operand(uint16_t h) {
-    if constexpr (ACT == FQ_F16) {
+    if constexpr (ACT == FQ_F16 || ACT == FQ_BF16_VIA_F16) {
         return (uint32_t)h | ((uint32_t)h << 16);
     } else if constexpr (ACT == FQ_BF16_BS) {
         return (uint32_t)h << 16;
@@ -730,6 +743,56 @@ __global__ __launch_bounds__(256) void fq_reduce_tail_kernel(const float* __rest
     }
 }
 
+// bfloat16 rows -> binary16 rows divided by a power of two per row (see FQ_BF16_VIA_F16): block r
+// rewrites row r.  e = (exponent of the row's largest element) - 14, kept within +-100;
+// A16[r, :] = A[r, :] * 2^-e rounded to binary16, rowscale[r] = 2^e.
+template <int THREADS>   // (a template so that every translation unit may hold a copy)
+__global__ __launch_bounds__(THREADS) void fq_rows_to_f16_kernel(const uint16_t* __restrict__ A, int K,
+                                                             uint16_t* __restrict__ A16,
+                                                             float* __restrict__ rowscale) {
+    __shared__ uint32_t red[4];
+    const int64_t r = blockIdx.x;
+    const u32x4* src = reinterpret_cast<const u32x4*>(A + r * K);
+    u32x4* dst = reinterpret_cast<u32x4*>(A16 + r * K);
+    const int units = K / 8;
+    uint32_t m = 0;
+    static_assert(THREADS == 256, "four waves are reduced below");
+    for (int u = threadIdx.x; u < units; u += 256) {
+        const u32x4 v = src[u];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t a0 = v[i] & 0x7fffu, a1 = (v[i] >> 16) & 0x7fffu;
+            m = a0 > m ? a0 : m;
+            m = a1 > m ? a1 : m;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint32_t t = (uint32_t)__shfl_xor((int)m, o, 64);
+        m = t > m ? t : m;
+    }
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    m = red[0];
+#pragma unroll
+    for (int i = 1; i < 4; ++i) m = red[i] > m ? red[i] : m;
+    int e = (int)(m >> 7) - 127 - 14;
+    e = e < -100 ? -100 : (e > 100 ? 100 : e);
+    if (threadIdx.x == 0) rowscale[r] = ldexpf(1.0f, e);
+    for (int u = threadIdx.x; u < units; u += 256) {
+        const u32x4 v = src[u];
+        u32x4 o;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float f0 = ldexpf(bitcast<float>(v[i] << 16), -e);
+            const float f1 = ldexpf(bitcast<float>(v[i] & 0xffff0000u), -e);
+            const f16x2 h = {(_Float16)f0, (_Float16)f1};
+            o[i] = bitcast<uint32_t>(h);
+        }
+        dst[u] = o;
+    }
+}
+
 // s_waitcnt vmcnt(N) only (the other counters left alone); gfx9 encoding: vmcnt in bits 3:0 and 15:14
 template <int N>
 __device__ inline void wait_vmcnt() {
@@ -742,7 +805,7 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
     const uint16_t* __restrict__ A, const u32x4* __restrict__ codes, const uint16_t* __restrict__ scales,
     uint16_t* __restrict__ C, float* __restrict__ partial, int M, int N, int K, int g, int kb_per_split,
     int splits, int nblocks_n, int nblocks_m, int64_t codes_stride16, int64_t scales_stride,
-    fq_group_items items, int tail_tiles, int tail_splits, int tail_kbs) {
+    fq_group_items items, int tail_tiles, int tail_splits, int tail_kbs, const float* __restrict__ rowscale) {
     constexpr int KBLK = fq_kblk(BITS);
     constexpr int STEPS = KBLK / FQ_KSTEP;
     constexpr int KC = KBLK / 8;
@@ -1201,6 +1264,12 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
     for (int mt = 0; mt < MT; ++mt) {
         const int row = mt * 16 + ml;
         if (row >= rows) continue;
+        if constexpr (ACT == FQ_BF16_VIA_F16) {
+            // back from the row's normalised scale (a power of two: exact)
+            const float rs = rowscale[row0 + row];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) acc[mt][nt] *= rs;
+        }
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
             if (!tvalid[nt]) continue;

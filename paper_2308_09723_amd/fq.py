@@ -48,6 +48,7 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "fq_codes_bytes": (sz, [i64, i64, i32]),
         "fq_scales_bytes": (sz, [i64, i64, i32]),
         "fq_gemm_workspace_bytes": (sz, [i64, i64, i64, i32, i32]),
+        "fq_gemm_workspace_bytes_for": (sz, [i64, i64, i64, i32, i32, i32, i32]),
         "fq_gemm_grouped_workspace_bytes": (sz, [i64, i32, i64, i64, i32, i32]),
         "fq_choose_group_workspace_bytes": (sz, [i64, i64, i32, i32]),
         "fq_quantize": (i32, [vp, i64, i64, i32, i32, vp, vp, vp]),
@@ -82,7 +83,7 @@ EXPORTED = [
     "fq_choose_group_workspace_bytes", "fq_quantize", "fq_unpack", "fq_choose_group", "fq_gemm",
     "fq_gemm_grouped", "fq_gemm_describe", "fq_status_string", "fq_version",
     "fq_quant_error_workspace_bytes", "fq_quant_error",
-    "fq_quantize_sf", "fq_quant_error_sf", "fq_gemm_sf", "fq_gemm_grouped_sf",
+    "fq_quantize_sf", "fq_quant_error_sf", "fq_gemm_sf", "fq_gemm_grouped_sf", "fq_gemm_workspace_bytes_for",
 ]
 
 
@@ -105,6 +106,10 @@ def scales_bytes(K, N, group_size):
 
 def gemm_workspace_bytes(M, N, K, bits, group_size):
     return int(load().fq_gemm_workspace_bytes(M, N, K, bits, group_size))
+
+
+def gemm_workspace_bytes_for(M, N, K, bits, group_size, act_dtype, scale_format=FQ_SCALE_F16):
+    return int(load().fq_gemm_workspace_bytes_for(M, N, K, bits, group_size, act_dtype, scale_format))
 
 
 def gemm_describe(M, N, K, bits, group_size):

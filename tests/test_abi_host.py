@@ -181,7 +181,10 @@ def test_plans_are_consistent_over_many_shapes():
         gs = [g for g in (32, 64, 128, 256, 0) if g == 0 or K % g == 0]
         g = int(rng.choice(gs))
         desc = fq.gemm_describe(M, N, K, bits, g)
-        ws = fq.gemm_workspace_bytes(M, N, K, bits, g)
+        ws = fq.gemm_workspace_bytes_for(M, N, K, bits, g, fq.FQ_F16)
+        ws_bf16 = fq.gemm_workspace_bytes_for(M, N, K, bits, g, fq.FQ_BF16)
+        assert fq.gemm_workspace_bytes(M, N, K, bits, g) == max(ws, ws_bf16)
+        assert fq.gemm_workspace_bytes_for(M, N, K, bits, g, fq.FQ_BF16, fq.FQ_SCALE_BF16) == ws
         KB = K // kblk
         if desc.startswith("small-m"):
             f = dict(re.findall(r"(\w+)=(\d+)", desc))
@@ -201,6 +204,9 @@ def test_plans_are_consistent_over_many_shapes():
             assert mt == 8 or M <= 256                     # the small block shapes compete up to 256 rows only
             assert mt == 2 or mt * 8 < M                   # no block more than twice as tall as the matrix
             assert splits >= 1 and kbs * splits >= KB and kbs * (splits - 1) < KB
+            # bf16 rows are rewritten as binary16 for the 128-row shapes of wide matrices
+            extra = (-(-(M * K * 2) // 256) * 256 + M * 4) if (mt == 8 and N >= 8192) else 0
+            assert ws_bf16 == ws + extra
             tiles = -(-(N // 16) // (waves * 3)) * -(-M // (mt * 16))
             if tail_tiles:
                 assert splits == 1 and 0 < tail_tiles < tiles and 2 <= tail_splits <= 8

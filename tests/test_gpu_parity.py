@@ -351,3 +351,67 @@ def test_grouped_gemm_more_tiles_than_one_launch_holds():
     """260 row tiles of 128 rows: the by-value tile list holds 256, so a second launch takes the rest."""
     _say("grouped 130 experts x 256 rows")
     _grouped_case("f16", 4, 128, 128, 48, [256] * 130, seed=32, shared_weights=True)
+
+
+# ------------------------------------------------------------------ bf16 activations on the fp16 matrix path
+def _rows_case(M, K, N, bits, g, seed, row_scales):
+    """bf16 activations whose rows are scaled by `row_scales` (wide matrix, 128-row blocks: the rows are
+    rewritten as binary16 over a power of two per row); parity per row, relative to that row's largest output."""
+    fq = _fq()
+    W = workloads.weights_gaussian(K, N, seed, outlier_prob=1e-3)
+    A = workloads.activations(M, K, "bf16", seed + 1).astype(np.float64)
+    A *= np.asarray(row_scales, dtype=np.float64)[:, None]
+    A = workloads.round_to_bf16(A.astype(np.float32))
+    codes, scales, q_ref, s_ref = assert_quantizer_parity(W, bits, g)
+    assert fq.gemm_workspace_bytes_for(M, N, K, bits, g, fq.FQ_BF16) > fq.gemm_workspace_bytes_for(M, N, K, bits, g, fq.FQ_F16)
+    C = from_dev_act(fq.gemm(to_dev_act(A, "bf16"), codes, scales, bits, g), "bf16")
+    C_ref = oracle.gemm_ref(A, q_ref, s_ref)
+    assert np.all(np.isfinite(C))
+    for r in range(M):
+        top = np.max(np.abs(C_ref[r]))
+        err = np.max(np.abs(C[r] - C_ref[r]))
+        assert err <= TOL["bf16"] * top + 1e-37, f"row {r} (scale {row_scales[r]:.3g}): {err} > {TOL['bf16']} * {top}"
+
+
+@pytest.mark.parametrize("bits,g", [(4, 128), (4, 64), (8, 0), (3, 32)])
+def test_gemm_bf16_rows_rewritten_as_binary16(bits, g):
+    _say(f"bf16 via fp16 path int{bits} g={g}")
+    M, K, N = 270, 256, 8192            # more than 256 rows: 128-row blocks
+    rng = np.random.default_rng(77)
+    row_scales = 2.0 ** rng.integers(-60, 60, size=M).astype(np.float64)
+    row_scales[0] = 0.0                 # an all-zero row
+    row_scales[1] = 2.0 ** -120         # far below the binary16 range
+    row_scales[2] = 2.0 ** 110          # far above it
+    row_scales[3] = 1.0
+    _rows_case(M, K, N, bits, g, 9100 + bits + g, row_scales)
+
+
+def test_gemm_bf16_rows_with_outliers_inside_a_row():
+    """One element 2^20 times larger than the rest of its row: the small elements keep their relative
+    precision (they are still normal binary16 numbers after the row's division)."""
+    _say("bf16 via fp16 path, outlier inside rows")
+    fq = _fq()
+    M, K, N = 260, 384, 8192
+    W = workloads.weights_gaussian(K, N, 9200, outlier_prob=1e-3)
+    A = workloads.activations(M, K, "bf16", 9201).astype(np.float32)
+    A[:, 5] *= np.float32(2.0 ** 20)
+    A = workloads.round_to_bf16(A)
+    codes, scales, q_ref, s_ref = assert_quantizer_parity(W, 4, 128)
+    assert fq.gemm_workspace_bytes_for(M, N, K, 4, 128, fq.FQ_BF16) > fq.gemm_workspace_bytes_for(M, N, K, 4, 128, fq.FQ_F16)
+    C = from_dev_act(fq.gemm(to_dev_act(A, "bf16"), codes, scales, 4, 128), "bf16")
+    assert_gemm_close(C, oracle.gemm_ref(A, q_ref, s_ref), "bf16", "outlier column")
+    # without the outlier column the same rows: the small elements alone must still be accurate
+    A2 = A.copy()
+    A2[:, 5] = 0
+    C2 = from_dev_act(fq.gemm(to_dev_act(A2, "bf16"), codes, scales, 4, 128), "bf16")
+    assert_gemm_close(C2, oracle.gemm_ref(A2, q_ref, s_ref), "bf16", "rows without the outlier")
+
+
+def test_gemm_bf16_wide_matrix_split_k_and_tail():
+    """Wide matrices whose plans split K (uniformly, or for the tail round only) on the fp16 path."""
+    _say("bf16 via fp16 path with split K")
+    fq = _fq()
+    for M, K, N in ((384, 2048, 8192), (300, 1024, 12288)):
+        assert fq.gemm_workspace_bytes_for(M, N, K, 4, 128, fq.FQ_BF16) > fq.gemm_workspace_bytes_for(M, N, K, 4, 128, fq.FQ_F16)
+        _say("  " + fq.gemm_describe(M, N, K, 4, 128))
+        _gemm_case(M, K, N, "bf16", 4, 128, seed=9300 + M)

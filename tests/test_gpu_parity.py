@@ -86,6 +86,40 @@ def test_quantize_exhaustive_quotient_window():
     assert_quantizer_parity(W, 4, 0)
 
 
+@pytest.mark.parametrize("bits", [3, 4, 8])
+def test_quantize_quotients_next_to_ties(bits):
+    """Numerators chosen next to (k + 1/2) * s for every code k and 256 scales of every mantissa pattern:
+    the binary16 values just below and above each tie (two on each side), both signs.  Hundreds of the
+    quotients are exact ties (counted below; with binary16 numerators nothing else comes within 2^-13 of
+    one), the rest are the closest misses there are: where a product with the reciprocal and the IEEE
+    quotient could round differently."""
+    _say(f"quantize next to ties int{bits}")
+    qmax = (1 << (bits - 1)) - 1
+    L = float((1 << bits) - 1)
+    tops = np.arange(0x3000, 0x3400, 4, dtype=np.uint16).view(np.float16)         # 256 column maxima in [1/8, 1/4)
+    N = len(tops)
+    s_col = oracle.scale_from_absmax(tops, bits).astype(np.float64)
+    all16 = np.arange(0x0001, 0x3400, dtype=np.uint16).view(np.float16).astype(np.float64)   # ascending
+    per_col = 4 * qmax
+    K = 128 * (-(-(2 * per_col + 1) // 128))
+    W = np.zeros((K, N), dtype=np.float16)
+    near = 0
+    for n in range(N):
+        ties = (np.arange(qmax) + 0.5) * s_col[n]
+        at = np.searchsorted(all16, ties)                     # first value >= tie
+        idx = np.concatenate([at - 2, at - 1, at, at + 1])
+        vals = all16[np.clip(idx, 0, len(all16) - 1)]
+        vals = vals[vals <= float(tops[n])]
+        quo = (vals.astype(np.float32) / np.float32(s_col[n])).astype(np.float64)
+        near += int(np.sum(np.abs(np.abs(quo - np.rint(quo)) - 0.5) < 2.0 ** -13))
+        col = np.concatenate([[float(tops[n])], vals, -vals])
+        W[: len(col), n] = col.astype(np.float16)
+    _say(f"  {near} quotients within 2^-13 of a tie")
+    assert near >= 400
+    _, _, _, s_ref = assert_quantizer_parity(W, bits, 0)
+    assert np.array_equal(s_ref[0].astype(np.float64), s_col)
+
+
 # ------------------------------------------------------------------ product, oracle-sized cases
 def _gemm_case(M, K, N, dtype, bits, g, seed, heavy=False):
     fq = _fq()

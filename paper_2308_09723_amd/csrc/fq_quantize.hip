@@ -37,40 +37,73 @@ __device__ inline uint32_t scale_bits_from_absmax_bits(uint32_t m, float L, int 
 }
 
 // ---------------------------------------------------------------------------------
-// Scales: abs-max over each block of g rows, then the smallest binary16 s with
-// L * s >= 2 m.  Block = 64 x 4 threads: x covers 128 columns (two per thread), the four
-// y-slices split the block's rows and are combined through LDS.
+// Scales: abs-max over each block of g rows, then the smallest storable s with
+// L * s >= 2 m.  Block = 16 x 16 threads: thread (tx, ty) takes 8 consecutive columns (one
+// 16-byte load per row, so a row of the block is 256 contiguous bytes) of the rows ty, ty + 16,
+// ... of the group; the sixteen row slices are combined through LDS.
 // ---------------------------------------------------------------------------------
+typedef uint16_t u16x2_t __attribute__((ext_vector_type(2)));
+
+// abs-max bit patterns of 8 columns (four packed pairs) over rows ty, ty + 16, ... < rows
+__device__ inline uint4 absmax8_slice(const uint16_t* __restrict__ base, int64_t N, int rows, int ty) {
+    u16x2_t m[4] = {{0, 0}, {0, 0}, {0, 0}, {0, 0}};
+    auto fold = [&](const uint4& v) {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t a = w[i] & 0x7fff7fffu;
+            m[i] = __builtin_elementwise_max(m[i], __builtin_bit_cast(u16x2_t, a));
+        }
+    };
+    int r = ty;
+    for (; r + 48 < rows; r += 64) {      // four loads in flight
+        const uint4 v0 = *reinterpret_cast<const uint4*>(base + (int64_t)r * N);
+        const uint4 v1 = *reinterpret_cast<const uint4*>(base + (int64_t)(r + 16) * N);
+        const uint4 v2 = *reinterpret_cast<const uint4*>(base + (int64_t)(r + 32) * N);
+        const uint4 v3 = *reinterpret_cast<const uint4*>(base + (int64_t)(r + 48) * N);
+        fold(v0); fold(v1); fold(v2); fold(v3);
+    }
+    for (; r < rows; r += 16) fold(*reinterpret_cast<const uint4*>(base + (int64_t)r * N));
+    return make_uint4(__builtin_bit_cast(uint32_t, m[0]), __builtin_bit_cast(uint32_t, m[1]),
+                      __builtin_bit_cast(uint32_t, m[2]), __builtin_bit_cast(uint32_t, m[3]));
+}
+// the sixteen slices of a block combined: valid in the threads with ty == 0
+__device__ inline uint4 absmax8_block(uint4 mine, uint4 (&red)[16][16], int tx, int ty) {
+    red[ty][tx] = mine;
+    __syncthreads();
+    if (ty != 0) return mine;
+    u16x2_t m[4];
+    m[0] = __builtin_bit_cast(u16x2_t, mine.x); m[1] = __builtin_bit_cast(u16x2_t, mine.y);
+    m[2] = __builtin_bit_cast(u16x2_t, mine.z); m[3] = __builtin_bit_cast(u16x2_t, mine.w);
+    for (int y = 1; y < 16; ++y) {
+        const uint4 o = red[y][tx];
+        m[0] = __builtin_elementwise_max(m[0], __builtin_bit_cast(u16x2_t, o.x));
+        m[1] = __builtin_elementwise_max(m[1], __builtin_bit_cast(u16x2_t, o.y));
+        m[2] = __builtin_elementwise_max(m[2], __builtin_bit_cast(u16x2_t, o.z));
+        m[3] = __builtin_elementwise_max(m[3], __builtin_bit_cast(u16x2_t, o.w));
+    }
+    return make_uint4(__builtin_bit_cast(uint32_t, m[0]), __builtin_bit_cast(uint32_t, m[1]),
+                      __builtin_bit_cast(uint32_t, m[2]), __builtin_bit_cast(uint32_t, m[3]));
+}
+
 __global__ __launch_bounds__(256) void fq_scales_kernel(const uint16_t* __restrict__ W, int64_t K,
                                                         int64_t N, int g, float L, int sfmt,
                                                         uint16_t* __restrict__ scales) {
-    __shared__ uint32_t red[4][64];
+    __shared__ uint4 red[16][16];
     const int tx = threadIdx.x, ty = threadIdx.y;
-    const int64_t n = ((int64_t)blockIdx.x * 64 + tx) * 2;
+    const int64_t n = ((int64_t)blockIdx.x * 16 + tx) * 8;      // N is a multiple of 16
     const int64_t grp = blockIdx.y;
-    uint32_t m0 = 0, m1 = 0;
-    if (n < N) {
-        const uint16_t* base = W + (grp * g) * N + n;
-        for (int r = ty; r < g; r += 4) {
-            const uint32_t v = *reinterpret_cast<const uint32_t*>(base + (int64_t)r * N);
-            const uint32_t a0 = v & 0x7fffu, a1 = (v >> 16) & 0x7fffu;
-            m0 = a0 > m0 ? a0 : m0;
-            m1 = a1 > m1 ? a1 : m1;
-        }
-    }
-    red[ty][tx] = m0 | (m1 << 16);
-    __syncthreads();
+    uint4 m = make_uint4(0u, 0u, 0u, 0u);
+    if (n < N) m = absmax8_slice(W + (grp * g) * N + n, N, g, ty);
+    m = absmax8_block(m, red, tx, ty);
     if (ty == 0 && n < N) {
-        uint32_t out = 0;
-        for (int c = 0; c < 2; ++c) {
-            uint32_t m = 0;
-            for (int y = 0; y < 4; ++y) {
-                const uint32_t v = (red[y][tx] >> (16 * c)) & 0xffffu;
-                m = v > m ? v : m;
-            }
-            out |= scale_bits_from_absmax_bits(m, L, sfmt) << (16 * c);
-        }
-        *reinterpret_cast<uint32_t*>(scales + grp * N + n) = out;
+        const uint32_t w[4] = {m.x, m.y, m.z, m.w};
+        uint32_t out[4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            out[i] = scale_bits_from_absmax_bits(w[i] & 0xffffu, L, sfmt) |
+                     (scale_bits_from_absmax_bits(w[i] >> 16, L, sfmt) << 16);
+        *reinterpret_cast<uint4*>(scales + grp * N + n) = make_uint4(out[0], out[1], out[2], out[3]);
     }
 }
 
@@ -268,31 +301,15 @@ __global__ __launch_bounds__(256) void fq_unpack_kernel(const uint32_t* __restri
 // ---------------------------------------------------------------------------------
 __global__ __launch_bounds__(256) void fq_fine_absmax_kernel(const uint16_t* __restrict__ W, int64_t N,
                                                              int f, uint16_t* __restrict__ fine) {
-    __shared__ uint32_t red[4][64];
+    // thread layout as in fq_scales_kernel: 16 x 16, eight columns per thread
+    __shared__ uint4 red[16][16];
     const int tx = threadIdx.x, ty = threadIdx.y;
-    const int64_t n = ((int64_t)blockIdx.x * 64 + tx) * 2;
+    const int64_t n = ((int64_t)blockIdx.x * 16 + tx) * 8;
     const int64_t blk = blockIdx.y;
-    uint32_t m0 = 0, m1 = 0;
-    if (n < N) {
-        const uint16_t* base = W + (blk * f) * N + n;
-        for (int r = ty; r < f; r += 4) {
-            const uint32_t v = *reinterpret_cast<const uint32_t*>(base + (int64_t)r * N);
-            const uint32_t a0 = v & 0x7fffu, a1 = (v >> 16) & 0x7fffu;
-            m0 = a0 > m0 ? a0 : m0;
-            m1 = a1 > m1 ? a1 : m1;
-        }
-    }
-    red[ty][tx] = m0 | (m1 << 16);
-    __syncthreads();
-    if (ty == 0 && n < N) {
-        uint32_t a = 0, b = 0;
-        for (int y = 0; y < 4; ++y) {
-            const uint32_t v = red[y][tx];
-            a = (v & 0xffffu) > a ? (v & 0xffffu) : a;
-            b = (v >> 16) > b ? (v >> 16) : b;
-        }
-        *reinterpret_cast<uint32_t*>(fine + blk * N + n) = a | (b << 16);
-    }
+    uint4 m = make_uint4(0u, 0u, 0u, 0u);
+    if (n < N) m = absmax8_slice(W + (blk * f) * N + n, N, f, ty);
+    m = absmax8_block(m, red, tx, ty);
+    if (ty == 0 && n < N) *reinterpret_cast<uint4*>(fine + blk * N + n) = m;
 }
 
 // levels = number of halvings covered; a top group spans 2^levels fine blocks.
@@ -306,28 +323,26 @@ __global__ __launch_bounds__(256) void fq_halving_flags_kernel(const uint16_t* _
     if (n >= N || top >= tops) return;
     const int64_t span = (int64_t)1 << levels;
     const uint16_t* col = fine + (top * span) * N + n;
-    // Bottom-up fold with an explicit stack-free scheme: at level d (d = levels-1 is the
-    // finest transition) parents are pairs of nodes of size 2^(levels-1-d) fine blocks.
-    // Values are recomputed per level from the fine array; the total work per thread is
-    // span * levels reads, which is small (span <= a few hundred).
-    for (int d = 0; d < levels; ++d) {
-        const int64_t child = span >> (d + 1);     // fine blocks per child at this level
-        bool hit = false;
-        for (int64_t p = 0; p < span; p += 2 * child) {
-            uint32_t c0 = 0, c1 = 0;
-            for (int64_t i = 0; i < child; ++i) {
-                const uint32_t a = col[(p + i) * N];
-                const uint32_t b = col[(p + child + i) * N];
-                c0 = a > c0 ? a : c0;
-                c1 = b > c1 ? b : c1;
-            }
-            const float lo = half_bits_to_float((uint16_t)(c0 < c1 ? c0 : c1));
-            const float hi = half_bits_to_float((uint16_t)(c0 < c1 ? c1 : c0));
-            const float bound = __fmul_rn(thr, hi);
-            hit = hit || (lo < bound);
+    // Level d = blockIdx.z (d = levels - 1 is the finest transition): parents are pairs of nodes of
+    // 2^(levels-1-d) fine blocks, recomputed from the fine array, so a thread reads span values; one
+    // grid layer per level keeps enough threads in flight when there are few top groups.
+    const int d = blockIdx.z;
+    const int64_t child = span >> (d + 1);     // fine blocks per child at this level
+    bool hit = false;
+    for (int64_t p = 0; p < span; p += 2 * child) {
+        uint32_t c0 = 0, c1 = 0;
+        for (int64_t i = 0; i < child; ++i) {
+            const uint32_t a = col[(p + i) * N];
+            const uint32_t b = col[(p + child + i) * N];
+            c0 = a > c0 ? a : c0;
+            c1 = b > c1 ? b : c1;
         }
-        if (hit) atomicOr(&flags[d], 1);
+        const float lo = half_bits_to_float((uint16_t)(c0 < c1 ? c0 : c1));
+        const float hi = half_bits_to_float((uint16_t)(c0 < c1 ? c1 : c0));
+        const float bound = __fmul_rn(thr, hi);
+        hit = hit || (lo < bound);
     }
+    if (hit) atomicOr(&flags[d], 1);
 }
 
 __global__ void fq_zero_ints_kernel(int* p, int n) {
@@ -444,14 +459,14 @@ int fq_launch_quantize(const void* W, int64_t K, int64_t N, int bits, int g, int
         // two stages; the block maxima (K / 128 x N binary16 = K * N / 64 bytes) are parked in the
         // code buffer, which is only written by the encoding pass below
         uint16_t* fine = (uint16_t*)codes;
-        dim3 block(64, 4);
+        dim3 block(16, 16);
         dim3 grid((unsigned)((N + 127) / 128), (unsigned)(K / 128));
         hipLaunchKernelGGL(fq_fine_absmax_kernel, grid, block, 0, stream, (const uint16_t*)W, N, 128, fine);
         dim3 grid2((unsigned)((N + 255) / 256), (unsigned)(K / g));
         hipLaunchKernelGGL(fq_scales_fold_kernel, grid2, dim3(256), 0, stream, (const uint16_t*)fine, N, g / 128, L,
                            sfmt, (uint16_t*)scales);
     } else {
-        dim3 block(64, 4);
+        dim3 block(16, 16);
         dim3 grid((unsigned)((N + 127) / 128), (unsigned)(K / g));
         hipLaunchKernelGGL(fq_scales_kernel, grid, block, 0, stream, (const uint16_t*)W, K, N, g, L, sfmt,
                            (uint16_t*)scales);
@@ -484,14 +499,14 @@ int fq_launch_choose_group(const void* W, int64_t K, int64_t N, int g_top, int l
     const int f = g_top >> levels;
     hipLaunchKernelGGL(fq_zero_ints_kernel, dim3(1), dim3(64), 0, stream, flags, 64);
     {
-        dim3 block(64, 4);
+        dim3 block(16, 16);
         dim3 grid((unsigned)((N + 127) / 128), (unsigned)(K / f));
         hipLaunchKernelGGL(fq_fine_absmax_kernel, grid, block, 0, stream, (const uint16_t*)W, N, f, fine);
     }
     {
         const float thr = 1.0f - alpha;
         dim3 block(256);
-        dim3 grid((unsigned)((N + 255) / 256), (unsigned)(K / g_top));
+        dim3 grid((unsigned)((N + 255) / 256), (unsigned)(K / g_top), (unsigned)levels);   // levels >= 1
         hipLaunchKernelGGL(fq_halving_flags_kernel, grid, block, 0, stream, (const uint16_t*)fine, N,
                            K / g_top, levels, thr, flags);
     }

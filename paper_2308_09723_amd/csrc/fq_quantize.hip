@@ -189,19 +189,18 @@ __global__ __launch_bounds__(256) void fq_quantize_panel_kernel(const uint16_t* 
     }
     __syncthreads();
     if constexpr (OWN_SCALES) {
-        // abs-max of the 32-row sub-blocks: thread -> column tid % 128, sub-blocks tid / 128 and tid / 128 + 2
+        // abs-max of the 32-row sub-blocks: thread -> column pair tid % 64, sub-block tid / 64; one 4-byte
+        // LDS read per row and a packed 16-bit maximum
         {
-            const int c = tid & 127;
-    #pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const int sb = (tid >> 7) + 2 * h;
-                uint32_t m = 0;
-                for (int r = 0; r < 32; ++r) {
-                    const uint32_t a = panel[(sb * 32 + r) * FQ_QP_PITCH + c] & 0x7fffu;
-                    m = a > m ? a : m;
-                }
-                submax[sb][c] = (uint16_t)m;
+            const int cp = (tid & 63) * 2;
+            const int sb = tid >> 6;
+            u16x2_t m = {0, 0};
+#pragma unroll
+            for (int r = 0; r < 32; ++r) {
+                const uint32_t v = *reinterpret_cast<const uint32_t*>(&panel[(sb * 32 + r) * FQ_QP_PITCH + cp]);
+                m = __builtin_elementwise_max(m, __builtin_bit_cast(u16x2_t, v & 0x7fff7fffu));
             }
+            *reinterpret_cast<uint32_t*>(&submax[sb][cp]) = __builtin_bit_cast(uint32_t, m);
         }
         __syncthreads();
         // scales: one per (group, column); a group is g / 32 consecutive sub-blocks

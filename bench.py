@@ -86,11 +86,12 @@ def main():
                     help="also time the other BASELINE configurations (reported under 'extra'): prefill and mid-M "
                          "products (configs[2]), the grouped expert products (configs[3]) and the heavy-tailed "
                          "stress layer (configs[4])")
-    ap.add_argument("--profile", choices=["decode", "prefill", "copy", "moe", "midm"], default=None,
+    ap.add_argument("--profile", choices=["decode", "prefill", "copy", "moe", "midm", "quantize"], default=None,
                     help="short untimed run of one case for rocprofv3 (no JSON line): 'decode' = the benchmark "
                          "step, 'prefill' = QKV-shaped product at M = 2048 (bf16), 'copy' = a 1 GiB device copy "
                          "whose FETCH_SIZE / WRITE_SIZE calibrate the counters, 'moe' = the grouped expert products of "
-                         "configs[3], 'midm' = the QKV-shaped product at M = 32 and M = 128 (bf16)")
+                         "configs[3], 'midm' = the QKV-shaped product at M = 32 and M = 128 (bf16), 'quantize' = the offline "
+                         "steps (fq_quantize, fq_choose_group, fq_quant_error) on the FC1-shaped matrix")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build targets one GPU; --gpus must be 1 (no multi-GPU path exists)", file=sys.stderr)
@@ -117,6 +118,9 @@ def main():
         return
     if args.profile == "moe":
         moe_section(torch, fq, workloads)
+        return
+    if args.profile == "quantize":
+        quantize_section(torch, fq, workloads)
         return
     if args.profile == "midm":
         K, N = workloads.OPT175B_LAYERS["qkv"]

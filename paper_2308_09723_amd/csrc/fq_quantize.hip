@@ -118,7 +118,15 @@ __global__ __launch_bounds__(256) void fq_scales_fold_kernel(const uint16_t* __r
     if (n >= N) return;
     const int64_t grp = blockIdx.y;
     uint32_t m = 0;
-    for (int i = 0; i < per_group; ++i) {
+    int i = 0;
+    for (; i + 8 <= per_group; i += 8) {     // eight loads in flight
+        uint32_t v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = fine[(grp * per_group + i + u) * N + n];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) m = v[u] > m ? v[u] : m;
+    }
+    for (; i < per_group; ++i) {
         const uint32_t v = fine[(grp * per_group + i) * N + n];
         m = v > m ? v : m;
     }
@@ -345,20 +353,79 @@ __global__ __launch_bounds__(256) void fq_halving_flags_kernel(const uint16_t* _
     const int d = blockIdx.z;
     const int64_t child = span >> (d + 1);     // fine blocks per child at this level
     bool hit = false;
-    for (int64_t p = 0; p < span; p += 2 * child) {
-        uint32_t c0 = 0, c1 = 0;
-        for (int64_t i = 0; i < child; ++i) {
-            const uint32_t a = col[(p + i) * N];
-            const uint32_t b = col[(p + child + i) * N];
-            c0 = a > c0 ? a : c0;
-            c1 = b > c1 ? b : c1;
+    // one pass over the column's fine values (independent loads, several in flight): `node` collects the
+    // child under way, `prev` is its left sibling once that one is complete
+    uint32_t node = 0, prev = 0;
+#pragma unroll 8
+    for (int64_t q = 0; q < span; ++q) {
+        const uint32_t a = col[q * N];
+        node = a > node ? a : node;
+        if (((q + 1) & (child - 1)) == 0) {            // a child ends here
+            if (((q + 1) & (2 * child - 1)) == 0) {    // ... and it is the right one of its pair
+                const float lo = half_bits_to_float((uint16_t)(prev < node ? prev : node));
+                const float hi = half_bits_to_float((uint16_t)(prev < node ? node : prev));
+                hit = hit || (lo < __fmul_rn(thr, hi));
+            }
+            prev = node;
+            node = 0;
         }
-        const float lo = half_bits_to_float((uint16_t)(c0 < c1 ? c0 : c1));
-        const float hi = half_bits_to_float((uint16_t)(c0 < c1 ? c1 : c0));
-        const float bound = __fmul_rn(thr, hi);
-        hit = hit || (lo < bound);
     }
     if (hit) atomicOr(&flags[d], 1);
+}
+
+// The same test with the pairwise fold done in LDS (a top group of at most 1024 fine blocks): a block
+// takes `cols` neighbouring columns of one top group, loads their 2^levels fine values with coalesced
+// 4-byte loads, and folds them level by level from the finest transition up, alternating between two LDS
+// arrays; every fine value is read from memory once instead of once per level, and no thread walks a
+// whole column.  Dynamic LDS: 3 * 2^levels * cols bytes.
+__global__ __launch_bounds__(256) void fq_halving_tree_kernel(const uint16_t* __restrict__ fine, int64_t N,
+                                                              int levels, float thr, int cols,
+                                                              int* __restrict__ flags) {
+    extern __shared__ uint16_t tree[];     // [span][cols], then [span / 2][cols]
+    const int tid = threadIdx.x;
+    const int span = 1 << levels;
+    const int64_t n0 = (int64_t)blockIdx.x * cols;
+    const uint16_t* base = fine + ((int64_t)blockIdx.y * span) * N + n0;
+    {
+        const int pairs = cols / 2, c2 = (tid % pairs) * 2;
+        const bool ok = n0 + c2 < N;       // N is even
+        const int step = 256 / pairs;
+        for (int r0 = tid / pairs; r0 < span; r0 += 8 * step) {     // eight loads in flight
+            uint32_t v[8];
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int r = r0 + u * step;
+                v[u] = (ok && r < span) ? *reinterpret_cast<const uint32_t*>(base + (int64_t)r * N + c2) : 0u;
+            }
+#pragma unroll
+            for (int u = 0; u < 8; ++u) {
+                const int r = r0 + u * step;
+                if (r < span) *reinterpret_cast<uint32_t*>(&tree[r * cols + c2]) = v[u];
+            }
+        }
+    }
+    __syncthreads();
+    uint16_t* src = tree;
+    uint16_t* dst = tree + span * cols;
+    int len = span;                        // nodes per column at the level being folded
+    const int lc = 31 - __clz(cols);       // cols is 16, 32 or 64
+    for (int d = levels - 1; d >= 0; --d) {
+        const int parents = len / 2;
+        bool hit = false;
+        for (int i = tid; i < parents * cols; i += 256) {
+            const int p = i >> lc, c = i & (cols - 1);
+            const uint32_t a = src[(2 * p) * cols + c], b = src[(2 * p + 1) * cols + c];
+            const float lo = half_bits_to_float((uint16_t)(a < b ? a : b));
+            const float hi = half_bits_to_float((uint16_t)(a < b ? b : a));
+            hit = hit || (lo < __fmul_rn(thr, hi));
+            dst[p * cols + c] = (uint16_t)(a < b ? b : a);
+        }
+        if (__syncthreads_or(hit) && tid == 0) atomicOr(&flags[d], 1);
+        uint16_t* t = src;
+        src = dst;
+        dst = t;
+        len = parents;
+    }
 }
 
 __global__ void fq_zero_ints_kernel(int* p, int n) {
@@ -521,10 +588,18 @@ int fq_launch_choose_group(const void* W, int64_t K, int64_t N, int g_top, int l
     }
     {
         const float thr = 1.0f - alpha;
-        dim3 block(256);
-        dim3 grid((unsigned)((N + 255) / 256), (unsigned)(K / g_top), (unsigned)levels);   // levels >= 1
-        hipLaunchKernelGGL(fq_halving_flags_kernel, grid, block, 0, stream, (const uint16_t*)fine, N,
-                           K / g_top, levels, thr, flags);
+        if (levels <= 10) {
+            // fold in LDS: 64 / 32 / 16 columns per block for up to 256 / 512 / 1024 fine blocks (<= 48 KiB)
+            const int cols = levels <= 8 ? 64 : (levels == 9 ? 32 : 16);
+            dim3 grid((unsigned)((N + cols - 1) / cols), (unsigned)(K / g_top));
+            hipLaunchKernelGGL(fq_halving_tree_kernel, grid, dim3(256), (size_t)3 * ((size_t)1 << levels) * cols,
+                               stream, (const uint16_t*)fine, N, levels, thr, cols, flags);
+        } else {
+            dim3 block(256);
+            dim3 grid((unsigned)((N + 255) / 256), (unsigned)(K / g_top), (unsigned)levels);   // levels >= 1
+            hipLaunchKernelGGL(fq_halving_flags_kernel, grid, block, 0, stream, (const uint16_t*)fine, N,
+                               K / g_top, levels, thr, flags);
+        }
     }
     if (hipGetLastError() != hipSuccess) return FQ_ERR_HIP;
     if (hipMemcpyAsync(flags_host, flags, sizeof(int) * 64, hipMemcpyDeviceToHost, stream) != hipSuccess)

@@ -274,6 +274,35 @@ def test_choose_group_matches_oracle():
 
 
 # ------------------------------------------------------------------ round-trip error (section 3.2)
+@pytest.mark.parametrize("K,N", [(32 * 512, 80), (32 * 1024, 48), (32 * 2048, 32), (48 * 256, 272)])
+def test_choose_group_deep_halving_trees(K, N):
+    """Per-column start with 9, 10, 11 and 8 halving levels (the fold over the levels runs in LDS with 32, 16
+    or 64 columns per block, or per column in registers beyond 1024 fine blocks).  One column carries 8.0 in
+    its first K / 2^(d+1) rows and 1.0 elsewhere: the halving test then fires at levels 0 .. d and nowhere
+    else, so the answer is K / 2^(d+1); plus Gaussian weights at several thresholds."""
+    fq = _fq()
+    torch = torch_mod()
+    f = 48 if K % 48 == 0 and (K // 48) & (K // 48 - 1) == 0 else 32
+    levels = (K // f).bit_length() - 1
+    assert f << levels == K
+    for d in sorted({0, 1, levels // 2, levels - 2, levels - 1}):
+        W = np.full((K, N), 1.0, dtype=np.float16)
+        W[: K >> (d + 1), N - 3] = 8.0
+        want = oracle.choose_group(W, 0, f, 0.5)
+        assert want == K >> (d + 1)
+        _say(f"choose_group deep K={K} N={N} levels={levels} d={d} -> {want}")
+        assert fq.choose_group(torch.from_numpy(W).cuda(), 0, f, 0.5) == want
+        assert fq.choose_group(torch.from_numpy(W).cuda(), 0, f, 0.8) == want     # 1 < 0.2 * 8 still holds
+        assert fq.choose_group(torch.from_numpy(W).cuda(), 0, f, 0.9) == K        # 1 < 0.1 * 8 does not
+        assert oracle.choose_group(W, 0, f, 0.8) == want and oracle.choose_group(W, 0, f, 0.9) == K
+    Wg = workloads.weights_gaussian(K, N, 77, outlier_prob=1e-4)
+    Wd = torch.from_numpy(Wg).cuda()
+    for alpha in (0.2, 0.6, 0.9, 0.99):
+        want = oracle.choose_group(Wg, 0, f, alpha)
+        _say(f"choose_group deep gaussian K={K} alpha={alpha} -> {want}")
+        assert fq.choose_group(Wd, 0, f, alpha) == want
+
+
 @pytest.mark.parametrize("bits", [4, 8])
 @pytest.mark.parametrize("K,N,g", [(384, 80, 32), (512, 272, 64), (1024, 16, 0), (256, 1040, 256), (768, 304, 128)])
 def test_quant_error_matches_oracle(bits, K, N, g):

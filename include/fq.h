@@ -125,6 +125,9 @@ int fq_unpack(const void* codes, int64_t K, int64_t N, int bits, int8_t* q, void
  * fq_choose_group_workspace_bytes(K, N, g_start, g_min) bytes.
  * The returned size is not checked against fq_gemm's limits (it may be odd multiples
  * of small numbers when K has odd factors); callers pass g_start / g_min accordingly.
+ * Errors: FQ_ERR_INVALID_ARG (null pointers, alpha outside [0, 1], g_start not dividing K),
+ *         FQ_ERR_UNSUPPORTED (N not a multiple of 16, more than 24 halvings, more than 65535
+ *         groups per column), FQ_ERR_WORKSPACE, FQ_ERR_HIP.
  */
 size_t fq_choose_group_workspace_bytes(int64_t K, int64_t N, int g_start, int g_min);
 int fq_choose_group(const void* W_f16, int64_t K, int64_t N, int g_start, int g_min, float alpha,

@@ -108,7 +108,8 @@ int fq_choose_group(const void* W_f16, int64_t K, int64_t N, int g_start, int g_
     if (!(alpha >= 0.0f && alpha <= 1.0f)) return FQ_ERR_INVALID_ARG;
     const int64_t g_top = g_start == 0 ? K : g_start;
     if (g_top > K || K % g_top != 0) return FQ_ERR_INVALID_ARG;
-    if (N % 2 != 0 || K > (int64_t)1 << 24 || N > (int64_t)1 << 24) return FQ_ERR_UNSUPPORTED;
+    // (the abs-max kernel reads eight columns per lane)
+    if (N % FQ_NTILE != 0 || K > (int64_t)1 << 24 || N > (int64_t)1 << 24) return FQ_ERR_UNSUPPORTED;
     const int levels = halving_levels(g_top, g_min);
     if (levels == 0) {
         *g_out = (int)g_top;

@@ -104,6 +104,8 @@ def test_grouped_and_heuristic_argument_checks():
     assert st == fq.FQ_ERR_INVALID_ARG
     st, _ = fq.choose_group_raw(16, 1024, 1024, 0, 32, 0.5, None, 0)
     assert st == fq.FQ_ERR_WORKSPACE
+    st, _ = fq.choose_group_raw(16, 1024, 1032, 0, 32, 0.5, 16, 1 << 30)
+    assert st == fq.FQ_ERR_UNSUPPORTED                    # N must be a multiple of 16
     st, g = fq.choose_group_raw(16, 1024, 1024, 64, 64, 0.5, None, 0)
     assert st == fq.FQ_OK and g == 64                     # nothing to halve: answered on the host
     assert fq.status_string(fq.FQ_ERR_WORKSPACE) == "FQ_ERR_WORKSPACE"

@@ -31,7 +31,8 @@ template <int ACT, int BITS, int NT, int DEPTH, int MAXW, int AU>
 int launch_skinny(const void* A, int64_t M, int64_t N, int64_t K, const void* codes, const void* scales, int g,
                   void* C, float* partial, const fq_gemm_plan& plan, hipStream_t stream) {
     const int kblk = fq_kblk(BITS);
-    const bool per_step = (g % kblk) != 0;
+    // scale rows per k-block: 1, KBLK / g, or one per 32-row step when g does not divide KBLK
+    const int sr = (g % kblk) == 0 ? 1 : ((kblk % g) == 0 ? kblk / g : kblk / 32);
     const int ntiles = (int)(N / FQ_NTILE);
     const int ngroups = (ntiles + NT - 1) / NT;
     const int bgroups = (ngroups + plan.gp - 1) / plan.gp;
@@ -41,13 +42,15 @@ int launch_skinny(const void* A, int64_t M, int64_t N, int64_t K, const void* co
     const size_t lds = lds_act > lds_red ? lds_act : lds_red;
     const uint32_t g32 = (uint32_t)(g / 32);
     const uint32_t g32_recip = (uint32_t)((((uint64_t)1 << 32) + g32 - 1) / g32);   // unused when g32 == 1
-    auto kern = per_step ? fq_gemm_skinny_kernel<ACT, BITS, NT, DEPTH, true, MAXW, AU>
-                         : fq_gemm_skinny_kernel<ACT, BITS, NT, DEPTH, false, MAXW, AU>;
+    constexpr int STEPS = fq_kblk(BITS) / FQ_KSTEP;
+    auto kern = sr == 1 ? fq_gemm_skinny_kernel<ACT, BITS, NT, DEPTH, 1, MAXW, AU>
+                        : (sr == 2 ? fq_gemm_skinny_kernel<ACT, BITS, NT, DEPTH, 2, MAXW, AU>
+                                   : fq_gemm_skinny_kernel<ACT, BITS, NT, DEPTH, STEPS, MAXW, AU>);
     if (lds > 65536) {
         // more than the default dynamic LDS limit: raise it for this kernel (up to the 160 KiB of a CU)
         if (lds > 160 * 1024) return FQ_ERR_UNSUPPORTED;
-        static std::atomic<uint64_t> raised[2];   // per instantiation: [per_step]
-        if (raise_lds_limit((const void*)kern, raised[per_step ? 1 : 0]) != FQ_OK) return FQ_ERR_HIP;
+        static std::atomic<uint64_t> raised[3];   // per instantiation: [scale rows per k-block]
+        if (raise_lds_limit((const void*)kern, raised[sr == 1 ? 0 : (sr == 2 ? 1 : 2)]) != FQ_OK) return FQ_ERR_HIP;
     }
     hipLaunchKernelGGL(kern, dim3((unsigned)(bgroups * plan.splits)), dim3((unsigned)(plan.gp * plan.kw * 64)),
                        lds, stream, (const uint16_t*)A, (const u32x4*)codes, (const uint16_t*)scales,

@@ -291,15 +291,16 @@ __device__ inline void flush(f32x4& acc, const f32x4& p, const f32x4& s, float r
 //    counter waits only for the stage about to be consumed.
 //  - The KW partial results of a column group are added through LDS (fixed order); if the grid
 //    also splits K (grid_splits > 1) block sums go to a binary32 partial buffer.
-// PER_STEP = the scale changes inside a k-block (group size not a multiple of KBLK).
+// SR = scale rows per k-block: 1 when the group size is a multiple of KBLK, else KBLK / g, or one per
+// 32-row k-step when g does not divide KBLK.
 // ==========================================================================================
 // AU = activation units (16 B) a lane fetches per super-block: M * KC <= AU * 64 * GP.
-template <int BITS, int NT, bool PER_STEP, int AU_>
+template <int BITS, int NT, int SR, int AU_>
 struct SkinnyStage {
     static constexpr int STEPS = fq_kblk(BITS) / FQ_KSTEP;
     static constexpr int AU = AU_;
     u32x4 wq[NT];
-    // four scales (output columns 4j .. 4j+3) of one scale row.  PER_STEP: the lane holds the row of
+    // four scales (output columns 4j .. 4j+3) of one scale row.  SR > 1: the lane holds the row of
     // k-step (lane % STEPS), so each quad of lanes holds all the rows of the k-block and a
     // quad broadcast hands every lane the row of the step at hand: one load per tile and k-block
     // instead of one per step.
@@ -331,21 +332,27 @@ __device__ inline u32x2 quad_bcast(const u32x2& v) {
     return r;
 }
 
-// acc[nt] += (this wave's k-block of the stage) x (activation fragments af[0..STEPS))
-template <int ACT, int BITS, int NT, bool PER_STEP, int AU>
-__device__ inline void skinny_block(const SkinnyStage<BITS, NT, PER_STEP, AU>& sl,
-                                    const u32x4 (&af)[SkinnyStage<BITS, NT, PER_STEP, AU>::STEPS], uint32_t magic,
+// acc[nt] += (this wave's k-block of the stage) x (activation fragments af[0..STEPS)).
+// The k-steps of one scale row (STEPS / SR of them) accumulate in p, which is then folded into acc with
+// that row's scales.
+template <int ACT, int BITS, int NT, int SR, int AU>
+__device__ inline void skinny_block(const SkinnyStage<BITS, NT, SR, AU>& sl,
+                                    const u32x4 (&af)[SkinnyStage<BITS, NT, SR, AU>::STEPS], uint32_t magic,
                                     f32x4 (&acc)[NT]) {
-    constexpr int STEPS = SkinnyStage<BITS, NT, PER_STEP, AU>::STEPS;
+    constexpr int STEPS = SkinnyStage<BITS, NT, SR, AU>::STEPS;
+    constexpr int GSTEPS = STEPS / SR;
+    static_assert(SR >= 1 && STEPS % SR == 0, "");
     constexpr float OFF = Dequant<ACT, BITS>::OFFSET;
     const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-    if constexpr (!PER_STEP) {
+#pragma unroll
+    for (int r = 0; r < SR; ++r) {
         f32x4 p[NT];
         f32x4 psa = zero;
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) p[nt] = zero;
 #pragma unroll
-        for (int t = 0; t < STEPS; ++t) {
+        for (int u = 0; u < GSTEPS; ++u) {
+            const int t = r * GSTEPS + u;
             const u32x4 a = af[t];
             if constexpr (OFF != 0.0f) psa = mfma16x16x32<ACT>(ones_operand<ACT>(), a, psa);
 #pragma unroll
@@ -359,28 +366,17 @@ __device__ inline void skinny_block(const SkinnyStage<BITS, NT, PER_STEP, AU>& s
             }
         }
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) flush<ACT, BITS>(acc[nt], p[nt], scales4<ACT>(sl.sc[nt]), psa[0]);
-    } else {
-#pragma unroll
-        for (int t = 0; t < STEPS; ++t) {
-            const u32x4 a = af[t];
-            f32x4 psa = zero;
-            if constexpr (OFF != 0.0f) psa = mfma16x16x32<ACT>(ones_operand<ACT>(), a, psa);
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
-                u32x4 w;
-                if (t == 0) w = Dequant<ACT, BITS>::template run<0>(sl.wq[nt], magic);
-                if (t == 1) w = Dequant<ACT, BITS>::template run<1>(sl.wq[nt], magic);
-                if (STEPS > 2 && t == 2) w = Dequant<ACT, BITS>::template run<2 % STEPS>(sl.wq[nt], magic);
-                if (STEPS > 2 && t == 3) w = Dequant<ACT, BITS>::template run<3 % STEPS>(sl.wq[nt], magic);
-                const f32x4 p = mfma16x16x32<ACT>(w, a, zero);
-                u32x2 sq;
-                if (t == 0) sq = quad_bcast<0>(sl.sc[nt]);
-                if (t == 1) sq = quad_bcast<1>(sl.sc[nt]);
-                if (STEPS > 2 && t == 2) sq = quad_bcast<2 % STEPS>(sl.sc[nt]);
-                if (STEPS > 2 && t == 3) sq = quad_bcast<3 % STEPS>(sl.sc[nt]);
-                flush<ACT, BITS>(acc[nt], p, scales4<ACT>(sq), psa[0]);
+        for (int nt = 0; nt < NT; ++nt) {
+            u32x2 sq = sl.sc[nt];
+            if constexpr (SR > 1) {
+                // the lane of the quad that fetched the row of this scale row's first k-step
+                const int t0 = r * GSTEPS;
+                if (t0 == 0) sq = quad_bcast<0>(sl.sc[nt]);
+                if (t0 == 1) sq = quad_bcast<1>(sl.sc[nt]);
+                if (STEPS > 2 && t0 == 2) sq = quad_bcast<2 % STEPS>(sl.sc[nt]);
+                if (STEPS > 2 && t0 == 3) sq = quad_bcast<3 % STEPS>(sl.sc[nt]);
             }
+            flush<ACT, BITS>(acc[nt], p[nt], scales4<ACT>(sq), psa[0]);
         }
     }
 }
@@ -390,7 +386,7 @@ __device__ inline void skinny_block(const SkinnyStage<BITS, NT, PER_STEP, AU>& s
 // lanes = consecutive unit columns of one row) spread over the banks.
 #define FQ_SK_PITCH 17
 
-template <int ACT, int BITS, int NT, int DEPTH, bool PER_STEP, int MAXW, int AU>
+template <int ACT, int BITS, int NT, int DEPTH, int SR, int MAXW, int AU>
 __global__ __launch_bounds__(MAXW * 64) void fq_gemm_skinny_kernel(
     const uint16_t* __restrict__ A, const u32x4* __restrict__ codes, const uint16_t* __restrict__ scales,
     uint16_t* __restrict__ C, float* __restrict__ partial, int M, int N, int K, uint32_t g32,
@@ -398,7 +394,7 @@ __global__ __launch_bounds__(MAXW * 64) void fq_gemm_skinny_kernel(
     constexpr int KBLK = fq_kblk(BITS);
     constexpr int STEPS = KBLK / FQ_KSTEP;
     constexpr int KC = KBLK / 8;                    // 16-byte activation units per row and k-block
-    typedef SkinnyStage<BITS, NT, PER_STEP, AU> Stage;
+    typedef SkinnyStage<BITS, NT, SR, AU> Stage;
     extern __shared__ u32x4 lds[];   // two activation buffers [kw_n * KC][FQ_SK_PITCH]; later the reduction
 
     const int tid = threadIdx.x;
@@ -477,9 +473,9 @@ __global__ __launch_bounds__(MAXW * 64) void fq_gemm_skinny_kernel(
         for (int nt = 0; nt < NT; ++nt) sl.wq[nt] = load_rec<BITS, true>(wbase[nt] + ((int64_t)kb * kb_stride + lane) * RB);
         {
             // scale row of a 32-row k-step: an exact division by g / 32 done as a multiplication by
-            // its rounded-up reciprocal (valid while the step index < 2^32 / (g/32)).  PER_STEP: the
+            // its rounded-up reciprocal (valid while the step index < 2^32 / (g/32)).  SR > 1: the
             // lane fetches the row of step (lane % STEPS) of the k-block.
-            const uint32_t step = (uint32_t)kb * STEPS + (PER_STEP ? (uint32_t)(lane & (STEPS - 1)) : 0u);
+            const uint32_t step = (uint32_t)kb * STEPS + (SR > 1 ? (uint32_t)(lane & (STEPS - 1)) : 0u);
             const uint32_t row = g32 == 1 ? step : __umulhi(step, g32_recip);
             const int64_t srow = (int64_t)row * N;
 #pragma unroll
@@ -496,7 +492,7 @@ __global__ __launch_bounds__(MAXW * 64) void fq_gemm_skinny_kernel(
         const u32x4* abuf = lds + (it & 1) * abuf_units + (kw * KC + j) * FQ_SK_PITCH + m;
 #pragma unroll
         for (int t = 0; t < STEPS; ++t) af[t] = abuf[t * 4 * FQ_SK_PITCH];
-        if (gvalid && kb < KB) skinny_block<ACT, BITS, NT, PER_STEP, AU>(sl, af, magic, acc);
+        if (gvalid && kb < KB) skinny_block<ACT, BITS, NT, SR, AU>(sl, af, magic, acc);
     };
 
     if (n_it > 0) {

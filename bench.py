@@ -243,9 +243,9 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            # FETCH_SIZE summed over the 8 launches of a step, rocprofv3 --pmc, 2 KiB per count as calibrated
+            # FETCH_SIZE summed over the 9 launches of a step, rocprofv3 --pmc, 2 KiB per count as calibrated
             # with a 1 GiB copy (profiles/fq_gemm_skinny_kernel_opt175b_decode.md); bytes per step
-            "traffic": 1.905e9,
+            "traffic": 1.903e9,
             "kernel": "fq_gemm_skinny_kernel (8 products per step, plus fq_reduce_kernel for the one that splits K "
                       "over the grid; algorithmic bytes of the step / mean HIP-event duration of its back-to-back "
                       "launches)",

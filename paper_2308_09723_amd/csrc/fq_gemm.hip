@@ -121,7 +121,6 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
         const int sr4 = g % 128 == 0 ? 1 : (128 % g == 0 ? 128 / g : 4);
         const double* cs = consts[bits == 8 ? 3 : (sr4 == 1 ? 0 : (sr4 == 2 ? 1 : 2))];
         const int split_opts[6] = {1, 2, 3, 4, 6, 8};
-        const double kscale = (double)kblk / 128.0;
         double best = 1e30;
         p.tail_tiles = 0;
         p.tail_splits = 1;
@@ -137,6 +136,11 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
             const double u4 = mt == 8 ? cs[5] : (mt == 4 ? cs[3] : cs[1]);
             for (int waves = 8; waves >= 4; waves -= 4) {
                 const int64_t nbn = (ntiles + waves * MMA_NT - 1) / (waves * MMA_NT);
+                // k-blocks of this shape: 8-bit codes in the 128-row, 8-wave shape go two layout blocks at
+                // a time (measured ~7 % less per row of K)
+                const int kblk_c = fq_mma_kblk(bits, mt, waves, K, g);
+                const int KB = (int)(K / kblk_c);
+                const double kscale = (double)kblk_c / 128.0 * (kblk_c != kblk ? 0.93 : 1.0);
                 const double u = (waves == 8 ? u8 : u4) * kscale;
                 for (int si = 0; si < 6; ++si) {
                     int splits = split_opts[si];

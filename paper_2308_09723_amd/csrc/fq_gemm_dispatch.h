@@ -72,9 +72,6 @@ int launch_skinny_au(const void* A, int64_t M, int64_t N, int64_t K, const void*
 template <int ACT, int BITS>
 int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* codes, const void* scales,
                  int g, void* C, void* workspace, const fq_gemm_plan& plan, hipStream_t stream) {
-    const int kblk = fq_kblk(BITS);
-    // scale rows per k-block: 1, KBLK / g, or one per 32-row step when g does not divide KBLK
-    const int sr = (g % kblk) == 0 ? 1 : ((kblk % g) == 0 ? kblk / g : kblk / 32);
     const int ntiles = (int)(N / FQ_NTILE);
     float* partial = (float*)workspace;
     if (plan.kind == 0) {
@@ -87,6 +84,11 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
         }
         if (st != FQ_OK) return st;
     } else {
+        // rows of K per k-block of this block shape (two layout blocks at a time for 8-bit codes in the
+        // 128-row, 8-wave shape), and the scale rows such a k-block spans: 1, kblk / g, or one per 32-row step
+        const int kblk = fq_mma_kblk(BITS, plan.mt, plan.waves, K, g);
+        const bool wide = kblk != fq_kblk(BITS);
+        const int sr = (g % kblk) == 0 ? 1 : ((kblk % g) == 0 ? kblk / g : kblk / 32);
         const int bm = plan.mt * 16;
         const int nblocks_n = (ntiles + plan.waves * MMA_NT - 1) / (plan.waves * MMA_NT);
         const int nblocks_m = (int)((M + bm - 1) / bm);
@@ -99,10 +101,10 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
                                                  : tiles * plan.splits));
         fq_group_items none;
         none.count = 0;
-#define FQ_MMA_LAUNCH_SR(ACT_, A_, RS_, MT_, W_, PIPE_, SR_)                                              \
+#define FQ_MMA_LAUNCH_SR(ACT_, A_, RS_, MT_, W_, PIPE_, SR_, KREC_)                                       \
     do {                                                                                                \
         auto kern = fq_gemm_mma_kernel<ACT_, BITS, MT_, MMA_NT, W_, SR_, false, PIPE_,                 \
-                                       use_post(ACT_, BITS, MT_, SR_, PIPE_)>;                          \
+                                       use_post(ACT_, BITS, MT_, SR_, PIPE_), KREC_>;                   \
         if (lds > 65536) {                                                                              \
             static std::atomic<uint64_t> raised;                                                        \
             if (raise_lds_limit((const void*)kern, raised) != FQ_OK) return FQ_ERR_HIP;                 \
@@ -115,9 +117,22 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
     } while (0)
 #define FQ_MMA_LAUNCH_ACT(ACT_, A_, RS_, MT_, W_, PIPE_)                                                \
     do {                                                                                                \
-        if (sr == 1) FQ_MMA_LAUNCH_SR(ACT_, A_, RS_, MT_, W_, PIPE_, 1);                                \
-        else if (sr == 2) FQ_MMA_LAUNCH_SR(ACT_, A_, RS_, MT_, W_, PIPE_, 2);                           \
-        else if constexpr (BITS != 8) FQ_MMA_LAUNCH_SR(ACT_, A_, RS_, MT_, W_, PIPE_, 4);               \
+        if (sr == 1) FQ_MMA_LAUNCH_SR(ACT_, A_, RS_, MT_, W_, PIPE_, 1, 1);                             \
+        else if (sr == 2) FQ_MMA_LAUNCH_SR(ACT_, A_, RS_, MT_, W_, PIPE_, 2, 1);                        \
+        else if constexpr (BITS != 8) FQ_MMA_LAUNCH_SR(ACT_, A_, RS_, MT_, W_, PIPE_, 4, 1);            \
+    } while (0)
+// the 128-row, 8-wave shape: 8-bit codes take two layout k-blocks per k-block where K allows it
+#define FQ_MMA_LAUNCH_BIG(ACT_, A_, RS_)                                                                \
+    do {                                                                                                \
+        if constexpr (BITS == 8) {                                                                      \
+            if (wide) { /* (one scale row per k-block by construction) */                              \
+                FQ_MMA_LAUNCH_SR(ACT_, A_, RS_, 8, 8, 2, 1, 2);                                         \
+            } else {                                                                                    \
+                FQ_MMA_LAUNCH_ACT(ACT_, A_, RS_, 8, 8, 2);                                              \
+            }                                                                                           \
+        } else {                                                                                        \
+            FQ_MMA_LAUNCH_ACT(ACT_, A_, RS_, 8, 8, 2);                                                  \
+        }                                                                                               \
     } while (0)
 #define FQ_MMA_LAUNCH(MT_, W_, PIPE_) FQ_MMA_LAUNCH_ACT(ACT, A, nullptr, MT_, W_, PIPE_)
         bool launched = false;
@@ -130,7 +145,7 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
                 float* rs = (float*)(extra + fq_a16_bytes(M, K));
                 hipLaunchKernelGGL(fq_rows_to_f16_kernel<256>, dim3((unsigned)M), dim3(256), 0, stream,
                                    (const uint16_t*)A, (int)K, A16, rs);
-                if (plan.waves == 8) FQ_MMA_LAUNCH_ACT(FQ_BF16_VIA_F16, A16, rs, 8, 8, 2);
+                if (plan.waves == 8) FQ_MMA_LAUNCH_BIG(FQ_BF16_VIA_F16, A16, rs);
                 else FQ_MMA_LAUNCH_ACT(FQ_BF16_VIA_F16, A16, rs, 8, 4, 0);
                 launched = true;
             }
@@ -139,13 +154,14 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
         } else if (plan.waves == 8) {
             if (plan.mt == 2) FQ_MMA_LAUNCH(2, 8, FQ_RING_MT2);
             else if (plan.mt == 4) FQ_MMA_LAUNCH(4, 8, FQ_RING_MT4);
-            else FQ_MMA_LAUNCH(8, 8, 2);
+            else FQ_MMA_LAUNCH_BIG(ACT, A, nullptr);
         } else {
             if (plan.mt == 2) FQ_MMA_LAUNCH(2, 4, FQ_RING_MT2);
             else if (plan.mt == 4) FQ_MMA_LAUNCH(4, 4, FQ_RING_MT4);
             else FQ_MMA_LAUNCH(8, 4, 0);
         }
 #undef FQ_MMA_LAUNCH
+#undef FQ_MMA_LAUNCH_BIG
 #undef FQ_MMA_LAUNCH_ACT
 #undef FQ_MMA_LAUNCH_SR
     }

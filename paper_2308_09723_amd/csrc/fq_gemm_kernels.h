@@ -796,17 +796,23 @@ __device__ inline void wait_vmcnt() {
     __builtin_amdgcn_s_waitcnt(0x0F70 | (N & 15) | ((N >> 4) << 14));
 }
 
-template <int ACT, int BITS, int MT, int NT, int WAVES, int SR, bool GROUPED, int PIPE, bool POST = false>
+// KREC = k-blocks of the packed layout that make one k-block of this kernel (lane records per column tile
+// and k-block): 2 for 8-bit codes in the 128-row shape, whose 64-row layout blocks would otherwise pay the
+// barrier, the waits and the address arithmetic of a k-block for half as many MFMAs.
+template <int ACT, int BITS, int MT, int NT, int WAVES, int SR, bool GROUPED, int PIPE, bool POST = false,
+          int KREC = 1>
 __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT == FQ_F16) ? 3 : 1) void fq_gemm_mma_kernel(
     const uint16_t* __restrict__ A, const u32x4* __restrict__ codes, const uint16_t* __restrict__ scales,
     uint16_t* __restrict__ C, float* __restrict__ partial, int M, int N, int K, int g, int kb_per_split,
     int splits, int nblocks_n, int nblocks_m, int64_t codes_stride16, int64_t scales_stride,
     fq_group_items items, int tail_tiles, int tail_splits, int tail_kbs, const float* __restrict__ rowscale) {
-    constexpr int KBLK = fq_kblk(BITS);
+    constexpr int KBLK = fq_kblk(BITS) * KREC;
     constexpr int STEPS = KBLK / FQ_KSTEP;
+    constexpr int SPR = STEPS / KREC;            // k-steps per lane record
     constexpr int KC = KBLK / 8;
     constexpr int BM = MT * 16;
     constexpr int UNITS = BM * KC;
+    static_assert(KREC == 1 || (PIPE > 0 && !POST), "several records per k-block: pipelined, pre-scaled form only");
     // LDS layout of the activation tile in the two-buffer form (the pipelined form has its own, below),
     // in 16-byte units: unit(kc, row) = kc * BM + (row ^ swz(kc)),
     // swz(kc) = kc * (16 / KC) mod 16.  A fragment read (16 rows of one kc per 16 lanes) then covers
@@ -919,7 +925,8 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
 
     const uint32_t magic = Dequant<ACT, BITS>::init();
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
-    u32x4 wq[NT], wq_n[NT], areg[UPT];
+    constexpr int NQ = KREC * NT;                // lane records of a k-block: [record][column tile]
+    u32x4 wq[NQ], wq_n[NQ], areg[UPT];
     // Scale registers: one per (scale row, column tile), or, with four scale rows per k-block,
     // two rows per register (low / high half, filled by 16-bit loads into register halves).
     // POST (few rows per block, where the conversion and not the matrix pipe sets the pace): the codes
@@ -939,14 +946,20 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
     // (used by the 128-row shapes; in the lower ones it costs registers they do not have)
     constexpr bool SADDR = MT == 8;
     const uint32_t lane_rec = (uint32_t)lane * RB;
-    auto load_q = [&](u32x4 (&q)[NT], int kb) {
-        if constexpr (SADDR) {
-            const int64_t kb_bytes = (int64_t)kb * kb_stride * RB;
+    auto load_q = [&](u32x4 (&q)[NQ], int kb) {
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) q[nt] = load_rec<BITS, false>(scalar_ptr(wbase[nt] + kb_bytes) + lane_rec);
-        } else {
+        for (int r = 0; r < KREC; ++r) {
+            const int64_t lkb = (int64_t)kb * KREC + r;      // k-block of the packed layout
+            if constexpr (SADDR) {
+                const int64_t kb_bytes = lkb * kb_stride * RB;
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) q[nt] = load_rec<BITS, false>(wbase[nt] + ((int64_t)kb * kb_stride + lane) * RB);
+                for (int nt = 0; nt < NT; ++nt)
+                    q[r * NT + nt] = load_rec<BITS, false>(scalar_ptr(wbase[nt] + kb_bytes) + lane_rec);
+            } else {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    q[r * NT + nt] = load_rec<BITS, false>(wbase[nt] + (lkb * kb_stride + lane) * RB);
+            }
         }
     };
     auto load_s = [&](SC (&s)[SREG][NT], int kb) {
@@ -974,7 +987,7 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
             }
         }
     };
-    auto load_w = [&](u32x4 (&q)[NT], SC (&s)[SREG][NT], int kb) {
+    auto load_w = [&](u32x4 (&q)[NQ], SC (&s)[SREG][NT], int kb) {
         load_q(q, kb);
         load_s(s, kb);
     };
@@ -992,12 +1005,14 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
             if (a_dst[r] >= 0) dst[a_dst[r]] = a_ok[r] ? areg[r] : zero4;
     };
     uint32_t s2c[NT];   // widened scale of the scale row under way, per column tile
-    auto convert = [&](const u32x4 (&q)[NT], const SC (&s)[SREG][NT], int t, int nt) -> u32x4 {
+    auto convert = [&](const u32x4 (&q)[NQ], const SC (&s)[SREG][NT], int t, int nt) -> u32x4 {
+        const u32x4& rec = q[(t / SPR) * NT + nt];   // the record that holds k-step t
+        const int ts = t % SPR;                      // ... as its step ts
         if constexpr (POST) {
-            if (t == 0) return Dequant<ACT, BITS>::template run<0>(q[nt], magic);
-            if (t == 1) return Dequant<ACT, BITS>::template run<1>(q[nt], magic);
-            if (STEPS > 2 && t == 2) return Dequant<ACT, BITS>::template run<2 % STEPS>(q[nt], magic);
-            return Dequant<ACT, BITS>::template run<3 % STEPS>(q[nt], magic);
+            if (ts == 0) return Dequant<ACT, BITS>::template run<0>(rec, magic);
+            if (ts == 1) return Dequant<ACT, BITS>::template run<1>(rec, magic);
+            if (SPR > 2 && ts == 2) return Dequant<ACT, BITS>::template run<2 % SPR>(rec, magic);
+            return Dequant<ACT, BITS>::template run<3 % SPR>(rec, magic);
         } else {
             // The scale is widened once per scale row and column tile (the k-steps of a row come one
             // after the other, the first of them first) and kept in s2c.  Its stored form stays opaque
@@ -1011,10 +1026,10 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
                 s2c[nt] = scale_operand<ACT>((uint16_t)h);
             }
             const uint32_t s2 = s2c[nt];
-            if (t == 0) return DequantScaled<ACT, BITS>::template run<0>(q[nt], magic, s2);
-            if (t == 1) return DequantScaled<ACT, BITS>::template run<1>(q[nt], magic, s2);
-            if (STEPS > 2 && t == 2) return DequantScaled<ACT, BITS>::template run<2 % STEPS>(q[nt], magic, s2);
-            return DequantScaled<ACT, BITS>::template run<3 % STEPS>(q[nt], magic, s2);
+            if (ts == 0) return DequantScaled<ACT, BITS>::template run<0>(rec, magic, s2);
+            if (ts == 1) return DequantScaled<ACT, BITS>::template run<1>(rec, magic, s2);
+            if (SPR > 2 && ts == 2) return DequantScaled<ACT, BITS>::template run<2 % SPR>(rec, magic, s2);
+            return DequantScaled<ACT, BITS>::template run<3 % SPR>(rec, magic, s2);
         }
     };
 
@@ -1058,7 +1073,7 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
         constexpr int BAR_SLOT = NFR - APD - 1;
         constexpr int W_SLOT = (STEPS - 2) * MT + (NT < MT ? NT : MT);   // after the last conversion from the set
         constexpr bool W_FIRST = W_SLOT <= BAR_SLOT;    // order of the two issue points inside a k-block
-        constexpr int NWLOADS = NT + SREG * SPK * NT;   // vector loads of one load_w
+        constexpr int NWLOADS = NQ + SREG * SPK * NT;   // vector loads of one load_w
         // loads issued after those of tile kb + 1 and before the barrier of k-block kb
         constexpr int NYOUNGER = (D - 1) * NWLOADS + (D - 2) * DPT;
         static_assert(NYOUNGER < 64 && (D - 1) * (NWLOADS + DPT) < 64, "wait counter range");
@@ -1094,7 +1109,7 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
 #pragma unroll
         for (int t = 0; t < STEPS; ++t) a_rd[t] = ml * KC + ((4 * t + j) ^ swz(ml));
 
-        u32x4 wqs[D][NT];
+        u32x4 wqs[D][NQ];
         SC scs[D][SREG][NT];
         // POST: partial sums of the scale group at hand and the activations' row sums over it
         f32x4 pg[POST ? MT : 1][POST ? NT : 1], rsum[POST ? MT : 1];
@@ -1128,7 +1143,7 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
                     flush<ACT, BITS>(acc[mt][nt], pg[mt][nt], scales4<ACT>(sa[srow][nt]), rsum[mt][0]);
             }
         };
-        auto kblock = [&](int kb, u32x4 (&qa)[NT], SC (&sa)[SREG][NT], u32x4 (&qb)[NT],
+        auto kblock = [&](int kb, u32x4 (&qa)[NQ], SC (&sa)[SREG][NT], u32x4 (&qb)[NQ],
                           SC (&sb)[SREG][NT]) {
             const int nxt = cur == D ? 0 : cur + 1;
             const int last = cur == 0 ? D : cur - 1;     // the tile read during kb - 1
@@ -1247,7 +1262,7 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
                 }
             }
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) wq[nt] = wq_n[nt];
+            for (int nt = 0; nt < NQ; ++nt) wq[nt] = wq_n[nt];
 #pragma unroll
             for (int r = 0; r < SREG; ++r)
 #pragma unroll

@@ -33,6 +33,13 @@ struct fq_gemm_plan {
     int tail_tiles, tail_splits, tail_kbs;
 };
 fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g);
+// Rows of K per k-block of the tiled kernel for a block shape (the unit of kb_per_split and tail_kbs):
+// the layout's k-block, except that the 128-row, 8-wave shape takes two 64-row blocks of 8-bit codes at a
+// time when K allows it and such a k-block lies inside one scale group (with two scale rows the wider
+// kernel spills and gains nothing, with four it loses).
+inline int fq_mma_kblk(int bits, int mt, int waves, int64_t K, int g) {
+    return (bits == 8 && mt == 8 && waves == 8 && K % 128 == 0 && g % 128 == 0) ? 128 : (bits == 8 ? 64 : 128);
+}
 // Workspace layout of fq_gemm: [split-K partial tiles][bf16 activations rewritten as binary16][their row scales]
 inline size_t fq_partial_bytes(const fq_gemm_plan& p, int64_t M, int64_t N) {
     const int parts = p.splits > 1 ? p.splits : (p.tail_tiles > 0 ? p.tail_splits : 0);

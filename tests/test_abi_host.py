@@ -205,6 +205,11 @@ def test_plans_are_consistent_over_many_shapes():
             assert M > 16 and mt in (2, 4, 8) and waves in (4, 8)
             assert mt == 8 or M <= 256                     # the small block shapes compete up to 256 rows only
             assert mt == 2 or mt * 8 < M                   # no block more than twice as tall as the matrix
+            # k-blocks of the block shape: 8-bit codes in the 128-row, 8-wave shape go two 64-row layout
+            # blocks at a time when a k-block of 128 rows stays inside one scale group
+            if bits == 8 and mt == 8 and waves == 8 and K % 128 == 0 and (g or K) % 128 == 0:
+                KB = K // 128
+                seen.add("wide")
             assert splits >= 1 and kbs * splits >= KB and kbs * (splits - 1) < KB
             # bf16 rows are rewritten as binary16 for the 128-row shapes of wide matrices
             extra = (-(-(M * K * 2) // 256) * 256 + M * 4) if (mt == 8 and N >= 8192) else 0
@@ -215,4 +220,4 @@ def test_plans_are_consistent_over_many_shapes():
                 assert ws == tail_splits * M * N * 4
             else:
                 assert ws == (splits * M * N * 4 if splits > 1 else 0)
-    assert {"small", "tiled", "split", "tail"} <= seen, seen
+    assert {"small", "tiled", "split", "tail", "wide"} <= seen, seen

@@ -482,12 +482,14 @@ def test_gemm_bf16_wide_matrix_split_k_and_tail():
 
 @pytest.mark.parametrize("M,K,N,dtype,g", [(300, 4224, 6160, "f16", 128), (260, 4224, 6160, "bf16", 0),
                                            (1100, 1152, 6160, "f16", 0), (900, 1152, 12288, "bf16", 128),
-                                           (1030, 1280, 9232, "f16", 256), (300, 4224, 6160, "f16", 64)])
+                                           (1030, 1280, 9232, "f16", 256), (300, 4224, 6160, "f16", 64),
+                                           (600, 128, 12288, "f16", 128)])
 def test_gemm_int8_two_layout_blocks_per_k_block(M, K, N, dtype, g):
     """8-bit codes in the 128-row, 8-wave shape: the kernel takes two 64-row k-blocks of the packed layout
     per k-block when K is a multiple of 128 and the group size too (checked through the plan's k-block
     count: K / 128 instead of K / 64 blocks in all); an odd number of them, a ragged split of K, ragged
-    last row blocks, the fp16 path for bf16 rows (N >= 8192), and g = 64, which keeps the 64-row blocks."""
+    last row blocks, the fp16 path for bf16 rows (N >= 8192), a single k-block, and g = 64, which keeps
+    the 64-row blocks."""
     import re
     fq = _fq()
     desc = fq.gemm_describe(M, N, K, 8, g)

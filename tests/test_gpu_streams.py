@@ -1,0 +1,98 @@
+"""GPU checks of how the entry points behave on streams other than the default one and when two host
+threads call them at the same time: results must be bit-identical to those of a plain call (the kernels
+add in a fixed order), also for the grouped product, whose launches fork onto two library-owned side
+streams and join back (serialised across host threads inside the library).
+"""
+import threading
+
+import numpy as np
+import pytest
+
+from paper_2308_09723_amd import workloads
+
+from gpu_util import to_dev_act, torch_mod
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _setup(fq, torch, seed):
+    """A few products that cover the small-M kernel, a split of K with workspace, the bf16 rows rewritten as
+    binary16 (workspace) and the grouped product."""
+    K, N, g = 1024, 9216, 128
+    W = workloads.weights_gaussian(K, N, seed, outlier_prob=1e-3)
+    codes, scales = fq.quantize(torch.from_numpy(W).cuda(), 4, g)
+    acts = {(M, dt): to_dev_act(workloads.activations(M, K, dt, seed + M), dt)
+            for M, dt in ((3, "f16"), (40, "f16"), (300, "bf16"))}
+    rows = [70, 0, 33, 129, 5]
+    offsets = np.concatenate([[0], np.cumsum(rows)]).astype(np.int32)
+    Ag = to_dev_act(workloads.activations(int(offsets[-1]), K, "f16", seed + 7), "f16")
+    Ng = 768
+    cg, sg = [], []
+    for e in range(len(rows)):
+        c, s = fq.quantize(torch.from_numpy(workloads.weights_gaussian(K, Ng, seed + 20 + e)).cuda(), 4, g)
+        cg.append(c)
+        sg.append(s.reshape(-1))
+    return dict(K=K, N=N, g=g, codes=codes, scales=scales, acts=acts, offsets=offsets.tolist(), Ag=Ag, Ng=Ng,
+                cg=torch.cat(cg), sg=torch.cat(sg))
+
+
+def _run_all(fq, d):
+    out = [fq.gemm(A, d["codes"], d["scales"], 4, d["g"]) for A in d["acts"].values()]
+    out.append(fq.gemm_grouped(d["Ag"], d["offsets"], d["cg"], d["sg"], 4, d["g"], d["Ng"]))
+    return out
+
+
+def test_products_on_a_side_stream_match_the_default_stream():
+    from paper_2308_09723_amd import fq
+    torch = torch_mod()
+    d = _setup(fq, torch, 4100)
+    for (M, dt) in d["acts"]:
+        _say(f"  M={M} {dt}: {fq.gemm_describe(M, d['N'], d['K'], 4, d['g'])}")
+    ref = [t.clone() for t in _run_all(fq, d)]
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        for _ in range(3):
+            got = _run_all(fq, d)
+    side.synchronize()
+    for r, c in zip(ref, got):
+        assert torch.equal(r, c)
+
+
+def test_two_host_threads_on_their_own_streams():
+    from paper_2308_09723_amd import fq
+    torch = torch_mod()
+    data = [_setup(fq, torch, 4200), _setup(fq, torch, 4300)]
+    refs = [[t.clone() for t in _run_all(fq, d)] for d in data]
+    torch.cuda.synchronize()
+    start = threading.Barrier(2)
+    failures = []
+
+    def worker(i):
+        try:
+            torch.cuda.set_device(0)
+            stream = torch.cuda.Stream()
+            with torch.cuda.stream(stream):
+                start.wait(timeout=60)
+                for it in range(25):
+                    got = _run_all(fq, data[i])
+                    stream.synchronize()
+                    for r, c in zip(refs[i], got):
+                        if not torch.equal(r, c):
+                            failures.append((i, it))
+                            return
+        except Exception as exc:      # noqa: BLE001 - reported below
+            failures.append((i, repr(exc)))
+
+    threads = [threading.Thread(target=worker, args=(i,)) for i in range(2)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    assert not any(t.is_alive() for t in threads), "a worker did not finish"
+    assert not failures, failures

@@ -172,6 +172,10 @@ int fq_quant_error_sf(const void* W_f16, int64_t K, int64_t N, int bits, int gro
  *   workspace        device scratch, >= fq_gemm_workspace_bytes(M, N, K, bits, group_size)
  *                    bytes (may be NULL when that is 0)
  * M = 0 is a valid no-op.  Deterministic: the same inputs give the same bits.
+ * The call only enqueues kernels on `stream` (no allocation, no memset, no synchronisation), so it
+ * may be recorded into a HIP graph by stream capture once every kernel shape involved has been
+ * launched normally before (the first launch of some shapes raises their LDS limit, which is a
+ * host-side call).  Calls that share a workspace must be ordered on one stream.
  * Errors: as fq_quantize, plus FQ_ERR_WORKSPACE.
  */
 int fq_gemm(const void* A, int act_dtype, int64_t M, int64_t N, int64_t K, const void* codes,

@@ -96,3 +96,33 @@ def test_two_host_threads_on_their_own_streams():
         t.join(timeout=100)
     assert not any(t.is_alive() for t in threads), "a worker did not finish"
     assert not failures, failures
+
+
+def test_products_captured_in_a_graph_replay_to_the_same_bits():
+    """fq_gemm enqueues kernels only (no memsets, no synchronisation, no allocation), so a caller may
+    capture it in a HIP graph: three replays, with eager work and synchronisations between them, each
+    compared with the eager result."""
+    from paper_2308_09723_amd import fq
+    torch = torch_mod()
+    d = _setup(fq, torch, 4400)
+    acts = list(d["acts"].values())
+    ref = [fq.gemm(A, d["codes"], d["scales"], 4, d["g"]).clone() for A in acts]
+    outs = [torch.empty_like(r) for r in ref]
+    ws = [torch.empty(max(16, fq.gemm_workspace_bytes(A.shape[0], d["N"], d["K"], 4, d["g"])), dtype=torch.uint8,
+                      device="cuda") for A in acts]
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        for A, C, w in zip(acts, outs, ws):
+            fq.gemm(A, d["codes"], d["scales"], 4, d["g"], out=C, workspace=w)
+    for replay in range(3):
+        for C in outs:
+            C.fill_(7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for r, c in zip(ref, outs):
+            assert torch.equal(r, c), f"replay {replay}"
+        # eager work between the replays
+        again = fq.gemm(acts[0], d["codes"], d["scales"], 4, d["g"])
+        assert torch.equal(again, ref[0])

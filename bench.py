@@ -254,6 +254,7 @@ def main():
         },
         "per_product": per_layer,
     }
+    out["stream_ceiling"] = stream_ceiling(torch, fq)
     if args.large_m or args.all_configs:
         out["extra"] = large_m_section(torch, fq, layers, (32, 128, 512, 2048) if args.all_configs else (256, 2048))
     if args.all_configs:
@@ -267,6 +268,24 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
+
+
+def stream_ceiling(torch, fq):
+    """What this machine's memory system delivers to a kernel that only reads (fq_stream_read_probe over a 2 GiB
+    buffer, eight times the Infinity Cache, in the launch shape of the small-M kernel), next to the vendor
+    peak the roofline uses."""
+    n = 1 << 31
+    buf = torch.empty(n, dtype=torch.uint8, device="cuda").zero_()
+    sink = torch.empty(8192, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+
+    def run():
+        st = fq.stream_read_probe_raw(buf.data_ptr(), n, sink.data_ptr(), stream)
+        if st != fq.FQ_OK:
+            raise fq.FqError(st, "fq_stream_read_probe")
+    ms = _timed(torch, run, settle=0.2, reps=20)
+    return {"kind": "read-only kernel over a 2 GiB buffer", "GBps": round(n / ms / 1e6, 1),
+            "frac_of_hbm_peak": round(n / ms / 1e6 / HBM_PEAK_GBS, 4)}
 
 
 def profile_prefill(torch, fq, workloads, reps, settle):

@@ -225,6 +225,17 @@ int fq_gemm_grouped_sf(const void* A, int act_dtype, const int32_t* offsets_host
 int fq_gemm_describe(int64_t M, int64_t N, int64_t K, int bits, int group_size, char* buf,
                      size_t buf_bytes);
 
+/*
+ * fq_stream_read_probe -- measurement helper, not part of the method: one kernel that reads
+ * `bytes` bytes of device memory (16 bytes per lane, grid-stride, 256 blocks of 768 threads: the
+ * launch shape of the small-M product) and writes one 32-bit checksum word per block to `sink`
+ * (device, >= 1024 bytes).  Timed by the caller, it gives the
+ * rate at which this GPU streams a buffer through a kernel that does nothing else: the ceiling the
+ * small-M product is compared with next to the vendor's peak.  `bytes` must be a multiple of 16.
+ * Errors: FQ_ERR_INVALID_ARG, FQ_ERR_HIP.
+ */
+int fq_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stream);
+
 /* Human-readable name of a status code (static string, never NULL). */
 const char* fq_status_string(int status);
 

@@ -248,6 +248,11 @@ int fq_gemm_describe(int64_t M, int64_t N, int64_t K, int bits, int group_size, 
     return FQ_OK;
 }
 
+int fq_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stream) {
+    if (!buf || !sink || bytes == 0 || bytes % 16 != 0) return FQ_ERR_INVALID_ARG;
+    return fq_launch_stream_read_probe(buf, bytes, sink, (hipStream_t)stream);
+}
+
 const char* fq_status_string(int status) {
     switch (status) {
         case FQ_OK: return "FQ_OK";

@@ -18,6 +18,9 @@ int fq_launch_quant_error(const void* W, int64_t K, int64_t N, int bits, int g, 
 int fq_launch_choose_group(const void* W, int64_t K, int64_t N, int g_top, int levels, float alpha,
                            int* flags_host, void* workspace, hipStream_t stream);
 
+// measurement helper: a kernel that only reads a buffer
+int fq_launch_stream_read_probe(const void* buf, size_t bytes, void* sink, hipStream_t stream);
+
 // product side
 struct fq_gemm_plan {
     int kind;      // 0 = skinny (M <= 16), 1 = tiled

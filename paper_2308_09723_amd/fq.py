@@ -67,6 +67,7 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "fq_gemm_grouped_sf": (i32, [vp, i32, ctypes.POINTER(ctypes.c_int32), i32, i64, i64, vp, vp, i32, i32, i32,
                                      vp, vp, sz, vp]),
         "fq_gemm_describe": (i32, [i64, i64, i64, i32, i32, ctypes.c_char_p, sz]),
+        "fq_stream_read_probe": (i32, [vp, sz, vp, vp]),
         "fq_status_string": (ctypes.c_char_p, [i32]),
         "fq_version": (ctypes.c_char_p, []),
     }
@@ -84,7 +85,12 @@ EXPORTED = [
     "fq_gemm_grouped", "fq_gemm_describe", "fq_status_string", "fq_version",
     "fq_quant_error_workspace_bytes", "fq_quant_error",
     "fq_quantize_sf", "fq_quant_error_sf", "fq_gemm_sf", "fq_gemm_grouped_sf", "fq_gemm_workspace_bytes_for",
+    "fq_stream_read_probe",
 ]
+
+
+def stream_read_probe_raw(buf_ptr, nbytes, sink_ptr, stream=0):
+    return int(load().fq_stream_read_probe(buf_ptr, nbytes, sink_ptr, stream))
 
 
 def status_string(status: int) -> str:

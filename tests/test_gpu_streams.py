@@ -126,3 +126,22 @@ def test_products_captured_in_a_graph_replay_to_the_same_bits():
         # eager work between the replays
         again = fq.gemm(acts[0], d["codes"], d["scales"], 4, d["g"])
         assert torch.equal(again, ref[0])
+
+
+@pytest.mark.parametrize("nbytes", [16, 1 << 20, (1 << 22) + 4096 + 48, 256 * 768 * 16 * 4 + 16])
+def test_stream_read_probe_reads_every_word_once(nbytes):
+    """The measurement helper that bench.py times as the streaming-read ceiling: the XOR of its per-block
+    checksum words equals the XOR of all 32-bit words of the buffer (every word read, none twice)."""
+    from paper_2308_09723_amd import fq
+    torch = torch_mod()
+    rng = np.random.default_rng(nbytes)
+    host = rng.integers(0, 2 ** 32, size=nbytes // 4, dtype=np.uint32)
+    buf = torch.from_numpy(host.view(np.int32)).cuda()
+    sink = torch.zeros(256, dtype=torch.int32, device="cuda")
+    st = fq.stream_read_probe_raw(buf.data_ptr(), nbytes, sink.data_ptr(), torch.cuda.current_stream().cuda_stream)
+    assert st == fq.FQ_OK
+    torch.cuda.synchronize()
+    got = np.bitwise_xor.reduce(sink.cpu().numpy().view(np.uint32))
+    assert got == np.bitwise_xor.reduce(host)
+    assert fq.stream_read_probe_raw(buf.data_ptr(), 24, sink.data_ptr(), 0) == fq.FQ_ERR_INVALID_ARG
+    assert fq.stream_read_probe_raw(None, 16, sink.data_ptr(), 0) == fq.FQ_ERR_INVALID_ARG

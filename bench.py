@@ -319,6 +319,25 @@ def profile_prefill(torch, fq, workloads, reps, settle):
         torch.cuda.synchronize()
 
 
+# Bytes of distinct weights that must pass between two uses of the same buffer in the weight-stream-bound
+# measurements: three times the 256 MB Infinity Cache, so that no call finds its weights cached.
+ROTATE_BYTES = 768e6
+
+
+def rotating(codes, scales, M):
+    """Copies of (codes, scales) to cycle through when the product is bound by the weight stream (M <= 128) and
+    one copy would fit the Infinity Cache; a single entry otherwise.  Returns (list, next_index function)."""
+    wbytes = codes.numel() * codes.element_size() + scales.numel() * scales.element_size()
+    n = 1 if M > 128 else max(1, int(-(-ROTATE_BYTES // wbytes)) + 1)
+    bufs = [(codes, scales)] + [(codes.clone(), scales.clone()) for _ in range(n - 1)]
+    state = {"i": 0}
+
+    def nxt():
+        state["i"] = (state["i"] + 1) % n
+        return bufs[state["i"]]
+    return bufs, nxt
+
+
 def _timed(torch, run, settle=0.3, reps=20):
     """Mean milliseconds per call of run(), after `settle` seconds of the same call."""
     run()
@@ -435,12 +454,16 @@ def bf16_scales_section(torch, fq, workloads):
             need = fq.gemm_workspace_bytes(M, N, K, BITS, GROUP)
             ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
 
+            bufs, nxt = rotating(codes, scales, M)
+
             def run():
-                st = fq.gemm_sf_raw(A.data_ptr(), fq.FQ_BF16, M, N, K, codes.data_ptr(), scales.data_ptr(), sf, BITS,
+                c, s_ = nxt()
+                st = fq.gemm_sf_raw(A.data_ptr(), fq.FQ_BF16, M, N, K, c.data_ptr(), s_.data_ptr(), sf, BITS,
                                     GROUP, C.data_ptr(), ws.data_ptr(), ws.numel(), stream)
                 if st != fq.FQ_OK:
                     raise fq.FqError(st, "fq_gemm_sf")
             ms = _timed(torch, run)
+            del bufs
             wbytes = codes.numel() + scales.numel() * 2
             res[f"M{M}_{tag}"] = {"us": round(ms * 1e3, 2), "weight_TBps": round(wbytes / ms / 1e9, 3),
                                   "TFLOPs": round(2.0 * M * N * K / ms / 1e9, 1)}
@@ -466,12 +489,16 @@ def int3_section(torch, fq, workloads):
             need = fq.gemm_workspace_bytes(M, N, K, 3, GROUP)
             ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
 
+            bufs, nxt = rotating(codes, scales, M)
+
             def run():
-                st = fq.gemm_raw(A.data_ptr(), act, M, N, K, codes.data_ptr(), scales.data_ptr(), 3, GROUP,
+                c, s_ = nxt()
+                st = fq.gemm_raw(A.data_ptr(), act, M, N, K, c.data_ptr(), s_.data_ptr(), 3, GROUP,
                                  C.data_ptr(), ws.data_ptr(), ws.numel(), stream)
                 if st != fq.FQ_OK:
                     raise fq.FqError(st, "fq_gemm")
             ms = _timed(torch, run)
+            del bufs
             res[f"{name}_M{M}"] = {"us": round(ms * 1e3, 2), "weight_TBps": round(wbytes / ms / 1e9, 3),
                                    "TFLOPs": round(2.0 * M * N * K / ms / 1e9, 1),
                                    "plan": fq.gemm_describe(M, N, K, 3, GROUP)}
@@ -504,12 +531,16 @@ def stress_section(torch, fq, workloads):
                 need = fq.gemm_workspace_bytes(M, N, K, bits, g)
                 ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
 
+                bufs, nxt = rotating(codes, scales, M)
+
                 def run():
-                    st = fq.gemm_raw(A.data_ptr(), fq.FQ_BF16, M, N, K, codes.data_ptr(), scales.data_ptr(), bits, g,
+                    c, s_ = nxt()
+                    st = fq.gemm_raw(A.data_ptr(), fq.FQ_BF16, M, N, K, c.data_ptr(), s_.data_ptr(), bits, g,
                                      C.data_ptr(), ws.data_ptr(), ws.numel(), stream)
                     if st != fq.FQ_OK:
                         raise fq.FqError(st, "fq_gemm")
                 ms = _timed(torch, run, settle=0.15, reps=20)
+                del bufs
                 res[f"int{bits}_g{g or K}_M{M}"] = {
                     "us": round(ms * 1e3, 2), "weight_TBps": round(wbytes / ms / 1e9, 3),
                     "TFLOPs": round(2.0 * M * N * K / ms / 1e9, 1), "plan": fq.gemm_describe(M, N, K, bits, g)}
@@ -518,7 +549,9 @@ def stress_section(torch, fq, workloads):
 
 
 def large_m_section(torch, fq, layers, Ms=(256, 2048)):
-    """Prefill-sized products on the same int4 weights: TFLOP/s and fraction of the dense MFMA peak."""
+    """Prefill-sized and mid-M products on the same int4 weights: TFLOP/s and fraction of the dense MFMA peak,
+    and the weight-stream rate.  Up to M = 128 the calls cycle through copies of the weights (see `rotating`),
+    so that the rate is not that of the Infinity Cache."""
     res = {}
     stream = torch.cuda.current_stream().cuda_stream
     for name, K, N, codes, scales in layers:
@@ -529,8 +562,11 @@ def large_m_section(torch, fq, layers, Ms=(256, 2048)):
                 need = fq.gemm_workspace_bytes(M, N, K, BITS, GROUP)
                 ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
 
+                bufs, nxt = rotating(codes, scales, M)
+
                 def run():
-                    st = fq.gemm_raw(A.data_ptr(), act, M, N, K, codes.data_ptr(), scales.data_ptr(), BITS, GROUP,
+                    c, s_ = nxt()
+                    st = fq.gemm_raw(A.data_ptr(), act, M, N, K, c.data_ptr(), s_.data_ptr(), BITS, GROUP,
                                      C.data_ptr(), ws.data_ptr(), ws.numel(), stream)
                     if st != fq.FQ_OK:
                         raise fq.FqError(st, "fq_gemm")

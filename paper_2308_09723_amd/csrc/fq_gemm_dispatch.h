@@ -190,10 +190,7 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
 template <int ACT, int BITS>
 int launch_grouped_typed(const void* A, const int32_t* offsets, int E, int64_t N, int64_t K,
                          const void* codes, const void* scales, int g, void* C, const hipStream_t* streams) {
-    const int kblk = fq_kblk(BITS);
-    const int sr = (g % kblk) == 0 ? 1 : ((kblk % g) == 0 ? kblk / g : kblk / 32);
     const int ntiles = (int)(N / FQ_NTILE);
-    const int KB = (int)(K / kblk);
     const int64_t codes_stride16 = (int64_t)(K * N * BITS / 8) / 16;
     const int64_t scales_stride = (K / g) * N;
     fq_group_items items;
@@ -205,15 +202,21 @@ int launch_grouped_typed(const void* A, const int32_t* offsets, int E, int64_t N
         const hipStream_t stream = streams[mt == 8 ? 0 : (mt == 4 ? 1 : 2)];
         const int nblocks_n = (ntiles + waves * MMA_NT - 1) / (waves * MMA_NT);
         const int ring = mt == 8 ? 2 : (mt == 4 ? FQ_RING_MT4 : FQ_RING_MT2);
+        // rows of K per k-block of this tile size (8-bit codes: two layout blocks at a time in the 128-row
+        // shape where K and g allow it) and the scale rows such a k-block spans
+        const int kblk = fq_mma_kblk(BITS, mt, waves, K, g);
+        const bool wide = kblk != fq_kblk(BITS);
+        const int sr = (g % kblk) == 0 ? 1 : ((kblk % g) == 0 ? kblk / g : kblk / 32);
+        const int KB = (int)(K / kblk);
         const size_t lds = (size_t)(ring ? ring + 1 : 2) * (kblk / 8) * bm * 16;
         items.count = 0;
         auto flush_items = [&]() -> int {
             if (items.count == 0) return FQ_OK;
             dim3 grid((unsigned)((int64_t)nblocks_n * items.count));
-#define FQ_GROUPED_LAUNCH_SR(MT_, W_, PIPE_, SR_)                                                        \
+#define FQ_GROUPED_LAUNCH_SR(MT_, W_, PIPE_, SR_, KREC_)                                                 \
     do {                                                                                                \
         auto kern = fq_gemm_mma_kernel<ACT, BITS, MT_, MMA_NT, W_, SR_, true, PIPE_,                   \
-                                       use_post(ACT, BITS, MT_, SR_, PIPE_)>;                                 \
+                                       use_post(ACT, BITS, MT_, SR_, PIPE_), KREC_>;                    \
         if (lds > 65536) {                                                                              \
             static std::atomic<uint64_t> raised;                                                        \
             if (raise_lds_limit((const void*)kern, raised) != FQ_OK) return FQ_ERR_HIP;                 \
@@ -225,11 +228,18 @@ int launch_grouped_typed(const void* A, const int32_t* offsets, int E, int64_t N
     } while (0)
 #define FQ_GROUPED_LAUNCH(MT_, W_, PIPE_)                                                               \
     do {                                                                                                \
-        if (sr == 1) FQ_GROUPED_LAUNCH_SR(MT_, W_, PIPE_, 1);                                           \
-        else if (sr == 2) FQ_GROUPED_LAUNCH_SR(MT_, W_, PIPE_, 2);                                      \
-        else if constexpr (BITS != 8) FQ_GROUPED_LAUNCH_SR(MT_, W_, PIPE_, 4);                          \
+        if (sr == 1) FQ_GROUPED_LAUNCH_SR(MT_, W_, PIPE_, 1, 1);                                        \
+        else if (sr == 2) FQ_GROUPED_LAUNCH_SR(MT_, W_, PIPE_, 2, 1);                                   \
+        else if constexpr (BITS != 8) FQ_GROUPED_LAUNCH_SR(MT_, W_, PIPE_, 4, 1);                       \
     } while (0)
-            if (mt == 8) FQ_GROUPED_LAUNCH(8, 8, 2);
+            if (mt == 8) {
+                if constexpr (BITS == 8) {
+                    if (wide) FQ_GROUPED_LAUNCH_SR(8, 8, 2, 1, 2);
+                    else FQ_GROUPED_LAUNCH(8, 8, 2);
+                } else {
+                    FQ_GROUPED_LAUNCH(8, 8, 2);
+                }
+            }
             else if (mt == 4 && waves == 8) FQ_GROUPED_LAUNCH(4, 8, FQ_RING_MT4);
             else if (mt == 4) FQ_GROUPED_LAUNCH(4, 4, FQ_RING_MT4);
             else if (waves == 8) FQ_GROUPED_LAUNCH(2, 8, FQ_RING_MT2);

@@ -500,3 +500,11 @@ def test_gemm_int8_two_layout_blocks_per_k_block(M, K, N, dtype, g):
     unit = 128 if (g or K) % 128 == 0 else 64
     assert kbs * splits >= K // unit > kbs * (splits - 1)
     _gemm_case(M, K, N, dtype, 8, g, seed=9500 + M + g)
+
+
+@pytest.mark.parametrize("dtype,g,K", [("bf16", 128, 384), ("f16", 0, 640), ("f16", 64, 384)])
+def test_grouped_gemm_int8_two_layout_blocks_per_k_block(dtype, g, K):
+    """8-bit experts: the 128-row tiles take two 64-row layout k-blocks per k-block when K and the group size
+    are multiples of 128 (an odd number of them here), the smaller tiles and g = 64 keep the 64-row blocks."""
+    _say(f"grouped int8 wide {dtype} g={g} K={K}")
+    _grouped_case(dtype, 8, g, K, 784, [130, 31, 64, 0, 257, 1, 97], seed=35)

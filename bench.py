@@ -86,9 +86,10 @@ def main():
                     help="also time the other BASELINE configurations (reported under 'extra'): prefill and mid-M "
                          "products (configs[2]), the grouped expert products (configs[3]) and the heavy-tailed "
                          "stress layer (configs[4])")
-    ap.add_argument("--profile", choices=["decode", "prefill", "copy", "moe", "midm", "quantize"], default=None,
+    ap.add_argument("--profile", choices=["decode", "prefill", "prefill-int8", "copy", "moe", "midm", "quantize"], default=None,
                     help="short untimed run of one case for rocprofv3 (no JSON line): 'decode' = the benchmark "
-                         "step, 'prefill' = QKV-shaped product at M = 2048 (bf16), 'copy' = a 1 GiB device copy "
+                         "step, 'prefill' = QKV-shaped product at M = 2048 (bf16, then fp16; 'prefill-int8': the same with "
+                         "8-bit codes, one group per column), 'copy' = a 1 GiB device copy "
                          "whose FETCH_SIZE / WRITE_SIZE calibrate the counters, 'moe' = the grouped expert products of "
                          "configs[3], 'midm' = the QKV-shaped product at M = 32 and M = 128 (bf16), 'quantize' = the offline "
                          "steps (fq_quantize, fq_choose_group, fq_quant_error) on the FC1-shaped matrix")
@@ -115,6 +116,9 @@ def main():
         return
     if args.profile == "prefill":
         profile_prefill(torch, fq, workloads, args.steps, args.settle)
+        return
+    if args.profile == "prefill-int8":
+        profile_prefill(torch, fq, workloads, args.steps, args.settle, bits=8, group=0)
         return
     if args.profile == "moe":
         moe_section(torch, fq, workloads)
@@ -288,16 +292,16 @@ def stream_ceiling(torch, fq):
             "frac_of_hbm_peak": round(n / ms / 1e6 / HBM_PEAK_GBS, 4)}
 
 
-def profile_prefill(torch, fq, workloads, reps, settle):
+def profile_prefill(torch, fq, workloads, reps, settle, bits=BITS, group=GROUP):
     """QKV-shaped product at M = 2048, first with bf16 and then with fp16 activations: `settle` seconds of
     launches each, then `reps` more (for rocprofv3; the last records of each kernel in the trace are the
     settled ones)."""
     K, N = workloads.OPT175B_LAYERS["qkv"]
     M = 2048
     W = make_weight(torch, K, N, 100)
-    codes, scales = fq.quantize(W, BITS, GROUP)
+    codes, scales = fq.quantize(W, bits, group)
     del W
-    need = fq.gemm_workspace_bytes(M, N, K, BITS, GROUP)
+    need = fq.gemm_workspace_bytes(M, N, K, bits, group)
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
     for act, dt in ((fq.FQ_BF16, torch.bfloat16), (fq.FQ_F16, torch.float16)):
@@ -305,7 +309,7 @@ def profile_prefill(torch, fq, workloads, reps, settle):
         C = torch.empty((M, N), device="cuda", dtype=dt)
 
         def run():
-            st = fq.gemm_raw(A.data_ptr(), act, M, N, K, codes.data_ptr(), scales.data_ptr(), BITS, GROUP,
+            st = fq.gemm_raw(A.data_ptr(), act, M, N, K, codes.data_ptr(), scales.data_ptr(), bits, group,
                              C.data_ptr(), ws.data_ptr(), ws.numel(), stream)
             if st != fq.FQ_OK:
                 raise fq.FqError(st, "fq_gemm")

@@ -82,6 +82,8 @@ def main():
                          "slower for the first ~0.1-0.5 s of sustained load (clock ramp); 0 disables")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--large-m", action="store_true", help="also time the M >= 256 products (reported under 'extra')")
+    ap.add_argument("--no-large-m", action="store_true",
+                    help="leave out the short M >= 256 / mid-M block of the default line ('roofline_large_m', 'mid_m')")
     ap.add_argument("--all-configs", action="store_true",
                     help="also time the other BASELINE configurations (reported under 'extra'): prefill and mid-M "
                          "products (configs[2]), the grouped expert products (configs[3]) and the heavy-tailed "
@@ -217,8 +219,10 @@ def main():
         ts = [ev[k][i][0].elapsed_time(ev[k][i][1]) * 1e3 for k in ev]
         per_call_us.append(sum(ts) / len(ts) if ts else float("nan"))
     per_layer = {f"{c[0]}_M{c[1]}": {"us": round(t, 2), "weight_TBps": round(c[7] / t / 1e6, 3),
+                                    "frac_of_hbm_peak": round(c[7] / t / 1e3 / HBM_PEAK_GBS, 4),
                                     "plan": fq.gemm_describe(c[1], c[5].shape[1], c[2].shape[1], BITS, GROUP)}
                  for c, t in zip(calls, per_call_us)}
+    traffic, traffic_note = profiled_traffic([v["plan"] for v in per_layer.values()])
 
     out = {
         "metric": "W4A16 GEMM weight-stream rate, OPT-175B decode layers (M=1 and M=8)",
@@ -247,9 +251,11 @@ def main():
             "peak": HBM_PEAK_GBS,
             "unit": "GB/s",
             "frac": round(achieved / HBM_PEAK_GBS, 4),
-            # FETCH_SIZE summed over the 9 launches of a step, rocprofv3 --pmc, 2 KiB per count as calibrated
-            # with a 1 GiB copy (profiles/fq_gemm_skinny_kernel_opt175b_decode.md); bytes per step
-            "traffic": 1.903e9,
+            # HBM bytes per step from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE passes recorded in
+            # profiles/ (counter-calibrated with a 1 GiB copy); null when that record was taken with other
+            # kernel plans than the ones this run used
+            "traffic": traffic,
+            "traffic_source": traffic_note,
             "kernel": "fq_gemm_skinny_kernel (8 products per step, plus fq_reduce_kernel for the one that splits K "
                       "over the grid; algorithmic bytes of the step / mean HIP-event duration of its back-to-back "
                       "launches)",
@@ -259,6 +265,8 @@ def main():
         "per_product": per_layer,
     }
     out["stream_ceiling"] = stream_ceiling(torch, fq)
+    if not args.no_large_m:
+        out.update(default_large_m(torch, fq, layers))
     if args.large_m or args.all_configs:
         out["extra"] = large_m_section(torch, fq, layers, (32, 128, 512, 2048) if args.all_configs else (256, 2048))
     if args.all_configs:
@@ -272,6 +280,60 @@ def main():
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
+
+
+TRAFFIC_PROFILE = os.path.join(ROOT, "profiles", "fq_gemm_skinny_kernel_opt175b_decode.md")
+
+
+def profiled_traffic(plans):
+    """HBM bytes per decode step as the rocprofv3 counter passes recorded them.  The profile summary carries
+    one line `bench-traffic: bytes_per_step=<float> commit=<hash> plans=<the eight plan descriptions joined by
+    ';'>`; the figure is used only if this run's plans are the recorded ones, so that it cannot outlive the
+    kernels it was measured on unnoticed."""
+    try:
+        with open(TRAFFIC_PROFILE) as f:
+            lines = [ln.strip() for ln in f if ln.strip().startswith("bench-traffic:")]
+    except OSError:
+        return None, "no profile summary found"
+    if not lines:
+        return None, "profile summary carries no bench-traffic line"
+    fields = dict(kv.split("=", 1) for kv in lines[-1][len("bench-traffic:"):].strip().split(" ", 2))
+    if fields.get("plans", "") != ";".join(plans):
+        return None, (f"profiles/{os.path.basename(TRAFFIC_PROFILE)} (commit {fields.get('commit')}) was taken with "
+                      "other kernel plans; re-profile")
+    return float(fields["bytes_per_step"]), (f"rocprofv3 --pmc FETCH_SIZE + WRITE_SIZE, profiles/"
+                                             f"{os.path.basename(TRAFFIC_PROFILE)}, commit {fields.get('commit')}")
+
+
+def default_large_m(torch, fq, layers):
+    """The M >= 256 half of the metric in the default line, kept to a few seconds: the QKV-shaped product at
+    M = 2048 with bf16 and with fp16 activations (for bf16 the rewrite of the activation rows that precedes
+    the product is inside the timed bracket), as TFLOP/s against the dense fp16 / bf16 MFMA peak; and the
+    transition regime, QKV at M = 32 (against the HBM peak) and M = 128 (against the MFMA peak), bf16, cycling
+    through copies of the weights."""
+    qkv = [l for l in layers if l[0] == "qkv"]
+    big = large_m_section(torch, fq, qkv, (2048,), settle=0.4, reps=10)
+    mid = large_m_section(torch, fq, qkv, (32, 128), dtypes=("bf16",), settle=0.25, reps=20)
+    best = max(big.values(), key=lambda r: r["TFLOPs"])
+    res = {
+        "roofline_large_m": {
+            "bound": "mfma", "unit": "TFLOP/s", "peak": MFMA_PEAK_TFLOPS,
+            "achieved": best["TFLOPs"], "frac": best["frac_of_mfma_peak"],
+            "kernel": "fq_gemm_mma_kernel, 128-row x 384-column blocks (bf16 activations: fq_rows_to_f16_kernel + the "
+                      "product on the fp16 matrix path, both inside the timed bracket); flops = 2 M N K / mean HIP-event "
+                      "time of 10 back-to-back calls",
+            "workload": "BASELINE configs[2] shape: QKV 12288 x 36864, int4 g=128, M = 2048",
+            "cases": big,
+        },
+        "mid_m": {
+            "workload": "BASELINE configs[2] shape: QKV 12288 x 36864, int4 g=128, bf16, weights cycled through "
+                        "copies so that none is cache-resident",
+            "M32": dict(mid["qkv_M32_bf16"], bound="hbm",
+                        frac=round(mid["qkv_M32_bf16"]["weight_TBps"] * 1e3 / HBM_PEAK_GBS, 4)),
+            "M128": dict(mid["qkv_M128_bf16"], bound="mfma", frac=mid["qkv_M128_bf16"]["frac_of_mfma_peak"]),
+        },
+    }
+    return res
 
 
 def stream_ceiling(torch, fq):
@@ -552,7 +614,7 @@ def stress_section(torch, fq, workloads):
     return res
 
 
-def large_m_section(torch, fq, layers, Ms=(256, 2048)):
+def large_m_section(torch, fq, layers, Ms=(256, 2048), dtypes=("bf16", "f16"), settle=0.3, reps=20):
     """Prefill-sized and mid-M products on the same int4 weights: TFLOP/s and fraction of the dense MFMA peak,
     and the weight-stream rate.  Up to M = 128 the calls cycle through copies of the weights (see `rotating`),
     so that the rate is not that of the Infinity Cache."""
@@ -561,6 +623,8 @@ def large_m_section(torch, fq, layers, Ms=(256, 2048)):
     for name, K, N, codes, scales in layers:
         for M in Ms:
             for tag, act, dt in (("bf16", fq.FQ_BF16, torch.bfloat16), ("f16", fq.FQ_F16, torch.float16)):
+                if tag not in dtypes:
+                    continue
                 A = torch.randn((M, K), device="cuda", dtype=torch.float32).to(dt)
                 C = torch.empty((M, N), device="cuda", dtype=dt)
                 need = fq.gemm_workspace_bytes(M, N, K, BITS, GROUP)
@@ -577,12 +641,11 @@ def large_m_section(torch, fq, layers, Ms=(256, 2048)):
                 # untimed: about 0.3 s of the same product, so that the clocks have settled
                 run()
                 torch.cuda.synchronize()
-                t_end = time.perf_counter() + 0.3
+                t_end = time.perf_counter() + settle
                 while time.perf_counter() < t_end:
                     for _ in range(4):
                         run()
                     torch.cuda.synchronize()
-                reps = 20
                 e0 = torch.cuda.Event(enable_timing=True)
                 e1 = torch.cuda.Event(enable_timing=True)
                 e0.record()

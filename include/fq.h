@@ -58,8 +58,8 @@ typedef enum fq_scale_format {
  *   N           multiple of 16
  *   K           multiple of 128 (bits = 3, 4) or 64 (bits = 8)
  *   group_size  0 or K (one scale per column), or a multiple of 32 that divides K
- *               (the paper plans "any power of 2 group size greater than 16",
- *               section 5; multiples of 32 cover that from 32 up).
+ *               (section 5 plans kernels for every power-of-two group size
+ *               above 16; multiples of 32 cover that from 32 up).
  */
 
 /* Size in bytes of the packed code buffer: K*N*bits/8 (no padding).  0 on invalid arguments. */

@@ -41,8 +41,9 @@ R6  Section 3.3: "range" is the abs-max of a group; a halving step is taken
     min(child ranges) < (1 - alpha) * parent range.  (Read literally with
     abs-max ranges, new/old > alpha is always true for alpha < 1 because the
     child that holds the parent's maximum has ratio exactly 1; the closing
-    sentence of the section states the stop rule as "range differences ...
-    smaller than alpha", which is what is implemented.)  One group size per
+    sentence of the section states the stop rule in terms of the range
+    difference between two granularities falling below alpha, which is what
+    is implemented.)  One group size per
     matrix.  The value of alpha is not recoverable from the paper (its figure
     2b is an image): the *default* alpha is PARITY UNPINNED; the function
     alpha -> g is pinned by constructed cases.

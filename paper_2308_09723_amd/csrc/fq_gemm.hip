@@ -30,14 +30,29 @@ FQ_DECLARE_GEMM(0, 3)   // 3-bit codes
 FQ_DECLARE_GEMM(1, 3)
 FQ_DECLARE_GEMM(2, 3)
 
+// Compute units of the device, asked once per process (the current device at the first call); without a
+// device (host-only use of the size queries and fq_gemm_describe) the MI355X's 256.
+static int fq_cu_count() {
+    static const int n = [] {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            return v;
+        (void)hipGetLastError();
+        return 256;
+    }();
+    return n;
+}
+
 fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
     fq_gemm_plan p = {};
+    const int ncu = fq_cu_count();
     const int kblk = fq_kblk(bits);
     const int KB = (int)(K / kblk);
     const int ntiles = (int)(N / FQ_NTILE);
     if (M <= 16) {
         // One block per compute unit, all resident at once.  Candidates are scored by how evenly
-        // the column tiles (times the grid's split of K) fill 256 blocks, by the bytes a compute
+        // the column tiles (times the grid's split of K) fill one block per compute unit, by the bytes a compute
         // unit keeps in flight (waves x NT KiB x ring depth, ~64 KiB saturates), and by how many
         // activation units a lane must stage (fewer registers); ties keep the earlier variant.
         // The factors come from sweeps over the OPT-175B shapes at M = 1 and 8.
@@ -63,12 +78,12 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
                 // Few column blocks: K is also split over the grid (binary32 partials + a second kernel),
                 // which moreover divides the activation bytes every block has to fetch.
                 int gs = 1;
-                if (blocks <= 128) gs = (int)(256 / blocks);
+                if (blocks <= ncu / 2) gs = (int)(ncu / blocks);
                 if (gs > 8) gs = 8;
                 if (gs > SB) gs = SB;
                 const int64_t grid = blocks * gs;
-                const int64_t rounds = (grid + 255) / 256;
-                const double eff = (double)ntiles * gs / (double)(rounds * 256 * tb);
+                const int64_t rounds = (grid + ncu - 1) / ncu;
+                const double eff = (double)ntiles * gs / (double)(rounds * ncu * tb);
                 const int waves = gp * kw;
                 const double inflight = (double)waves * sv.nt * sv.depth;   // KiB
                 const double n_it = (double)((SB + gs - 1) / gs);
@@ -79,8 +94,8 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
                 // block the register ring is mostly filling and draining
                 if (gs > 1) score *= n_it >= 16.0 ? 0.80 : 0.65;
                 // every block fetches its whole k range of the activations: M * K * 2 / gs bytes,
-                // 256 times over, next to K * N * bits / 8 bytes of weights
-                score /= 1.0 + 0.15 * ((double)M * 2.0 * 256.0 / gs) / ((double)N * bits / 8.0);
+                // once per block, next to K * N * bits / 8 bytes of weights
+                score /= 1.0 + 0.15 * ((double)M * 2.0 * (double)ncu / gs) / ((double)N * bits / 8.0);
                 if (waves < 6) score *= 0.85;
                 if (kw == 1) score *= 0.95;                  // no k-workers: measured ~5 % slower
                 if (score > best + 1e-9) {
@@ -99,7 +114,7 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
         // Tiled MFMA kernel: BM = 16 * mt rows per block (mt = 2, 4 or 8), 48 columns per wave, 4 or 8
         // waves, and optionally a split of K over `splits` blocks whose binary32 partial tiles a second
         // kernel adds.  The block shape is the one that minimises a measured cost model:
-        //   time = ceil(blocks / 256) * k-blocks per block * u(mt, waves)  +  cost of the partials
+        //   time = ceil(blocks / compute units) * k-blocks per block * u(mt, waves)  +  cost of the partials
         // where u is the time one block spends on one k-block of 128 rows of K when every compute
         // unit holds its share of blocks (microseconds), and the partials cost their write plus read
         // at ~5 TB/s plus a launch.  The constants are a least-squares fit (of log time; rms error
@@ -148,7 +163,7 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
                     const int kbs = (KB + splits - 1) / splits;
                     splits = (KB + kbs - 1) / kbs;
                     const int64_t blocks = nbn * nbm * splits;
-                    const int64_t per_cu = (blocks + 255) / 256;
+                    const int64_t per_cu = (blocks + ncu - 1) / ncu;
                     double t = (double)per_cu * kbs * u;
                     if (waves == 4) {
                         // u is a 4-wave block's share when `cap` of them run together on a compute unit; the
@@ -177,7 +192,7 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
                 // that they occupy every block slot once more: the last round then lasts 1 / tail_splits
                 // of a full one, at the price of partial tiles for those tiles only.
                 const int64_t tiles = nbn * nbm;
-                const int64_t slots = 256 * (waves == 8 ? 1 : (mt == 2 ? 3 : 2));
+                const int64_t slots = (int64_t)ncu * (waves == 8 ? 1 : (mt == 2 ? 3 : 2));
                 const int64_t rem = tiles % slots;
                 if (tiles > slots && rem > 0) {
                     int ts = (int)(slots / rem);
@@ -187,7 +202,7 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g) {
                         const int tkbs = (KB + ts - 1) / ts;
                         ts = (KB + tkbs - 1) / tkbs;
                         const int64_t head = tiles - rem;
-                        double t = (double)(head / 256) * KB * u + (double)((rem * ts + 255) / 256) * tkbs * u;
+                        double t = (double)(head / ncu) * KB * u + (double)((rem * ts + ncu - 1) / ncu) * tkbs * u;
                         const double bm_bn = (double)bm * (double)(waves * MMA_NT * FQ_NTILE);
                         t += 2.0 * ts * (double)rem * bm_bn * 4.0 / 5e6 + 5.0;
                         // for the small shapes the model is 10 % optimistic about this form (QKV at M = 256:

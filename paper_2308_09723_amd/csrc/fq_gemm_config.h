@@ -10,12 +10,8 @@ constexpr int MMA_NT = 3;       // column tiles per wave of the large-M kernel
 // the 32-row block shapes; 0 selects the two-buffer form.  The 128-row, 8-wave shape uses depth 2.
 // Measured on the OPT-175B shapes at M = 32 and 64: depth 2 is 2-6 % faster than the two-buffer form,
 // depths 3 and 4 are slower (their registers cost a resident wave per SIMD).
-#ifndef FQ_RING_MT4
-#define FQ_RING_MT4 2
-#endif
-#ifndef FQ_RING_MT2
-#define FQ_RING_MT2 2
-#endif
+constexpr int FQ_RING_MT4 = 2;
+constexpr int FQ_RING_MT2 = 2;
 
 // Post-scaled form of the large-M kernel (codes converted without their scale, one fold per scale
 // group and output tile): used where the conversion, not the matrix pipe, sets the pace, i.e. 3- and

@@ -1,7 +1,7 @@
 // Packed code layout shared by the quantiser, the unpacker and the product kernels.
 //
 // The paper's kernels consume a pre-arranged weight buffer it does not describe
-// (section 4.1 only says the block size 64 "matches the K tile size").  This layout is
+// (section 4.1 only notes that its block size of 64 equals the K extent of its kernel tile).  This layout is
 // chosen for CDNA4: a wavefront's 64 lanes x 16 bytes is one contiguous KiB (eight full
 // 128-byte lines), and the 16 bytes a lane receives are exactly the values it feeds, as
 // they are, into v_mfma_f32_16x16x32 operands for one output column.

@@ -27,6 +27,35 @@ def _sample_columns(N, count, seed):
     return np.array(sorted(cols), dtype=np.int64)
 
 
+def _structured_columns(N, seed, block=384, tile=16, extra=16):
+    """A column sample that follows the kernels' tiling instead of chance.  The tiled kernel's blocks span
+    384 columns (8 waves x 3 tiles of 16; 192 for its 4-wave shapes) and walk panels of four column blocks;
+    the small-M kernel's blocks take runs of 1 - 36 tiles.  The sample holds
+      * one column of EVERY 384-column block, its tile position (0..23) and its column inside the tile
+        (0..15) advancing from block to block, so that every column block of every panel (hence every block
+        of the grid, the K-split ones of a partly filled last round included) has a compared column;
+      * every one of the 24 tile positions of the first, the middle and the last column block, plus the
+        first and last column of each of these blocks;
+      * the first and last tiles' edge columns and `extra` seeded random columns."""
+    rng = np.random.default_rng(seed)
+    nblk = -(-N // block)
+    tpb = block // tile
+    cols = set()
+    for b in range(nblk):
+        c = b * block + ((7 * b + 3) % tpb) * tile + (5 * b + 1) % tile
+        cols.add(min(c, N - 1))
+    for b in sorted({0, nblk // 2, nblk - 1}):
+        lo, hi = b * block, min(N, (b + 1) * block)
+        cols.update([lo, hi - 1])
+        for t in range(tpb):
+            c = lo + t * tile + (3 * t + b) % tile
+            if c < hi:
+                cols.add(c)
+    cols.update([0, 1, 15, 16, N - 17, N - 16, N - 1])
+    cols.update(rng.integers(0, N, size=extra).tolist())
+    return np.array(sorted(cols), dtype=np.int64)
+
+
 def _check_layer(W, bits, g, cases, cols, tag):
     """cases: list of (M, dtype, seed).  Quantises W on the GPU, checks sampled columns against the oracle."""
     from paper_2308_09723_amd import fq
@@ -53,7 +82,7 @@ def _check_layer(W, bits, g, cases, cols, tag):
         assert err <= TOL[dtype] * scale, f"{tag} M={M} {dtype}: {err} > {TOL[dtype]} * {scale}"
 
 
-@pytest.mark.parametrize("layer", ["out_proj", "fc2", "qkv"])
+@pytest.mark.parametrize("layer", ["out_proj", "fc2", "qkv", "fc1"])
 def test_opt175b_decode_layers_full_size(layer):
     """BASELINE configs[1]: int4, group 128, fp16, M = 1 and M = 8 — the shapes and plans bench.py times."""
     _say(f"full-size decode layer {layer}: generating weights")
@@ -80,6 +109,46 @@ def test_opt175b_prefill_full_size_bf16():
     _check_layer(W, 4, 256 if g_pick != 256 else 128, [(512, "bf16", 35)], cols, "out_proj")
     # the 32- and 64-row blocks in their post-scaled form (one scale row per k-block), both activation types
     _check_layer(W, 4, 128, [(32, "f16", 36), (64, "f16", 37), (32, "bf16", 38), (64, "bf16", 39)], cols, "out_proj")
+
+
+@pytest.mark.parametrize("layer", ["qkv", "fc1", "fc2", "out_proj"])
+def test_opt175b_layers_full_size_structured_sample(layer):
+    """BASELINE configs[1] and configs[2] on every layer shape, in the plans bench.py times, compared with the
+    oracle on the structured column sample (every column block, every tile position): decode M = 1 and 8
+    (fp16), prefill M = 512 and 2048 in bf16 AND fp16; FC2 (384 k-blocks to accumulate) also at M = 32 and
+    128; QKV also with 8-bit codes, one group per column, at M = 2048."""
+    _say(f"full-size layer {layer}: generating weights")
+    W = workloads.opt175b_weight(layer, seed=7)
+    cols = _structured_columns(W.shape[1], seed=17)
+    _say(f"  {len(cols)} sampled columns of {W.shape[1]}")
+    cases = [(1, "f16", 71), (8, "f16", 72), (512, "bf16", 73), (2048, "bf16", 74), (2048, "f16", 75)]
+    if layer == "fc2":
+        cases += [(32, "bf16", 76), (128, "bf16", 77), (128, "f16", 78)]
+    _check_layer(W, 4, 128, cases, cols, layer)
+    if layer == "qkv":
+        _check_layer(W, 8, 0, [(2048, "bf16", 79), (2048, "f16", 80)], cols, layer)
+
+
+def test_out_proj_decode_every_column():
+    """The out-proj layer (the one whose k-workers run the fewest iterations and whose K is split over the
+    grid) at M = 1 and M = 8: codes, scales and the product compared with the oracle on ALL 12288 columns."""
+    from paper_2308_09723_amd import fq
+    torch = torch_mod()
+    _say("out-proj, every column: generating weights")
+    W = workloads.opt175b_weight("out_proj", seed=8)
+    K, N = W.shape
+    codes, scales = fq.quantize(torch.from_numpy(W).cuda(), 4, 128)
+    q_ref, s_ref = oracle.quantize(W, 4, 128)
+    assert np.array_equal(scales.view(torch.int16).cpu().numpy().view(np.uint16), s_ref.view(np.uint16))
+    assert np.array_equal(fq.unpack(codes, K, N, 4).cpu().numpy(), q_ref)
+    for M, seed in ((1, 81), (8, 82)):
+        A = workloads.activations(M, K, "f16", seed)
+        C = from_dev_act(fq.gemm(to_dev_act(A, "f16"), codes, scales, 4, 128), "f16")
+        C_ref = oracle.gemm_ref(A, q_ref, s_ref)
+        scale = np.max(np.abs(C_ref))
+        err = np.max(np.abs(C - C_ref))
+        _say(f"  out_proj all columns M={M}: rel err {err / scale:.2e}  [{fq.gemm_describe(M, N, K, 4, 128)}]")
+        assert err <= TOL["f16"] * scale
 
 
 def test_heavy_tailed_stress_layer_full_size():
@@ -132,6 +201,51 @@ def test_moe_grouped_full_shapes():
         assert err <= TOL["f16"] * scale
 
 
+def test_moe_grouped_all_64_experts():
+    """BASELINE configs[3] with the routing bench.py times: all 64 experts' offsets (Zipf(1.1), top-2, 2048
+    tokens, seed 5) plus the same routing with two experts emptied.  The 64 weight slots cycle through 8
+    distinct matrices (host time); every expert index, offset and stride of the real launch is exercised."""
+    from paper_2308_09723_amd import fq
+    torch = torch_mod()
+    E, D = workloads.MOE["experts"], 8
+    d_model, d_ff = workloads.MOE["d_model"], workloads.MOE["d_ff"]
+    offsets, _ = workloads.zipf_routing(2048, E, 2, 1.1, seed=5)
+    counts = np.diff(offsets)
+    counts2 = counts.copy()
+    counts2[[2, 40]] = 0                                      # a popular and a rare expert without rows
+    offsets2 = np.concatenate([[0], np.cumsum(counts2)]).astype(np.int32)
+    _say(f"moe-64: rows per expert {counts.tolist()}")
+    for (K, N, tag) in ((d_model, d_ff, "fc1"), (d_ff, d_model, "fc2")):
+        cols = _structured_columns(N, seed=18, extra=4)
+        cols_d = torch.from_numpy(cols).cuda()
+        codes_l, scales_l, qs, ss = [], [], [], []
+        for d in range(D):
+            W = workloads.weights_gaussian(K, N, 700 + d)
+            c, s = fq.quantize(torch.from_numpy(W).cuda(), 4, 64)
+            codes_l.append(c)
+            scales_l.append(s.reshape(-1))
+            q_ref, s_ref = oracle.quantize(np.ascontiguousarray(W[:, cols]), 4, 64)
+            assert np.array_equal(fq.unpack(c, K, N, 4).index_select(1, cols_d).cpu().numpy(), q_ref)
+            qs.append(q_ref)
+            ss.append(s_ref)
+        codes = torch.cat([codes_l[e % D] for e in range(E)])
+        scales = torch.cat([scales_l[e % D] for e in range(E)])
+        del codes_l, scales_l
+        for offs in (offsets, offsets2):
+            rows = int(offs[-1])
+            A = workloads.activations(rows, K, "f16", 52)
+            out = torch.full((rows, N), 5.0, dtype=torch.float16, device="cuda")
+            fq.gemm_grouped(to_dev_act(A, "f16"), offs.tolist(), codes, scales, 4, 64, N, out=out)
+            assert bool(torch.isfinite(out.float()).all())
+            C = out.index_select(1, cols_d).cpu().numpy().astype(np.float64)
+            C_ref = oracle.gemm_ref_grouped(A, offs, [qs[e % D] for e in range(E)], [ss[e % D] for e in range(E)])
+            scale = np.max(np.abs(C_ref))
+            err = np.max(np.abs(C - C_ref))
+            _say(f"  moe-64 {tag} rows={rows}: rel err {err / scale:.2e}")
+            assert err <= TOL["f16"] * scale
+        del codes, scales
+
+
 @pytest.mark.parametrize("bits,g,K", [(4, 128, 4096), (4, 64, 3072), (8, 0, 4096)])
 def test_split_tail_round_on_sampled_columns(bits, g, K):
     """QKV-wide products whose output tiles exceed the block slots by a partly filled last round: the plan
@@ -145,7 +259,8 @@ def test_split_tail_round_on_sampled_columns(bits, g, K):
         desc = fq.gemm_describe(M, N, K, bits, g)
         _say(f"  M={M}: {desc}")
         assert "tail=0x" not in desc, desc
-    cols = _sample_columns(N, 48, seed=15)
-    extra = np.arange(N - 1536, N, 97)                       # the last column blocks (the split tiles)
+    # every column block has a compared column (all rows are compared), so every K-split tile is covered
+    cols = _structured_columns(N, seed=15)
+    extra = np.arange(N - 1536, N, 97)                       # denser over the last column blocks
     cols = np.array(sorted(set(cols.tolist()) | set(extra.tolist())), dtype=np.int64)
     _check_layer(W, bits, g, cases, cols, "qkv-tail")

@@ -190,6 +190,29 @@ int fq_gemm_sf(const void* A, int act_dtype, int64_t M, int64_t N, int64_t K, co
                size_t workspace_bytes, void* stream);
 
 /*
+ * fq_gemm_noalloc -- fq_gemm for callers that cannot allocate device memory or hand over a workspace:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  The scratch
+ * fq_gemm takes as `workspace` (split-K partial sums, rewritten bfloat16 activation rows) lives in a
+ * device array that is part of the library's code object: FQ_NOALLOC_SCRATCH_BYTES bytes on every GPU
+ * the library runs on, held until the process ends.  The call allocates and frees nothing and runs the
+ * same kernels as fq_gemm (binary16 scales), so the results are bit-identical to fq_gemm's.
+ *
+ *   arguments  as fq_gemm, without the workspace
+ * Errors: as fq_gemm; FQ_ERR_WORKSPACE when the problem needs more scratch than the array holds
+ *         (fq_gemm_workspace_bytes_for(...) > FQ_NOALLOC_SCRATCH_BYTES: nothing is launched; use fq_gemm).
+ * All calls on one GPU share that GPU's array, which keeps the previous call's contents (no kernel reads
+ * what an earlier kernel of the same call has not written, so nothing needs clearing).  Calls that
+ * overlap on one GPU (two streams, two host threads) RACE on it: order them on one stream.  The first
+ * call on a device looks up the array's address (a host-side query); make one call outside any stream
+ * capture before capturing.
+ */
+#define FQ_NOALLOC_SCRATCH_BYTES (64u << 20)
+int fq_gemm_noalloc(const void* A, int act_dtype, int64_t M, int64_t N, int64_t K, const void* codes,
+                    const void* scales_f16, int bits, int group_size, void* C, void* stream);
+/* FQ_NOALLOC_SCRATCH_BYTES as the built library has it. */
+size_t fq_gemm_noalloc_scratch_bytes(void);
+
+/*
  * fq_gemm_grouped -- the same product for the expert FFNs of a mixture-of-experts
  * layer (section 4.3): rows offsets[e] .. offsets[e+1]-1 of A (tokens sorted by
  * expert) are multiplied by expert e's matrix.  Experts without rows are skipped

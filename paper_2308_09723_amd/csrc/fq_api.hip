@@ -1,6 +1,7 @@
 // C ABI of libfq: argument validation on the host, then dispatch to the launchers.
 // Every check happens before the first HIP call, so invalid calls never touch the GPU.
 #include <hip/hip_runtime.h>
+#include <mutex>
 #include <stdint.h>
 #include <stdio.h>
 
@@ -198,6 +199,68 @@ int fq_gemm_sf(const void* A, int act_dtype, int64_t M, int64_t N, int64_t K, co
     return fq_launch_gemm(A, kind, M, N, K, codes, scales_f16, bits, g, C, workspace,
                           (hipStream_t)stream);
 }
+
+}  // extern "C"
+
+// Scratch of fq_gemm_noalloc: a file-scope device array (every GPU the library runs on holds its own copy,
+// at its own address, until the process ends).  In host code the array's name is only a handle for
+// hipGetSymbolAddress; the address kernels may use is asked for once per device and kept here.
+static __device__ __align__(256) unsigned char scratch[FQ_NOALLOC_SCRATCH_BYTES];
+
+namespace {
+std::mutex g_scratch_mutex;
+void* g_scratch_ptr[64];
+
+// Device address of `scratch` on the current device, or nullptr (with *status set) on failure.
+void* scratch_of_current_device(int* status) {
+    int dev = 0;
+    *status = FQ_OK;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) {
+        *status = FQ_ERR_HIP;
+        return nullptr;
+    }
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) {
+            (void)hipGetLastError();
+            *status = FQ_ERR_HIP;
+            return nullptr;
+        }
+        g_scratch_ptr[dev] = p;
+    }
+    return g_scratch_ptr[dev];
+}
+}  // namespace
+
+extern "C" {
+
+int fq_gemm_noalloc(const void* A, int act_dtype, int64_t M, int64_t N, int64_t K, const void* codes,
+                    const void* scales_f16, int bits, int group_size, void* C, void* stream) {
+    if (M < 0) return FQ_ERR_INVALID_ARG;
+    int kst = FQ_OK;
+    const int kind = act_kind(act_dtype, FQ_SCALE_F16, &kst);
+    if (kst != FQ_OK) return kst;
+    int g = 0;
+    const int st = check_shape(K, N, bits, group_size, &g);
+    if (st != FQ_OK) return st;
+    if (M == 0) return FQ_OK;
+    if (!A || !codes || !scales_f16 || !C) return FQ_ERR_INVALID_ARG;
+    if (M > (int64_t)1 << 24) return FQ_ERR_UNSUPPORTED;
+    const size_t need = fq_gemm_workspace_bytes_for(M, N, K, bits, group_size, act_dtype, FQ_SCALE_F16);
+    if (need > (size_t)FQ_NOALLOC_SCRATCH_BYTES) return FQ_ERR_WORKSPACE;   // beyond the static scratch
+    void* ws = nullptr;
+    if (need > 0) {
+        int sst = FQ_OK;
+        ws = scratch_of_current_device(&sst);
+        if (!ws) return sst;
+    }
+    // Nothing in the scratch has to start at zero: every partial sum and every rewritten activation row a
+    // kernel of this call reads was written by an earlier kernel of the same call.
+    return fq_launch_gemm(A, kind, M, N, K, codes, scales_f16, bits, g, C, ws, (hipStream_t)stream);
+}
+
+size_t fq_gemm_noalloc_scratch_bytes(void) { return (size_t)FQ_NOALLOC_SCRATCH_BYTES; }
 
 int fq_gemm_grouped(const void* A, int act_dtype, const int32_t* offsets_host, int E, int64_t N,
                     int64_t K, const void* codes, const void* scales_f16, int bits, int group_size,

@@ -66,6 +66,8 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "fq_gemm_sf": (i32, [vp, i32, i64, i64, i64, vp, vp, i32, i32, i32, vp, vp, sz, vp]),
         "fq_gemm_grouped_sf": (i32, [vp, i32, ctypes.POINTER(ctypes.c_int32), i32, i64, i64, vp, vp, i32, i32, i32,
                                      vp, vp, sz, vp]),
+        "fq_gemm_noalloc": (i32, [vp, i32, i64, i64, i64, vp, vp, i32, i32, vp, vp]),
+        "fq_gemm_noalloc_scratch_bytes": (sz, []),
         "fq_gemm_describe": (i32, [i64, i64, i64, i32, i32, ctypes.c_char_p, sz]),
         "fq_stream_read_probe": (i32, [vp, sz, vp, vp]),
         "fq_status_string": (ctypes.c_char_p, [i32]),
@@ -85,7 +87,7 @@ EXPORTED = [
     "fq_gemm_grouped", "fq_gemm_describe", "fq_status_string", "fq_version",
     "fq_quant_error_workspace_bytes", "fq_quant_error",
     "fq_quantize_sf", "fq_quant_error_sf", "fq_gemm_sf", "fq_gemm_grouped_sf", "fq_gemm_workspace_bytes_for",
-    "fq_stream_read_probe",
+    "fq_stream_read_probe", "fq_gemm_noalloc", "fq_gemm_noalloc_scratch_bytes",
 ]
 
 
@@ -174,6 +176,15 @@ def gemm_raw(A_ptr, act_dtype, M, N, K, codes_ptr, scales_ptr, bits, group_size,
              stream=0):
     return int(load().fq_gemm(A_ptr, act_dtype, M, N, K, codes_ptr, scales_ptr, bits, group_size, C_ptr,
                               ws_ptr, ws_bytes, stream))
+
+
+def gemm_noalloc_raw(A_ptr, act_dtype, M, N, K, codes_ptr, scales_ptr, bits, group_size, C_ptr, stream=0):
+    return int(load().fq_gemm_noalloc(A_ptr, act_dtype, M, N, K, codes_ptr, scales_ptr, bits, group_size, C_ptr,
+                                      stream))
+
+
+def gemm_noalloc_scratch_bytes():
+    return int(load().fq_gemm_noalloc_scratch_bytes())
 
 
 def gemm_sf_raw(A_ptr, act_dtype, M, N, K, codes_ptr, scales_ptr, scale_format, bits, group_size, C_ptr, ws_ptr,

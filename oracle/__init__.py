@@ -19,3 +19,9 @@ from .fq_oracle import (  # noqa: F401
     quant_error,
     bf16_scale_bits,
 )
+from .fq_oracle_int import (  # noqa: F401
+    quantize_int_scales,
+    dequantize_int_scales,
+    quantize_activations_int8,
+    gemm_ref_int,
+)

@@ -239,6 +239,62 @@ int fq_gemm_grouped_sf(const void* A, int act_dtype, const int32_t* offsets_host
                        int group_size, void* C, void* workspace, size_t workspace_bytes, void* stream);
 
 /*
+ * The integer path -- int8 activations x int4 weights with INTEGER group scales, multiplied on the integer
+ * matrix cores.  Section 5 ("Conclusions and Limitations", last paragraph) names it as future work and gives
+ * no formula; the reading implemented here keeps Appendix A's quantiser and section 4.1's groups:
+ *   weights      s[i, n] = z[i, n] * t[n]: one binary16 step t per column (the smallest with
+ *                16 * 15 * t >= 2 max|w| over the column) and one integer multiplier z in 1..16 per group (the
+ *                smallest with 15 * z * t >= 2 max|w| over the group), one byte each;
+ *                q = clamp(round_half_even(w / (z t)), -7, 7), binary32 quotient.  |q z t - w| <= z t / 2 holds
+ *                exactly, and q * z is an int8 (at most 112 in magnitude).
+ *   activations  Appendix A at 8 bits per row: alpha[m] = the smallest binary32 with 255 alpha >= 2 max|A[m, :]|,
+ *                a = clamp(round_half_even(A / alpha), -127, 127), binary32 quotient.
+ *   product      S[m, n] = sum_k a[m, k] * q[k, n] * z[k / g, n] in exact int32 arithmetic (K <= 131072 keeps
+ *                |S| < 2^31),  C[m, n] = alpha[m] * t[n] * S[m, n] evaluated in binary32, rounded to out_dtype.
+ * Shape limits: N a multiple of 16, K a multiple of 128 and at most 131072, group_size 0 / K or a multiple of 32
+ * that divides K.  The packed codes use the 4-bit layout of fq_quantize (fq_codes_bytes(K, N, 4) bytes;
+ * fq_unpack(..., bits = 4, ...) reads them back).
+ */
+
+/* Size in bytes of the multiplier matrix z[K/g, N] (one byte per group).  0 on invalid arguments. */
+size_t fq_zscale_bytes(int64_t K, int64_t N, int group_size);
+
+/*
+ * fq_quantize_w4a8 -- the weight quantiser of the integer path.
+ *   W_f16      in   [K, N] binary16, row-major, finite
+ *   codes      out  fq_codes_bytes(K, N, 4) bytes (also used as scratch for the groups' abs-max on the way)
+ *   zscale     out  [K/g, N] bytes, values 1..16
+ *   tstep_f16  out  [N] binary16
+ * Errors: FQ_ERR_INVALID_ARG, FQ_ERR_UNSUPPORTED (shape limits above), FQ_ERR_HIP.
+ */
+int fq_quantize_w4a8(const void* W_f16, int64_t K, int64_t N, int group_size, void* codes, uint8_t* zscale,
+                     void* tstep_f16, void* stream);
+
+/*
+ * fq_quantize_act_i8 -- the activation quantiser of the integer path (one scale per row).
+ *   A      in   [M, K] row-major, act_dtype (FQ_F16 or FQ_BF16), finite
+ *   Aq     out  [M, K] int8, row-major
+ *   alpha  out  [M] binary32
+ * M = 0 is a valid no-op.  Errors: FQ_ERR_INVALID_ARG, FQ_ERR_UNSUPPORTED (M or K above 2^24), FQ_ERR_HIP.
+ */
+int fq_quantize_act_i8(const void* A, int act_dtype, int64_t M, int64_t K, int8_t* Aq, float* alpha, void* stream);
+
+/*
+ * fq_gemm_w4a8 -- the product of the integer path.
+ *   Aq, alpha            in   as written by fq_quantize_act_i8
+ *   codes, zscale, tstep in   as written by fq_quantize_w4a8 for the same (K, N, group_size)
+ *   C                    out  [M, N] row-major, out_dtype (FQ_F16 or FQ_BF16)
+ *   workspace                 device scratch, >= fq_gemm_w4a8_workspace_bytes(M, N, K, group_size) bytes (int32 sums
+ *                             of products whose K range is split over several blocks; may be NULL when that is 0)
+ * Asynchronous on `stream`, no allocation, deterministic (integer sums do not depend on their order).
+ * M = 0 is a valid no-op.  Errors: FQ_ERR_INVALID_ARG, FQ_ERR_UNSUPPORTED, FQ_ERR_WORKSPACE, FQ_ERR_HIP.
+ */
+size_t fq_gemm_w4a8_workspace_bytes(int64_t M, int64_t N, int64_t K, int group_size);
+int fq_gemm_w4a8(const int8_t* Aq, const float* alpha, int64_t M, int64_t N, int64_t K, const void* codes,
+                 const uint8_t* zscale, const void* tstep_f16, int group_size, void* C, int out_dtype,
+                 void* workspace, size_t workspace_bytes, void* stream);
+
+/*
  * fq_gemm_describe -- writes a short text description of the kernel configuration fq_gemm
  * would use for this problem (kernel family, tile shape, block shape, split-K factor) into
  * buf (HOST memory, at most buf_bytes including the terminating 0).  For logs and benchmark

@@ -1,0 +1,532 @@
+// The integer path: int8 activations x int4 weights with integer group scales on the integer matrix cores
+// (the paper's closing section names it as future work: "Conclusions and Limitations", last paragraph; the
+// reading is stated in fq.h next to fq_quantize_w4a8).
+//
+//   weights      s[i, n] = z[i, n] * t[n],  z an integer in 1..16 (one byte per group), t binary16 per column;
+//                codes q = int(w / s) as in Appendix A, stored in the packed 4-bit layout of fq_layout.h
+//   activations  Appendix A at 8 bits per row: alpha[m] binary32, a[m, k] in [-127, 127]
+//   product      S = sum_k a * (q * z) in int32 (v_mfma_i32_16x16x64_i8), C = alpha[m] * t[n] * S
+//
+// The weights are brought to the activation's type before the multiply, as section 4.1 describes for the
+// floating-point kernels; here that type is int8 and the conversion is q * z, formed four at a time: the stored
+// nibbles u = q + 8 of a dword are spread over bytes, one packed 16-bit multiply-add gives u * z + (128 - 8 z)
+// in every byte (between 16 and 240: no carries), and flipping the top bit of each byte leaves q * z in two's
+// complement.
+#include <hip/hip_runtime.h>
+#include <hip/hip_fp16.h>
+#include <stdint.h>
+
+#include "fq_gemm_kernels.h"
+#include "fq_internal.h"
+#include "fq_layout.h"
+
+using namespace fqk;
+
+namespace {
+
+constexpr int ZMAX = 16;           // largest group multiplier: 7 * 16 = 112 fits an int8
+constexpr float WLEVELS = 15.0f;   // 2^4 - 1, Appendix A
+constexpr float ALEVELS = 255.0f;  // 2^8 - 1
+constexpr int W8_NT = 3;           // column tiles per wave
+constexpr int W8_WAVES = 8;
+
+__device__ inline float f16_bits_to_float(uint16_t b) { return __half2float(__ushort_as_half(b)); }
+
+// ------------------------------------------------------------------------------------------------------
+// Weight quantiser, three small kernels (offline path):
+//   1. abs-max of every group, as binary16 bit patterns, parked in the not-yet-written code buffer;
+//   2. per column: t = smallest binary16 with 16 * 15 * t >= 2 * (largest group abs-max), then for every
+//      group the smallest z in 1..16 with 15 * z * t >= 2 * (its abs-max)  (all products exact in binary32);
+//   3. codes q = clamp(round_half_even(w / (z t)), -7, 7), IEEE binary32 quotient, packed.
+// ------------------------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void w8_group_absmax_kernel(const uint16_t* __restrict__ W, int64_t N, int g,
+                                                               uint16_t* __restrict__ amax) {
+    // thread (x, y): column x of the block's 64 columns, rows y, y + 4, ... of group blockIdx.y
+    __shared__ uint16_t red[4][64];
+    const int x = threadIdx.x & 63, y = threadIdx.x >> 6;
+    const int64_t n = (int64_t)blockIdx.x * 64 + x;
+    const int64_t grp = blockIdx.y;
+    uint16_t m = 0;
+    if (n < N) {
+        const uint16_t* base = W + grp * g * N + n;
+        for (int r = y; r < g; r += 4) {
+            const uint16_t v = base[(int64_t)r * N] & 0x7fffu;
+            m = v > m ? v : m;
+        }
+    }
+    red[y][x] = m;
+    __syncthreads();
+    if (y == 0 && n < N) {
+        for (int i = 1; i < 4; ++i) m = red[i][x] > m ? red[i][x] : m;
+        amax[grp * N + n] = m;
+    }
+}
+
+__global__ __launch_bounds__(256) void w8_scales_kernel(const uint16_t* __restrict__ amax, int64_t N, int groups,
+                                                         uint8_t* __restrict__ z, uint16_t* __restrict__ tstep) {
+    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (n >= N) return;
+    uint16_t mcol = 0;
+    for (int i = 0; i < groups; ++i) {
+        const uint16_t v = amax[(int64_t)i * N + n];
+        mcol = v > mcol ? v : mcol;
+    }
+    const float L = WLEVELS * (float)ZMAX;                                  // 240
+    const float two_m = 2.0f * f16_bits_to_float(mcol);
+    uint16_t tb = __half_as_ushort(__float2half_rn(__fdiv_rn(two_m, L)));   // nearest, then up if too small
+    if (__fmul_rn(L, f16_bits_to_float(tb)) < two_m) tb += 1;
+    tstep[n] = tb;
+    const float t = f16_bits_to_float(tb);
+    for (int i = 0; i < groups; ++i) {
+        const float two_mi = 2.0f * f16_bits_to_float(amax[(int64_t)i * N + n]);
+        int zi = 1;
+        while (zi < ZMAX && __fmul_rn(WLEVELS * (float)zi, t) < two_mi) ++zi;   // (15 z) * t: exact
+        z[(int64_t)i * N + n] = (uint8_t)zi;
+    }
+}
+
+// one thread per lane record (16 bytes: the 4 x 8 codes of one column in one k-block)
+__global__ __launch_bounds__(256) void w8_encode_kernel(const uint16_t* __restrict__ W, int64_t K, int64_t N,
+                                                         int g, const uint8_t* __restrict__ z,
+                                                         const uint16_t* __restrict__ tstep,
+                                                         uint32_t* __restrict__ codes) {
+    const int64_t rec = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t ntiles = N / FQ_NTILE;
+    if (rec >= (K / 128) * ntiles * 64) return;
+    const int lane = (int)(rec & 63);
+    const int64_t tile = (rec >> 6) % ntiles, kb = (rec >> 6) / ntiles;
+    const int64_t n = tile * FQ_NTILE + (lane & 15);
+    const int j = lane >> 4;
+    const float t = f16_bits_to_float(tstep[n]);
+    uint32_t out[4];
+#pragma unroll
+    for (int d = 0; d < 4; ++d) {
+        const int64_t k0 = kb * 128 + 32 * d + 8 * j;
+        const float s = (float)z[(k0 / g) * N + n] * t;                      // exact
+        uint32_t w = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const float x = f16_bits_to_float(W[(k0 + e) * N + n]);
+            int q = 0;
+            if (s != 0.0f) q = (int)fminf(fmaxf(rintf(__fdiv_rn(x, s)), -7.0f), 7.0f);
+            w |= (uint32_t)(q + 8) << (4 * fq_nibble_slot(e));
+        }
+        out[d] = w;
+    }
+    *reinterpret_cast<uint4*>(codes + rec * 4) = make_uint4(out[0], out[1], out[2], out[3]);
+}
+
+// ------------------------------------------------------------------------------------------------------
+// Activation quantiser: block r handles row r.  alpha = smallest binary32 with 255 alpha >= 2 max|A[r, :]|
+// (nearest quotient, then one step up if the exact sign of 127.5 alpha - max, taken from a fused
+// multiply-add, is negative); a = clamp(round_half_even(A / alpha), -127, 127), IEEE binary32 quotient.
+// ------------------------------------------------------------------------------------------------------
+template <int ACT>
+__device__ inline float act_to_float(uint16_t b) {
+    if constexpr (ACT == FQ_F16) return f16_bits_to_float(b);
+    else return __uint_as_float((uint32_t)b << 16);
+}
+
+template <int ACT>
+__global__ __launch_bounds__(256) void w8_act_quant_kernel(const uint16_t* __restrict__ A, int64_t K,
+                                                            int8_t* __restrict__ Aq, float* __restrict__ alpha) {
+    __shared__ uint32_t red[4];
+    const int64_t r = blockIdx.x;
+    const uint16_t* src = A + r * K;
+    uint32_t m = 0;
+    for (int64_t k = threadIdx.x; k < K; k += 256) {
+        const uint32_t v = src[k] & 0x7fffu;      // magnitudes of one format order like their bit patterns
+        m = v > m ? v : m;
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint32_t t = (uint32_t)__shfl_xor((int)m, o, 64);
+        m = t > m ? t : m;
+    }
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    m = red[0];
+#pragma unroll
+    for (int i = 1; i < 4; ++i) m = red[i] > m ? red[i] : m;
+    // 2 max / 255 = max / 127.5 (the same real number; this form cannot overflow for bfloat16 inputs near 2^128)
+    const float amax = act_to_float<ACT>((uint16_t)m);
+    float al = __fdiv_rn(amax, 0.5f * ALEVELS);
+    if (__builtin_fmaf(0.5f * ALEVELS, al, -amax) < 0.0f) al = __uint_as_float(__float_as_uint(al) + 1u);   // next value up
+    if (threadIdx.x == 0) alpha[r] = al;
+    int8_t* dst = Aq + r * K;
+    for (int64_t k = threadIdx.x; k < K; k += 256) {
+        int q = 0;
+        if (al != 0.0f) q = (int)fminf(fmaxf(rintf(__fdiv_rn(act_to_float<ACT>(src[k]), al)), -127.0f), 127.0f);
+        dst[k] = (int8_t)q;
+    }
+}
+
+// ------------------------------------------------------------------------------------------------------
+// Product.  Same orientation as the floating-point kernels: 16 x 16 tiles of C^T, the weights the first
+// MFMA operand (16 columns n), the activations the second (16 rows m); a lane's packed record holds, after the
+// conversion, its slice of the first operand, so weights never pass through LDS.  One v_mfma_i32_16x16x64_i8
+// contracts 64 rows of K: lane (n or m, j) supplies the 16 values of rows 64 T + 32 h + 8 j + e (h = 0, 1;
+// e = 0..7), i.e. dwords 2 T and 2 T + 1 of its record, in the byte order the nibble extraction leaves:
+// (e0, e4, e1, e5), (e2, e6, e3, e7) per dword.  The activation tile (BM rows x 128 int8) is staged through LDS
+// in that same order, 16 bytes per (row, T, j), the eight units of a row XOR-swizzled with the row so that a
+// fragment read of 16 rows spreads over all banks.
+// Block = 8 waves x 3 column tiles (384 columns), BM = 16 MT rows; k-block = 128 rows; two LDS buffers, one
+// barrier per k-block, the next k-block's weights and activations in flight during the multiply.
+// ZR = multiplier rows a k-block spans (1, 2 or 4: every 128, 64 or 32 rows).
+// With splits > 1 the blocks of a tile add their int32 sums into a zeroed buffer (integer addition: the
+// result does not depend on the order), and a second kernel scales it.
+// ------------------------------------------------------------------------------------------------------
+typedef int v4i __attribute__((ext_vector_type(4)));
+typedef uint16_t u16x2v __attribute__((ext_vector_type(2)));
+
+// four stored nibbles spread over the bytes of x (each 1..15) -> four int8 values (u - 8) * z
+__device__ inline uint32_t w8_scale_bytes(uint32_t x, u16x2v zz, u16x2v cc) {
+    const u16x2v r = bitcast<u16x2v>(x) * zz + cc;          // u z + (128 - 8 z) in every byte, no carries
+    return bitcast<uint32_t>(r) ^ 0x80808080u;
+}
+
+template <int OUT>
+__device__ inline void w8_store4(uint16_t* C, const v4i& s, float scale_m, const float (&tn)[4]) {
+    f32x4 v;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) v[i] = (float)s[i] * (scale_m * tn[i]);
+    *reinterpret_cast<u32x2*>(C) = pack4<OUT>(v);
+}
+
+template <int MT, int ZR, int OUT>
+__global__ __launch_bounds__(W8_WAVES * 64) void fq_gemm_w4a8_kernel(
+    const int8_t* __restrict__ Aq, const float* __restrict__ alpha, const u32x4* __restrict__ codes,
+    const uint8_t* __restrict__ z, const uint16_t* __restrict__ tstep, uint16_t* __restrict__ C,
+    int32_t* __restrict__ partial, int M, int N, int K, int g32, int kb_per_split, int splits, int nblocks_n,
+    int nblocks_m) {
+    constexpr int NT = W8_NT;
+    constexpr int BM = MT * 16;
+    constexpr int NTHR = W8_WAVES * 64;
+    constexpr int UNITS = BM * 8;                       // 16-byte units of an activation tile
+    constexpr int UPT = (UNITS + NTHR - 1) / NTHR;
+    extern __shared__ u32x4 lds[];                       // [2][UNITS]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ntiles = N / FQ_NTILE;
+    const int KB = K / 128;
+    const int ml = lane & 15, j = lane >> 4;
+    const int64_t kb_stride = (int64_t)ntiles * 64;
+
+    const int tiles = nblocks_n * nblocks_m;
+    int bid = blockIdx.x;
+    const int split = bid / tiles;
+    bid -= split * tiles;
+    // the block ids an XCD receives (every eighth) -> one contiguous run of logical tiles
+    const int L = (tiles & 7) == 0 ? (bid & 7) * (tiles >> 3) + (bid >> 3) : bid;
+    int bn, bm_idx;
+    fq_tile_of(L, nblocks_n, nblocks_m, bn, bm_idx);
+    const int kb0 = split * kb_per_split;
+    const int kb1 = min(KB, kb0 + kb_per_split);
+    const int64_t row0 = (int64_t)bm_idx * BM;
+    const int rows = (int)min((int64_t)BM, (int64_t)M - row0);
+
+    const u32x4* wbase[NT];
+    const uint8_t* zbase[NT];
+    bool tvalid[NT];
+    const int tile0 = (bn * W8_WAVES + wave) * NT;
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int tile = tile0 + nt;
+        tvalid[nt] = tile < ntiles;
+        const int tc = tvalid[nt] ? tile : 0;
+        wbase[nt] = codes + fq_rec(tc, 0, ntiles, lane);
+        zbase[nt] = z + (int64_t)tc * FQ_NTILE + ml;
+    }
+
+    // activation staging: unit u = tid + NTHR r -> (row = u / 8, slot = u % 8 = 4 T + jj)
+    int64_t a_off[UPT];
+    int a_dst[UPT];
+#pragma unroll
+    for (int r = 0; r < UPT; ++r) {
+        const int u = tid + NTHR * r;
+        const int row = u >> 3, slot = u & 7;
+        const int rowc = row < rows ? row : rows - 1;          // rows past the end repeat the last one; never stored
+        a_off[r] = (row0 + rowc) * (int64_t)K + 64 * (slot >> 2) + 8 * (slot & 3);
+        a_dst[r] = u < UNITS ? row * 8 + (slot ^ (row & 7)) : -1;
+    }
+    int a_rd[2];
+#pragma unroll
+    for (int T = 0; T < 2; ++T) a_rd[T] = ml * 8 + ((4 * T + j) ^ (ml & 7));
+
+    v4i acc[MT][NT];
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = v4i{0, 0, 0, 0};
+
+    u32x4 wq[NT], wq_n[NT];
+    uint32_t zq[ZR][NT], zq_n[ZR][NT];
+    u32x2 areg[UPT][2];
+    auto load_w = [&](u32x4 (&q)[NT], uint32_t (&zr)[ZR][NT], int kb) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) q[nt] = wbase[nt][(int64_t)kb * kb_stride];
+#pragma unroll
+        for (int r = 0; r < ZR; ++r) {
+            const int64_t zrow = (int64_t)((kb * 4 + r * (4 / ZR)) / g32) * N;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) zr[r][nt] = zbase[nt][zrow];
+        }
+    };
+    auto load_a = [&](int kb) {
+#pragma unroll
+        for (int r = 0; r < UPT; ++r) {
+            const int8_t* p = Aq + a_off[r] + (int64_t)kb * 128;
+            areg[r][0] = *reinterpret_cast<const u32x2*>(p);
+            areg[r][1] = *reinterpret_cast<const u32x2*>(p + 32);
+        }
+    };
+    auto store_a = [&](u32x4* dst) {
+#pragma unroll
+        for (int r = 0; r < UPT; ++r) {
+            if (a_dst[r] < 0) continue;
+            u32x4 v;
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const uint32_t x = areg[r][h][0], y = areg[r][h][1];   // bytes a0..a3, a4..a7
+                v[2 * h] = __builtin_amdgcn_perm(y, x, 0x05010400u);     // (a0, a4, a1, a5)
+                v[2 * h + 1] = __builtin_amdgcn_perm(y, x, 0x07030602u); // (a2, a6, a3, a7)
+            }
+            dst[a_dst[r]] = v;
+        }
+    };
+
+    if (kb0 < kb1) {
+        load_a(kb0);
+        load_w(wq, zq, kb0);
+        store_a(lds);
+    }
+    __syncthreads();
+    int buf = 0;
+    for (int kb = kb0; kb < kb1; ++kb) {
+        const int kbn = kb + 1 < kb1 ? kb + 1 : kb;
+        load_w(wq_n, zq_n, kbn);
+        load_a(kbn);
+        const u32x4* abuf = lds + buf * UNITS;
+#pragma unroll
+        for (int T = 0; T < 2; ++T) {
+            u32x4 wop[NT];
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const int d = 2 * T + h;
+                    const uint32_t zi = zq[d / (4 / ZR)][nt];
+                    const uint16_t zz1 = (uint16_t)zi, cc1 = (uint16_t)((128u - 8u * zi) * 0x0101u);
+                    const u16x2v zz = {zz1, zz1}, cc = {cc1, cc1};
+                    const uint32_t w = wq[nt][d];
+                    wop[nt][2 * h] = w8_scale_bytes(w & 0x0f0f0f0fu, zz, cc);
+                    wop[nt][2 * h + 1] = w8_scale_bytes((w >> 4) & 0x0f0f0f0fu, zz, cc);
+                }
+            }
+#pragma unroll
+            for (int mt = 0; mt < MT; ++mt) {
+                const u32x4 a = abuf[a_rd[T] + mt * 128];
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt)
+                    acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(bitcast<v4i>(wop[nt]), bitcast<v4i>(a),
+                                                                        acc[mt][nt], 0, 0, 0);
+            }
+        }
+        store_a(lds + (buf ^ 1) * UNITS);
+        __syncthreads();
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) wq[nt] = wq_n[nt];
+#pragma unroll
+        for (int r = 0; r < ZR; ++r)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) zq[r][nt] = zq_n[r][nt];
+        buf ^= 1;
+    }
+
+    float tn[NT][4];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt)
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            tn[nt][i] = tvalid[nt] ? f16_bits_to_float(tstep[(int64_t)(tile0 + nt) * FQ_NTILE + j * 4 + i]) : 0.0f;
+#pragma unroll
+    for (int mt = 0; mt < MT; ++mt) {
+        const int row = mt * 16 + ml;
+        if (row >= rows) continue;
+        const float am = alpha[row0 + row];
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+            if (!tvalid[nt]) continue;
+            const int64_t at = (row0 + row) * (int64_t)N + (int64_t)(tile0 + nt) * FQ_NTILE + j * 4;
+            if (splits == 1) {
+                w8_store4<OUT>(C + at, acc[mt][nt], am, tn[nt]);
+            } else {
+#pragma unroll
+                for (int i = 0; i < 4; ++i) atomicAdd(partial + at + i, acc[mt][nt][i]);
+            }
+        }
+    }
+}
+
+__global__ __launch_bounds__(256) void w8_zero_kernel(int32_t* __restrict__ p, int64_t n4) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i < n4) reinterpret_cast<v4i*>(p)[i] = v4i{0, 0, 0, 0};
+}
+
+template <int OUT>
+__global__ __launch_bounds__(256) void w8_finalize_kernel(const int32_t* __restrict__ S, const float* __restrict__ alpha,
+                                                           const uint16_t* __restrict__ tstep, int64_t M, int64_t N,
+                                                           uint16_t* __restrict__ C) {
+    const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
+    if (i >= M * N) return;
+    const int64_t m = i / N, n = i - m * N;                  // N is a multiple of 16: the four share a row
+    const v4i s = *reinterpret_cast<const v4i*>(S + i);
+    float tn[4];
+#pragma unroll
+    for (int k = 0; k < 4; ++k) tn[k] = f16_bits_to_float(tstep[n + k]);
+    w8_store4<OUT>(C + i, s, alpha[m], tn);
+}
+
+struct w8_plan {
+    int mt, splits, kb_per_split, nblocks_n, nblocks_m;
+};
+
+w8_plan w8_plan_of(int64_t M, int64_t N, int64_t K) {
+    w8_plan p;
+    p.mt = M <= 16 ? 1 : (M <= 32 ? 2 : (M <= 64 ? 4 : 8));
+    const int ntiles = (int)(N / FQ_NTILE);
+    p.nblocks_n = (ntiles + W8_WAVES * W8_NT - 1) / (W8_WAVES * W8_NT);
+    p.nblocks_m = (int)((M + p.mt * 16 - 1) / (p.mt * 16));
+    const int64_t tiles = (int64_t)p.nblocks_n * p.nblocks_m;
+    const int KB = (int)(K / 128);
+    int splits = 1;
+    if (tiles < 192) splits = (int)(256 / tiles);      // fill the compute units when there are few tiles
+    if (splits > 8) splits = 8;
+    if (splits > KB) splits = KB;
+    p.kb_per_split = (KB + splits - 1) / splits;
+    p.splits = (KB + p.kb_per_split - 1) / p.kb_per_split;
+    return p;
+}
+
+int w8_check(int64_t K, int64_t N, int group_size, int* g_eff) {
+    if (K <= 0 || N <= 0 || group_size < 0) return FQ_ERR_INVALID_ARG;
+    const int64_t g = group_size == 0 ? K : (int64_t)group_size;
+    if (g > K || K % g != 0) return FQ_ERR_INVALID_ARG;
+    // K <= 131072 keeps every sum inside an int32: K * 127 * 112 < 2^31
+    if (K > 131072 || N > (int64_t)1 << 24 || N % FQ_NTILE != 0 || K % 128 != 0 || g % 32 != 0) return FQ_ERR_UNSUPPORTED;
+    *g_eff = (int)g;
+    return FQ_OK;
+}
+
+template <int MT, int OUT>
+void w8_launch(const w8_plan& p, int g, const int8_t* Aq, const float* alpha, const void* codes, const uint8_t* z,
+               const void* tstep, void* C, int32_t* partial, int64_t M, int64_t N, int64_t K, hipStream_t stream) {
+    const dim3 grid((unsigned)((int64_t)p.nblocks_n * p.nblocks_m * p.splits));
+    const size_t lds = (size_t)2 * MT * 16 * 8 * 16;
+    const int zr = g % 128 == 0 ? 1 : (g == 64 ? 2 : 4);
+#define W8_GO(ZR_)                                                                                              \
+    hipLaunchKernelGGL((fq_gemm_w4a8_kernel<MT, ZR_, OUT>), grid, dim3(W8_WAVES * 64), lds, stream, Aq, alpha,   \
+                       (const u32x4*)codes, z, (const uint16_t*)tstep, (uint16_t*)C, partial, (int)M, (int)N,    \
+                       (int)K, g / 32, p.kb_per_split, p.splits, p.nblocks_n, p.nblocks_m)
+    if (zr == 1) W8_GO(1);
+    else if (zr == 2) W8_GO(2);
+    else W8_GO(4);
+#undef W8_GO
+}
+
+template <int OUT>
+int w8_gemm(const int8_t* Aq, const float* alpha, int64_t M, int64_t N, int64_t K, const void* codes, const uint8_t* z,
+            const void* tstep, int g, void* C, void* workspace, hipStream_t stream) {
+    const w8_plan p = w8_plan_of(M, N, K);
+    int32_t* partial = (int32_t*)workspace;
+    if (p.splits > 1) {
+        const int64_t n4 = M * N / 4;
+        hipLaunchKernelGGL(w8_zero_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, stream, partial, n4);
+    }
+    switch (p.mt) {
+        case 1: w8_launch<1, OUT>(p, g, Aq, alpha, codes, z, tstep, C, partial, M, N, K, stream); break;
+        case 2: w8_launch<2, OUT>(p, g, Aq, alpha, codes, z, tstep, C, partial, M, N, K, stream); break;
+        case 4: w8_launch<4, OUT>(p, g, Aq, alpha, codes, z, tstep, C, partial, M, N, K, stream); break;
+        default: w8_launch<8, OUT>(p, g, Aq, alpha, codes, z, tstep, C, partial, M, N, K, stream); break;
+    }
+    if (p.splits > 1) {
+        const int64_t n4 = M * N / 4;
+        hipLaunchKernelGGL(w8_finalize_kernel<OUT>, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, stream,
+                           (const int32_t*)partial, alpha, (const uint16_t*)tstep, M, N, (uint16_t*)C);
+    }
+    return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t fq_zscale_bytes(int64_t K, int64_t N, int group_size) {
+    int g = 0;
+    if (w8_check(K, N, group_size, &g) != FQ_OK) return 0;
+    return (size_t)((K / g) * N);
+}
+
+int fq_quantize_w4a8(const void* W_f16, int64_t K, int64_t N, int group_size, void* codes, uint8_t* zscale,
+                     void* tstep_f16, void* stream) {
+    if (!W_f16 || !codes || !zscale || !tstep_f16) return FQ_ERR_INVALID_ARG;
+    int g = 0;
+    const int st = w8_check(K, N, group_size, &g);
+    if (st != FQ_OK) return st;
+    hipStream_t s = (hipStream_t)stream;
+    const int groups = (int)(K / g);
+    if (groups > 65535) return FQ_ERR_UNSUPPORTED;
+    uint16_t* amax = (uint16_t*)codes;      // K N / 2 bytes hold the K / g x N abs-max values (g >= 32)
+    hipLaunchKernelGGL(w8_group_absmax_kernel, dim3((unsigned)((N + 63) / 64), (unsigned)groups), dim3(256), 0, s,
+                       (const uint16_t*)W_f16, N, g, amax);
+    hipLaunchKernelGGL(w8_scales_kernel, dim3((unsigned)((N + 255) / 256)), dim3(256), 0, s, (const uint16_t*)amax, N,
+                       groups, zscale, (uint16_t*)tstep_f16);
+    const int64_t recs = (K / 128) * (N / FQ_NTILE) * 64;
+    hipLaunchKernelGGL(w8_encode_kernel, dim3((unsigned)((recs + 255) / 256)), dim3(256), 0, s, (const uint16_t*)W_f16, K,
+                       N, g, (const uint8_t*)zscale, (const uint16_t*)tstep_f16, (uint32_t*)codes);
+    return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;
+}
+
+int fq_quantize_act_i8(const void* A, int act_dtype, int64_t M, int64_t K, int8_t* Aq, float* alpha, void* stream) {
+    if (M < 0 || K <= 0) return FQ_ERR_INVALID_ARG;
+    if (act_dtype != FQ_F16 && act_dtype != FQ_BF16) return FQ_ERR_INVALID_ARG;
+    if (M == 0) return FQ_OK;
+    if (!A || !Aq || !alpha) return FQ_ERR_INVALID_ARG;
+    if (M > (int64_t)1 << 24 || K > (int64_t)1 << 24) return FQ_ERR_UNSUPPORTED;
+    if (act_dtype == FQ_F16)
+        hipLaunchKernelGGL(w8_act_quant_kernel<FQ_F16>, dim3((unsigned)M), dim3(256), 0, (hipStream_t)stream,
+                           (const uint16_t*)A, K, Aq, alpha);
+    else
+        hipLaunchKernelGGL(w8_act_quant_kernel<FQ_BF16>, dim3((unsigned)M), dim3(256), 0, (hipStream_t)stream,
+                           (const uint16_t*)A, K, Aq, alpha);
+    return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;
+}
+
+size_t fq_gemm_w4a8_workspace_bytes(int64_t M, int64_t N, int64_t K, int group_size) {
+    int g = 0;
+    if (M <= 0 || w8_check(K, N, group_size, &g) != FQ_OK) return 0;
+    const w8_plan p = w8_plan_of(M, N, K);
+    return p.splits > 1 ? (size_t)M * (size_t)N * sizeof(int32_t) : 0;
+}
+
+int fq_gemm_w4a8(const int8_t* Aq, const float* alpha, int64_t M, int64_t N, int64_t K, const void* codes,
+                 const uint8_t* zscale, const void* tstep_f16, int group_size, void* C, int out_dtype,
+                 void* workspace, size_t workspace_bytes, void* stream) {
+    if (M < 0) return FQ_ERR_INVALID_ARG;
+    if (out_dtype != FQ_F16 && out_dtype != FQ_BF16) return FQ_ERR_INVALID_ARG;
+    int g = 0;
+    const int st = w8_check(K, N, group_size, &g);
+    if (st != FQ_OK) return st;
+    if (M == 0) return FQ_OK;
+    if (!Aq || !alpha || !codes || !zscale || !tstep_f16 || !C) return FQ_ERR_INVALID_ARG;
+    if (M > (int64_t)1 << 24) return FQ_ERR_UNSUPPORTED;
+    const size_t need = fq_gemm_w4a8_workspace_bytes(M, N, K, group_size);
+    if (need > 0 && (!workspace || workspace_bytes < need)) return FQ_ERR_WORKSPACE;
+    if (out_dtype == FQ_F16)
+        return w8_gemm<FQ_F16>(Aq, alpha, M, N, K, codes, zscale, tstep_f16, g, C, workspace, (hipStream_t)stream);
+    return w8_gemm<FQ_BF16>(Aq, alpha, M, N, K, codes, zscale, tstep_f16, g, C, workspace, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -68,6 +68,11 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
                                      vp, vp, sz, vp]),
         "fq_gemm_noalloc": (i32, [vp, i32, i64, i64, i64, vp, vp, i32, i32, vp, vp]),
         "fq_gemm_noalloc_scratch_bytes": (sz, []),
+        "fq_zscale_bytes": (sz, [i64, i64, i32]),
+        "fq_quantize_w4a8": (i32, [vp, i64, i64, i32, vp, vp, vp, vp]),
+        "fq_quantize_act_i8": (i32, [vp, i32, i64, i64, vp, vp, vp]),
+        "fq_gemm_w4a8_workspace_bytes": (sz, [i64, i64, i64, i32]),
+        "fq_gemm_w4a8": (i32, [vp, vp, i64, i64, i64, vp, vp, vp, i32, vp, i32, vp, sz, vp]),
         "fq_gemm_describe": (i32, [i64, i64, i64, i32, i32, ctypes.c_char_p, sz]),
         "fq_stream_read_probe": (i32, [vp, sz, vp, vp]),
         "fq_status_string": (ctypes.c_char_p, [i32]),
@@ -88,6 +93,7 @@ EXPORTED = [
     "fq_quant_error_workspace_bytes", "fq_quant_error",
     "fq_quantize_sf", "fq_quant_error_sf", "fq_gemm_sf", "fq_gemm_grouped_sf", "fq_gemm_workspace_bytes_for",
     "fq_stream_read_probe", "fq_gemm_noalloc", "fq_gemm_noalloc_scratch_bytes",
+    "fq_zscale_bytes", "fq_quantize_w4a8", "fq_quantize_act_i8", "fq_gemm_w4a8_workspace_bytes", "fq_gemm_w4a8",
 ]
 
 
@@ -209,6 +215,28 @@ def gemm_grouped_sf_raw(A_ptr, act_dtype, offsets, N, K, codes_ptr, scales_ptr, 
                                          group_size, C_ptr, ws_ptr, ws_bytes, stream))
 
 
+def zscale_bytes(K, N, group_size):
+    return int(load().fq_zscale_bytes(K, N, group_size))
+
+
+def quantize_w4a8_raw(W_ptr, K, N, group_size, codes_ptr, z_ptr, t_ptr, stream=0):
+    return int(load().fq_quantize_w4a8(W_ptr, K, N, group_size, codes_ptr, z_ptr, t_ptr, stream))
+
+
+def quantize_act_i8_raw(A_ptr, act_dtype, M, K, Aq_ptr, alpha_ptr, stream=0):
+    return int(load().fq_quantize_act_i8(A_ptr, act_dtype, M, K, Aq_ptr, alpha_ptr, stream))
+
+
+def gemm_w4a8_workspace_bytes(M, N, K, group_size):
+    return int(load().fq_gemm_w4a8_workspace_bytes(M, N, K, group_size))
+
+
+def gemm_w4a8_raw(Aq_ptr, alpha_ptr, M, N, K, codes_ptr, z_ptr, t_ptr, group_size, C_ptr, out_dtype, ws_ptr, ws_bytes,
+                  stream=0):
+    return int(load().fq_gemm_w4a8(Aq_ptr, alpha_ptr, M, N, K, codes_ptr, z_ptr, t_ptr, group_size, C_ptr, out_dtype,
+                                   ws_ptr, ws_bytes, stream))
+
+
 # ------------------------------------------------------------------ torch-tensor conveniences
 def _stream():
     import torch
@@ -323,4 +351,53 @@ def gemm_grouped(A, offsets, codes, scales, bits, group_size, N, out=None):
     _check(gemm_grouped_sf_raw(A.data_ptr(), _act_code(A), offsets, N, K, codes.data_ptr(), scales.data_ptr(),
                                _scale_format_of(scales), bits, group_size, C.data_ptr(), None, 0, _stream()),
            "fq_gemm_grouped_sf")
+    return C
+
+
+def quantize_w4a8(W, group_size):
+    """W: cuda float16 [K, N] -> (codes uint8 [K*N/2], z uint8 [K/g, N], t float16 [N]) of the integer path."""
+    import torch
+
+    assert W.is_cuda and W.dtype == torch.float16 and W.is_contiguous()
+    K, N = W.shape
+    g = K if group_size in (0, K) else group_size
+    zb = zscale_bytes(K, N, group_size)
+    if zb == 0:
+        raise FqError(FQ_ERR_UNSUPPORTED, "fq_quantize_w4a8")
+    codes = torch.empty(codes_bytes(K, N, 4), dtype=torch.uint8, device=W.device)
+    z = torch.empty((K // g, N), dtype=torch.uint8, device=W.device)
+    t = torch.empty((N,), dtype=torch.float16, device=W.device)
+    _check(quantize_w4a8_raw(W.data_ptr(), K, N, group_size, codes.data_ptr(), z.data_ptr(), t.data_ptr(), _stream()),
+           "fq_quantize_w4a8")
+    return codes, z, t
+
+
+def quantize_act_i8(A):
+    """A: cuda [M, K] float16/bfloat16 -> (Aq int8 [M, K], alpha float32 [M])."""
+    import torch
+
+    assert A.is_cuda and A.is_contiguous()
+    M, K = A.shape
+    Aq = torch.empty((M, K), dtype=torch.int8, device=A.device)
+    alpha = torch.empty((M,), dtype=torch.float32, device=A.device)
+    _check(quantize_act_i8_raw(A.data_ptr(), _act_code(A), M, K, Aq.data_ptr(), alpha.data_ptr(), _stream()),
+           "fq_quantize_act_i8")
+    return Aq, alpha
+
+
+def gemm_w4a8(Aq, alpha, codes, z, t, group_size, out_dtype, out=None, workspace=None):
+    """C [M, N] (torch dtype out_dtype: float16 or bfloat16) = alpha * t * (Aq . (q * z))."""
+    import torch
+
+    M, K = Aq.shape
+    N = t.shape[0]
+    C = out if out is not None else torch.empty((M, N), dtype=out_dtype, device=Aq.device)
+    need = gemm_w4a8_workspace_bytes(M, N, K, group_size)
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=Aq.device)
+    ws_ptr = workspace.data_ptr() if workspace is not None else None
+    ws_bytes = workspace.numel() * workspace.element_size() if workspace is not None else 0
+    _check(gemm_w4a8_raw(Aq.data_ptr(), alpha.data_ptr(), M, N, K, codes.data_ptr(), z.data_ptr(), t.data_ptr(),
+                         group_size, C.data_ptr(), FQ_F16 if out_dtype == torch.float16 else FQ_BF16, ws_ptr, ws_bytes,
+                         _stream()), "fq_gemm_w4a8")
     return C

@@ -88,7 +88,7 @@ def main():
                     help="also time the other BASELINE configurations (reported under 'extra'): prefill and mid-M "
                          "products (configs[2]), the grouped expert products (configs[3]) and the heavy-tailed "
                          "stress layer (configs[4])")
-    ap.add_argument("--profile", choices=["decode", "prefill", "prefill-int8", "copy", "moe", "midm", "quantize"], default=None,
+    ap.add_argument("--profile", choices=["decode", "prefill", "prefill-int8", "copy", "moe", "midm", "quantize", "w4a8"], default=None,
                     help="short untimed run of one case for rocprofv3 (no JSON line): 'decode' = the benchmark "
                          "step, 'prefill' = QKV-shaped product at M = 2048 (bf16, then fp16; 'prefill-int8': the same with "
                          "8-bit codes, one group per column), 'copy' = a 1 GiB device copy "
@@ -127,6 +127,9 @@ def main():
         return
     if args.profile == "quantize":
         quantize_section(torch, fq, workloads)
+        return
+    if args.profile == "w4a8":
+        print(json.dumps(w4a8_section(torch, fq, workloads, layers=("qkv",))), file=sys.stderr)
         return
     if args.profile == "midm":
         K, N = workloads.OPT175B_LAYERS["qkv"]
@@ -277,6 +280,7 @@ def main():
         out["extra_quantize"] = quantize_section(torch, fq, workloads)
         out["extra_bf16_scales"] = bf16_scales_section(torch, fq, workloads)
         out["extra_int3"] = int3_section(torch, fq, workloads)
+        out["extra_w4a8"] = w4a8_section(torch, fq, workloads)
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline()
     print(json.dumps(out))
@@ -569,6 +573,61 @@ def int3_section(torch, fq, workloads):
                                    "TFLOPs": round(2.0 * M * N * K / ms / 1e9, 1),
                                    "plan": fq.gemm_describe(M, N, K, 3, GROUP)}
         del codes, scales
+    return res
+
+
+INT8_PEAK_TOPS = 5000.0        # dense int8 MFMA, published
+
+
+def w4a8_section(torch, fq, workloads, layers=("qkv", "out_proj", "fc1", "fc2")):
+    """The integer path (int8 activations x int4 weights with integer group scales, g = 128) on the OPT-175B
+    shapes: the product alone (activations quantised beforehand) at M = 1, 8, 32, 128, 512, 2048, against the HBM
+    peak (weight stream) and the dense int8 MFMA peak; plus the two quantisers' times."""
+    res = {}
+    stream = torch.cuda.current_stream().cuda_stream
+    for name in layers:
+        K, N = workloads.OPT175B_LAYERS[name]
+        W = make_weight(torch, K, N, 100)
+        codes, z, t = fq.quantize_w4a8(W, GROUP)
+
+        def quant():
+            st = fq.quantize_w4a8_raw(W.data_ptr(), K, N, GROUP, codes.data_ptr(), z.data_ptr(), t.data_ptr(), stream)
+            if st != fq.FQ_OK:
+                raise fq.FqError(st, "fq_quantize_w4a8")
+        if name == "qkv":
+            res["quantize_w4a8_qkv_ms"] = round(_timed(torch, quant, settle=0.1, reps=5), 3)
+        del W
+        wbytes = codes.numel() + z.numel() + t.numel() * 2
+        for M in (1, 8, 32, 128, 512, 2048):
+            A = torch.randn((M, K), device="cuda", dtype=torch.float32).to(torch.bfloat16)
+            Aq, alpha = fq.quantize_act_i8(A)
+            C = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)
+            need = fq.gemm_w4a8_workspace_bytes(M, N, K, GROUP)
+            ws = torch.empty(max(need, 16), dtype=torch.uint8, device="cuda")
+            n = 1 if M > 128 else max(1, int(-(-ROTATE_BYTES // wbytes)) + 1)
+            bufs = [(codes, z)] + [(codes.clone(), z.clone()) for _ in range(n - 1)]
+            state = {"i": 0}
+
+            def run():
+                state["i"] = (state["i"] + 1) % n
+                c, zz = bufs[state["i"]]
+                st = fq.gemm_w4a8_raw(Aq.data_ptr(), alpha.data_ptr(), M, N, K, c.data_ptr(), zz.data_ptr(), t.data_ptr(),
+                                      GROUP, C.data_ptr(), fq.FQ_BF16, ws.data_ptr(), ws.numel(), stream)
+                if st != fq.FQ_OK:
+                    raise fq.FqError(st, "fq_gemm_w4a8")
+            ms = _timed(torch, run, settle=0.2, reps=20)
+            del bufs
+            tops = 2.0 * M * N * K / ms / 1e9
+            res[f"{name}_M{M}"] = {"us": round(ms * 1e3, 2), "weight_TBps": round(wbytes / ms / 1e9, 3),
+                                   "frac_of_hbm_peak": round(wbytes / ms / 1e6 / HBM_PEAK_GBS, 4),
+                                   "TOPs": round(tops, 1), "frac_of_int8_peak": round(tops / INT8_PEAK_TOPS, 4)}
+            if name == "qkv" and M == 2048:
+                def aq():
+                    st = fq.quantize_act_i8_raw(A.data_ptr(), fq.FQ_BF16, M, K, Aq.data_ptr(), alpha.data_ptr(), stream)
+                    if st != fq.FQ_OK:
+                        raise fq.FqError(st, "fq_quantize_act_i8")
+                res["quantize_act_M2048_K12288_us"] = round(_timed(torch, aq, settle=0.05, reps=20) * 1e3, 2)
+        del codes, z, t
     return res
 
 

@@ -304,36 +304,54 @@ __global__ __launch_bounds__(W8_WAVES * 64) void fq_gemm_w4a8_kernel(
     }
     __syncthreads();
     int buf = 0;
+    auto convert = [&](u32x4 (&wop)[NT], int T) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) {
+#pragma unroll
+            for (int h = 0; h < 2; ++h) {
+                const int d = 2 * T + h;
+                const uint32_t zi = zq[d / (4 / ZR)][nt];
+                const uint16_t zz1 = (uint16_t)zi, cc1 = (uint16_t)((128u - 8u * zi) * 0x0101u);
+                const u16x2v zz = {zz1, zz1}, cc = {cc1, cc1};
+                const uint32_t w = wq[nt][d];
+                wop[nt][2 * h] = w8_scale_bytes(w & 0x0f0f0f0fu, zz, cc);
+                wop[nt][2 * h + 1] = w8_scale_bytes((w >> 4) & 0x0f0f0f0fu, zz, cc);
+            }
+        }
+    };
     for (int kb = kb0; kb < kb1; ++kb) {
+        // Order of a k-block (kept by the scheduling barriers; left alone, the compiler sinks the global loads
+        // to the end of the iteration and waits for them at the top of the next one):
+        //   global loads of the next k-block | fragment reads of step 0 | conversion of step 0 |
+        //   fragment reads of step 1 | MFMAs of step 0 | conversion of step 1 | MFMAs of step 1 |
+        //   the next activation tile to LDS | barrier
         const int kbn = kb + 1 < kb1 ? kb + 1 : kb;
         load_w(wq_n, zq_n, kbn);
         load_a(kbn);
+        __builtin_amdgcn_sched_barrier(0);
         const u32x4* abuf = lds + buf * UNITS;
+        u32x4 af0[MT], af1[MT], wop0[NT], wop1[NT];
 #pragma unroll
-        for (int T = 0; T < 2; ++T) {
-            u32x4 wop[NT];
+        for (int mt = 0; mt < MT; ++mt) af0[mt] = abuf[a_rd[0] + mt * 128];
+        convert(wop0, 0);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) {
+        for (int mt = 0; mt < MT; ++mt) af1[mt] = abuf[a_rd[1] + mt * 128];
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const int d = 2 * T + h;
-                    const uint32_t zi = zq[d / (4 / ZR)][nt];
-                    const uint16_t zz1 = (uint16_t)zi, cc1 = (uint16_t)((128u - 8u * zi) * 0x0101u);
-                    const u16x2v zz = {zz1, zz1}, cc = {cc1, cc1};
-                    const uint32_t w = wq[nt][d];
-                    wop[nt][2 * h] = w8_scale_bytes(w & 0x0f0f0f0fu, zz, cc);
-                    wop[nt][2 * h + 1] = w8_scale_bytes((w >> 4) & 0x0f0f0f0fu, zz, cc);
-                }
-            }
+        for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
-            for (int mt = 0; mt < MT; ++mt) {
-                const u32x4 a = abuf[a_rd[T] + mt * 128];
+            for (int nt = 0; nt < NT; ++nt)
+                acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(bitcast<v4i>(wop0[nt]), bitcast<v4i>(af0[mt]),
+                                                                    acc[mt][nt], 0, 0, 0);
+        convert(wop1, 1);
 #pragma unroll
-                for (int nt = 0; nt < NT; ++nt)
-                    acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(bitcast<v4i>(wop[nt]), bitcast<v4i>(a),
-                                                                        acc[mt][nt], 0, 0, 0);
-            }
-        }
+        for (int mt = 0; mt < MT; ++mt)
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(bitcast<v4i>(wop1[nt]), bitcast<v4i>(af1[mt]),
+                                                                    acc[mt][nt], 0, 0, 0);
+        __builtin_amdgcn_sched_barrier(0);
         store_a(lds + (buf ^ 1) * UNITS);
         __syncthreads();
 #pragma unroll

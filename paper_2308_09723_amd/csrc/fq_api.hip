@@ -57,7 +57,7 @@ size_t fq_gemm_workspace_bytes_for(int64_t M, int64_t N, int64_t K, int bits, in
     if (M <= 0 || check_shape(K, N, bits, group_size, &g) != FQ_OK) return 0;
     const fq_gemm_plan plan = fq_plan_gemm(M, N, K, bits, g);
     size_t need = fq_partial_bytes(plan, M, N);
-    if (fq_via_f16(act_dtype, scale_format, plan, N)) need += fq_a16_bytes(M, K) + (size_t)M * sizeof(float);
+    if (fq_via_f16(act_dtype, scale_format, plan, N)) need += fq_a16_bytes(M, K) + fq_rowscale_bytes(M);
     return need;
 }
 

@@ -150,6 +150,25 @@ int launch_typed(const void* A, int64_t M, int64_t N, int64_t K, const void* cod
                 launched = true;
             }
         }
+        if constexpr (ACT == FQ_BF16_BS) {
+            if (fq_via_f16(FQ_BF16, FQ_SCALE_BF16, plan, N)) {
+                // the same with bfloat16 scales: their common power of two is found first
+                char* extra = (char*)workspace + fq_partial_bytes(plan, M, N);
+                uint16_t* A16 = (uint16_t*)extra;
+                float* rs = (float*)(extra + fq_a16_bytes(M, K));
+                uint32_t* parts = (uint32_t*)(rs + M + 2);
+                const int64_t count = (K / g) * N;
+                hipLaunchKernelGGL(fq_scale_max_kernel<256>, dim3(FQ_SCALE_PARTS), dim3(256), 0, stream,
+                                   (const uint16_t*)scales, count, parts);
+                hipLaunchKernelGGL(fq_scale_exp_kernel<256>, dim3(1), dim3(256), 0, stream, (const uint32_t*)parts,
+                                   FQ_SCALE_PARTS, rs + M);
+                hipLaunchKernelGGL(fq_rows_to_f16_kernel<256>, dim3((unsigned)M), dim3(256), 0, stream,
+                                   (const uint16_t*)A, (int)K, A16, rs);
+                if (plan.waves == 8) FQ_MMA_LAUNCH_BIG(FQ_BF16S_VIA_F16, A16, rs);
+                else FQ_MMA_LAUNCH_ACT(FQ_BF16S_VIA_F16, A16, rs, 8, 4, 0);
+                launched = true;
+            }
+        }
         if (launched) {
         } else if (plan.waves == 8) {
             if (plan.mt == 2) FQ_MMA_LAUNCH(2, 8, FQ_RING_MT2);

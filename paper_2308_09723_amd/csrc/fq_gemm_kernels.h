@@ -43,6 +43,13 @@ namespace fqk {
 // codes is packed (13 vector instructions per 8 weights against 23 for bf16), which is what the large-M
 // loop is short of.  Used by the 128-row shapes only.
 #define FQ_BF16_VIA_F16 3
+// Fifth value: the same path for bfloat16 SCALES (FQ_BF16_BS computed with fp16 MFMAs).  A bfloat16 scale has
+// eight significant bits but binary32's exponent range, so the scales are first multiplied by 2^-E, E the
+// exponent of the largest scale of the matrix (found by fq_scale_maxexp_kernel): they then lie in (0, 2) and
+// convert to binary16 exactly unless they are more than 2^14 times smaller than the largest one (those lose
+// low bits or vanish: their weights are below 2^-14 of the matrix's widest group).  q * s * 2^-E is rounded
+// once to binary16 (at most 4 + 8 significant bits: usually exact), and the epilogue multiplies by 2^E.
+#define FQ_BF16S_VIA_F16 4
 
 typedef _Float16 f16x2 __attribute__((ext_vector_type(2)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
@@ -94,7 +101,7 @@ __device__ inline u32x4 load_rec(P p) {
 
 template <int ACT>
 __device__ inline f32x4 mfma16x16x32(const u32x4& w, const u32x4& a, const f32x4& c) {
-    if constexpr (ACT == FQ_F16 || ACT == FQ_BF16_VIA_F16) {
+    if constexpr (ACT == FQ_F16 || ACT == FQ_BF16_VIA_F16 || ACT == FQ_BF16S_VIA_F16) {
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(bitcast<f16x8>(w), bitcast<f16x8>(a), c, 0, 0, 0);
     } else {
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(bitcast<bf16x8>(w), bitcast<bf16x8>(a), c, 0, 0, 0);
@@ -233,6 +240,8 @@ template <int BITS>
 struct Dequant<FQ_BF16_BS, BITS> : Dequant<FQ_BF16, BITS> {};
 template <int BITS>
 struct Dequant<FQ_BF16_VIA_F16, BITS> : Dequant<FQ_F16, BITS> {};
+template <int BITS>
+struct Dequant<FQ_BF16S_VIA_F16, BITS> : Dequant<FQ_F16, BITS> {};
 
 template <int ACT>
 __device__ inline u32x4 ones_operand() {
@@ -701,12 +710,18 @@ template <int BITS>
 struct DequantScaled<FQ_BF16_BS, BITS> : DequantScaled<FQ_BF16, BITS> {};
 template <int BITS>
 struct DequantScaled<FQ_BF16_VIA_F16, BITS> : DequantScaled<FQ_F16, BITS> {};
+template <int BITS>
+struct DequantScaled<FQ_BF16S_VIA_F16, BITS> : DequantScaled<FQ_F16, BITS> {};
 
-// stored scale (16 bits) -> the form DequantScaled wants
+// stored scale (16 bits) -> the form DequantScaled wants (sshift: 2^-E for FQ_BF16S_VIA_F16, unused otherwise)
 template <int ACT>
-__device__ inline uint32_t scale_operand(uint16_t h) {
+__device__ inline uint32_t scale_operand(uint16_t h, float sshift) {
     if constexpr (ACT == FQ_F16 || ACT == FQ_BF16_VIA_F16) {
         return (uint32_t)h | ((uint32_t)h << 16);
+    } else if constexpr (ACT == FQ_BF16S_VIA_F16) {
+        const _Float16 s = (_Float16)(bitcast<float>((uint32_t)h << 16) * sshift);
+        const uint32_t b = (uint32_t)bitcast<uint16_t>(s);
+        return b | (b << 16);
     } else if constexpr (ACT == FQ_BF16_BS) {
         return (uint32_t)h << 16;
     } else {
@@ -800,6 +815,49 @@ __global__ __launch_bounds__(THREADS) void fq_rows_to_f16_kernel(const uint16_t*
         }
         dst[u] = o;
     }
+}
+
+// Largest scale of a bfloat16 scale matrix (FQ_BF16S_VIA_F16), in two steps without atomics: every block
+// writes the largest bit pattern it saw, then one block folds those and writes 2^-E and 2^E (E = exponent of
+// the largest scale, kept within +-120; 0 for an all-zero matrix) to out2[0], out2[1].
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void fq_scale_max_kernel(const uint16_t* __restrict__ scales, int64_t count,
+                                                               uint32_t* __restrict__ part) {
+    static_assert(THREADS == 256, "four waves are reduced below");
+    __shared__ uint32_t red[4];
+    uint32_t m = 0;
+    const int64_t units = count / 8;                               // the scale matrix is a multiple of 16 wide
+    for (int64_t u = (int64_t)blockIdx.x * 256 + threadIdx.x; u < units; u += (int64_t)gridDim.x * 256) {
+        const u32x4 v = reinterpret_cast<const u32x4*>(scales)[u];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t a0 = v[i] & 0x7fffu, a1 = (v[i] >> 16) & 0x7fffu;
+            m = a0 > m ? a0 : m;
+            m = a1 > m ? a1 : m;
+        }
+    }
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const uint32_t t = (uint32_t)__shfl_xor((int)m, o, 64);
+        m = t > m ? t : m;
+    }
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = m;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        for (int i = 1; i < 4; ++i) m = red[i] > m ? red[i] : m;
+        part[blockIdx.x] = m;
+    }
+}
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void fq_scale_exp_kernel(const uint32_t* __restrict__ part, int nparts,
+                                                               float* __restrict__ out2) {
+    if (threadIdx.x != 0) return;
+    uint32_t m = 0;
+    for (int i = 0; i < nparts; ++i) m = part[i] > m ? part[i] : m;
+    int e = m == 0 ? 0 : (int)(m >> 7) - 127;
+    e = e < -120 ? -120 : (e > 120 ? 120 : e);
+    out2[0] = ldexpf(1.0f, -e);
+    out2[1] = ldexpf(1.0f, e);
 }
 
 // s_waitcnt vmcnt(N) only (the other counters left alone); gfx9 encoding: vmcnt in bits 3:0 and 15:14
@@ -938,6 +996,12 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
 
     const uint32_t magic = Dequant<ACT, BITS>::init();
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
+    // FQ_BF16S_VIA_F16: the two floats behind the M row scales are 2^-E and 2^E (E: exponent of the largest scale)
+    float sshift = 1.0f, sback = 1.0f;
+    if constexpr (ACT == FQ_BF16S_VIA_F16) {
+        sshift = rowscale[M];
+        sback = rowscale[M + 1];
+    }
     constexpr int NQ = KREC * NT;                // lane records of a k-block: [record][column tile]
     u32x4 wq[NQ], wq_n[NQ], areg[UPT];
     // Scale registers: one per (scale row, column tile), or, with four scale rows per k-block,
@@ -1036,7 +1100,7 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
                 uint32_t h = s[srow / SPK][nt];
                 asm volatile("" : "+v"(h));
                 if (SPK == 2 && (srow & 1)) h >>= 16;
-                s2c[nt] = scale_operand<ACT>((uint16_t)h);
+                s2c[nt] = scale_operand<ACT>((uint16_t)h, sshift);
             }
             const uint32_t s2 = s2c[nt];
             if (ts == 0) return DequantScaled<ACT, BITS>::template run<0>(rec, magic, s2);
@@ -1288,9 +1352,9 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
     for (int mt = 0; mt < MT; ++mt) {
         const int row = mt * 16 + ml;
         if (row >= rows) continue;
-        if constexpr (ACT == FQ_BF16_VIA_F16) {
-            // back from the row's normalised scale (a power of two: exact)
-            const float rs = rowscale[row0 + row];
+        if constexpr (ACT == FQ_BF16_VIA_F16 || ACT == FQ_BF16S_VIA_F16) {
+            // back from the row's normalised scale (and the scales' common one): powers of two, exact
+            const float rs = rowscale[row0 + row] * sback;
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) acc[mt][nt] *= rs;
         }

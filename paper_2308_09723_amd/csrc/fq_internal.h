@@ -43,16 +43,20 @@ fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g);
 inline int fq_mma_kblk(int bits, int mt, int waves, int64_t K, int g) {
     return (bits == 8 && mt == 8 && waves == 8 && K % 128 == 0 && g % 128 == 0) ? 128 : (bits == 8 ? 64 : 128);
 }
-// Workspace layout of fq_gemm: [split-K partial tiles][bf16 activations rewritten as binary16][their row scales]
+// Workspace layout of fq_gemm: [split-K partial tiles][bf16 activations rewritten as binary16][their M row scales,
+// then 2^-E and 2^E of the scale matrix (bfloat16 scales), then FQ_SCALE_PARTS words of the search for E]
 inline size_t fq_partial_bytes(const fq_gemm_plan& p, int64_t M, int64_t N) {
     const int parts = p.splits > 1 ? p.splits : (p.tail_tiles > 0 ? p.tail_splits : 0);
     return (size_t)parts * (size_t)M * (size_t)N * sizeof(float);
 }
 inline size_t fq_a16_bytes(int64_t M, int64_t K) { return (((size_t)M * (size_t)K * 2) + 255) / 256 * 256; }
-// bf16 activations (with binary16 scales) take the fp16 matrix path for the 128-row shapes of wide
+#define FQ_SCALE_PARTS 256
+inline size_t fq_rowscale_bytes(int64_t M) { return ((size_t)M + 2 + FQ_SCALE_PARTS) * sizeof(float); }
+// bf16 activations (binary16 or bfloat16 scales) take the fp16 matrix path for the 128-row shapes of wide
 // matrices: the rewrite of the rows costs 4 M K bytes of traffic against 2 M N K flops
 inline bool fq_via_f16(int act_dtype, int scale_format, const fq_gemm_plan& p, int64_t N) {
-    return act_dtype == FQ_BF16 && scale_format == FQ_SCALE_F16 && p.kind == 1 && p.mt == 8 && N >= 8192;
+    (void)scale_format;
+    return act_dtype == FQ_BF16 && p.kind == 1 && p.mt == 8 && N >= 8192;
 }
 // act: FQ_F16, FQ_BF16, or 2 = bf16 activations with bf16 scales
 int fq_launch_gemm(const void* A, int act, int64_t M, int64_t N, int64_t K, const void* codes,

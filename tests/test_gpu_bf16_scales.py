@@ -102,6 +102,42 @@ def test_gemm_tiled_bf16_scales(bits, g, M):
     _gemm_case(M, 768, 304, bits, g, seed=6000 + M + bits + g)
 
 
+@pytest.mark.parametrize("bits,g,M", [(4, 128, 300), (4, 64, 130), (4, 32, 260), (8, 0, 300), (8, 64, 140), (3, 128, 300)])
+def test_gemm_wide_matrix_bf16_scales_on_the_fp16_matrix_path(bits, g, M):
+    """128-row blocks of a wide matrix (N >= 8192): bfloat16 scales are brought to binary16 through a common
+    power of two and the product runs on the fp16 matrix path (the plan's description names the block shape)."""
+    fq = _fq()
+    K, N = 512, 8192
+    desc = fq.gemm_describe(M, N, K, bits, g)
+    _say(f"gemm bf16 scales wide int{bits} g={g} M={M}: {desc}")
+    _gemm_case(M, K, N, bits, g, seed=6200 + M + bits + g)
+
+
+def test_gemm_wide_matrix_bf16_scales_spread_over_many_binades():
+    """Columns scaled by powers of two from 2^-12 to 2^3 (scales spread over 15 binades inside one matrix), a
+    zero column and a matrix that is tiny as a whole (every scale near 2^-22): the common power of two follows
+    the largest scale, and what falls more than 2^14 below it is far below the tolerance."""
+    fq = _fq()
+    torch = torch_mod()
+    K, N, M, g = 512, 8192, 300, 128
+    W = workloads.weights_gaussian(K, N, 6301, outlier_prob=1e-3).astype(np.float32)
+    W *= (2.0 ** ((np.arange(N) % 16) - 12)).astype(np.float32)[None, :]
+    W[:, 5] = 0
+    W = W.astype(np.float16)
+    A = workloads.activations(M, K, "bf16", 6302)
+    for Wm in (W, (workloads.weights_gaussian(K, N, 6303).astype(np.float32) * 2.0 ** -14).astype(np.float16)):
+        codes, scales, q_ref, s_ref = _quantize_parity(Wm, 4, g)
+        C_ref = oracle.gemm_ref(A, q_ref, s_ref)
+        C = from_dev_act(fq.gemm(to_dev_act(A, "bf16"), codes, scales, 4, g), "bf16")
+        assert np.max(np.abs(C_ref)) > 0
+        assert_gemm_close(C, C_ref, "bf16", "bf16 scales over many binades")
+        # column by column as well where the column is not negligible: each column's own scale of error
+        col_scale = np.max(np.abs(C_ref), axis=0)
+        big = col_scale >= 2.0 ** -10 * col_scale.max()
+        err = np.max(np.abs(C - C_ref), axis=0)
+        assert np.all(err[big] <= 1.6e-2 * col_scale[big])
+
+
 def test_gemm_split_k_bf16_scales():
     """A shape whose plan splits K (few column blocks, many k-blocks)."""
     _say("gemm bf16 scales split-K")

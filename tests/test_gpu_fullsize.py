@@ -56,19 +56,21 @@ def _structured_columns(N, seed, block=384, tile=16, extra=16):
     return np.array(sorted(cols), dtype=np.int64)
 
 
-def _check_layer(W, bits, g, cases, cols, tag):
-    """cases: list of (M, dtype, seed).  Quantises W on the GPU, checks sampled columns against the oracle."""
+def _check_layer(W, bits, g, cases, cols, tag, sfmt="f16"):
+    """cases: list of (M, dtype, seed).  Quantises W on the GPU, checks sampled columns against the oracle.
+    sfmt: storage format of the scales ("f16", or "bf16" with bf16 activations)."""
     from paper_2308_09723_amd import fq
     torch = torch_mod()
     K, N = W.shape
     Wd = torch.from_numpy(W).cuda()
-    codes, scales = fq.quantize(Wd, bits, g)
+    codes, scales = fq.quantize(Wd, bits, g, fq.FQ_SCALE_BF16 if sfmt == "bf16" else fq.FQ_SCALE_F16)
     del Wd
     cols_d = torch.from_numpy(cols).cuda()
     q_gpu = fq.unpack(codes, K, N, bits).index_select(1, cols_d).cpu().numpy()
     s_gpu = scales.index_select(1, cols_d).view(torch.int16).cpu().numpy().view(np.uint16)
-    q_ref, s_ref = oracle.quantize(np.ascontiguousarray(W[:, cols]), bits, g)
-    assert np.array_equal(s_gpu, s_ref.view(np.uint16)), f"{tag}: scales differ on sampled columns"
+    q_ref, s_ref = oracle.quantize(np.ascontiguousarray(W[:, cols]), bits, g, sfmt)
+    s_ref_bits = oracle.bf16_scale_bits(s_ref) if sfmt == "bf16" else s_ref.view(np.uint16)
+    assert np.array_equal(s_gpu, s_ref_bits), f"{tag}: scales differ on sampled columns"
     assert np.array_equal(q_gpu, q_ref), f"{tag}: codes differ on sampled columns"
     for M, dtype, seed in cases:
         A = workloads.activations(M, K, dtype, seed)
@@ -127,6 +129,8 @@ def test_opt175b_layers_full_size_structured_sample(layer):
     _check_layer(W, 4, 128, cases, cols, layer)
     if layer == "qkv":
         _check_layer(W, 8, 0, [(2048, "bf16", 79), (2048, "f16", 80)], cols, layer)
+        # bfloat16 scales (the scales of the activation's type): small-M, 32-row and 128-row kernels
+        _check_layer(W, 4, 128, [(8, "bf16", 83), (32, "bf16", 84), (2048, "bf16", 85)], cols, layer + "-bf16scales", sfmt="bf16")
 
 
 def test_out_proj_decode_every_column():

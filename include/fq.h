@@ -286,7 +286,7 @@ int fq_quantize_act_i8(const void* A, int act_dtype, int64_t M, int64_t K, int8_
  *   C                    out  [M, N] row-major, out_dtype (FQ_F16 or FQ_BF16)
  *   workspace                 device scratch, >= fq_gemm_w4a8_workspace_bytes(M, N, K, group_size) bytes (int32 sums
  *                             of products whose K range is split over several blocks; may be NULL when that is 0)
- * Asynchronous on `stream`, no allocation, deterministic (integer sums do not depend on their order).
+ * Asynchronous on `stream`, no allocation, deterministic.
  * M = 0 is a valid no-op.  Errors: FQ_ERR_INVALID_ARG, FQ_ERR_UNSUPPORTED, FQ_ERR_WORKSPACE, FQ_ERR_HIP.
  */
 size_t fq_gemm_w4a8_workspace_bytes(int64_t M, int64_t N, int64_t K, int group_size);

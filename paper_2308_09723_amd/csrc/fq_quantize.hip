@@ -440,52 +440,87 @@ __global__ void fq_zero_ints_kernel(int* p, int n) {
 // order (thread strip -> tree over the block -> one block over the per-block partials), so the
 // result is deterministic.  part[0 .. nblk) holds the sums, part[nblk .. 2 nblk) the maxima.
 // ---------------------------------------------------------------------------------
-#define FQ_QE_ROWS 64
+// A block takes a panel of 128 rows x 128 columns: the weights are staged in LDS with coalesced 16-byte loads,
+// and every thread walks whole lane records of the packed codes (16 or 12 bytes, read in layout order: a wave
+// reads one contiguous KiB) against the staged weights.  (Looking every weight's code up by its position
+// instead reads the packed buffer four bytes at a time and computes a record address per weight.)
+#define FQ_QE_PANEL 128
+#define FQ_QE_PITCH 130   // binary16 elements per LDS row: rows 8 apart fall 8 banks apart
 template <int BITS>
 __global__ __launch_bounds__(256) void fq_quant_error_kernel(const uint16_t* __restrict__ W,
                                                              const uint32_t* __restrict__ codes,
                                                              const uint16_t* __restrict__ scales, int64_t K,
                                                              int64_t N, int g, int sfmt,
                                                              double* __restrict__ part, int64_t nblk) {
+    __shared__ uint32_t wp[FQ_QE_PANEL * FQ_QE_PITCH / 2];
     __shared__ double sh_s[256];
     __shared__ double sh_m[256];
-    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int64_t k0 = (int64_t)blockIdx.y * FQ_QE_ROWS;
+    constexpr int KBLK = fq_kblk(BITS);
+    constexpr int STEPS = KBLK / FQ_KSTEP;
+    constexpr int RW = fq_rec_bytes(BITS) / 4;                 // dwords per lane record
+    constexpr int RECS = (FQ_QE_PANEL / KBLK) * (FQ_QE_PANEL / FQ_NTILE) * 64;
+    const int tid = threadIdx.x;
+    const int64_t panels_n = (N + FQ_QE_PANEL - 1) / FQ_QE_PANEL;
+    const int64_t panels = panels_n * ((K + FQ_QE_PANEL - 1) / FQ_QE_PANEL);
     double sse = 0.0, mx = 0.0;
-    if (n < N) {
-        for (int64_t k = k0; k < k0 + FQ_QE_ROWS && k < K; ++k) {
-            const fq_pos p = fq_locate(k, n, N, BITS);
-            int q;
-            if (BITS == 4) {
-                const uint32_t w = codes[p.rec * 4 + p.t];
-                q = (int)((w >> (4 * fq_nibble_slot(p.e))) & 0xfu) - 8;
-            } else if (BITS == 3) {
-                q = (int)fq_get3(codes + p.rec * 3, p.t, p.e) - 4;
-            } else {
-                const uint32_t w = codes[p.rec * 4 + 2 * p.t + (p.e >> 2)];
-                q = (int)((w >> (8 * (p.e & 3))) & 0xffu) - 128;
-            }
-            const double wv = (double)half_bits_to_float(W[k * N + n]);
-            const double sv = (double)scale_bits_to_float(scales[(k / g) * N + n], sfmt);
-            const double e = wv - (double)q * sv;
-            sse += e * e;
-            mx = fmax(mx, fabs(e));
+    // a block walks panels blockIdx.x, blockIdx.x + gridDim.x, ... (one partial result per block)
+    for (int64_t pnl = blockIdx.x; pnl < panels; pnl += gridDim.x) {
+    const int64_t n0 = (pnl % panels_n) * FQ_QE_PANEL;
+    const int64_t k0 = (pnl / panels_n) * FQ_QE_PANEL;
+    __syncthreads();                                           // the previous panel has been read
+    for (int u = tid; u < FQ_QE_PANEL * 16; u += 256) {
+        const int row = u >> 4, cu = u & 15;
+        const int64_t k = k0 + row, n = n0 + cu * 8;
+        if (k < K && n < N) {                                  // N is a multiple of 16: whole units
+            const uint4 v = *reinterpret_cast<const uint4*>(W + k * N + n);
+            uint32_t* dst = wp + row * (FQ_QE_PITCH / 2) + cu * 4;
+            dst[0] = v.x; dst[1] = v.y; dst[2] = v.z; dst[3] = v.w;
         }
     }
-    sh_s[threadIdx.x] = sse;
-    sh_m[threadIdx.x] = mx;
+    __syncthreads();
+    const uint16_t* wp16 = reinterpret_cast<const uint16_t*>(wp);
+    for (int r = tid; r < RECS; r += 256) {
+        const int lane = r & 63, tile_l = (r >> 6) & 7, kbl = r >> 9;
+        const int col = tile_l * FQ_NTILE + (lane & 15);
+        const int64_t n = n0 + col;
+        const int64_t kb = k0 / KBLK + kbl;
+        if (n >= N || kb * KBLK >= K) continue;
+        const uint32_t* rec = codes + fq_rec(n / FQ_NTILE, kb, N / FQ_NTILE, lane) * RW;
+        uint32_t d[4] = {0u, 0u, 0u, 0u};
+#pragma unroll
+        for (int i = 0; i < RW; ++i) d[i] = rec[i];
+        const int j = lane >> 4;
+#pragma unroll
+        for (int t = 0; t < STEPS; ++t) {
+            const int krel = kbl * KBLK + FQ_KSTEP * t + 8 * j;
+            const double sv = (double)scale_bits_to_float(scales[((k0 + krel) / g) * N + n], sfmt);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                int q;
+                if (BITS == 4) q = (int)((d[t] >> (4 * fq_nibble_slot(e))) & 0xfu) - 8;
+                else if (BITS == 3) q = (int)fq_get3(d, t, e) - 4;
+                else q = (int)((d[2 * t + (e >> 2)] >> (8 * (e & 3))) & 0xffu) - 128;
+                const double wv = (double)half_bits_to_float(wp16[(krel + e) * FQ_QE_PITCH + col]);
+                const double err = wv - (double)q * sv;
+                sse += err * err;
+                mx = fmax(mx, fabs(err));
+            }
+        }
+    }
+    }
+    sh_s[tid] = sse;
+    sh_m[tid] = mx;
     __syncthreads();
     for (int w = 128; w > 0; w >>= 1) {
-        if ((int)threadIdx.x < w) {
-            sh_s[threadIdx.x] += sh_s[threadIdx.x + w];
-            sh_m[threadIdx.x] = fmax(sh_m[threadIdx.x], sh_m[threadIdx.x + w]);
+        if (tid < w) {
+            sh_s[tid] += sh_s[tid + w];
+            sh_m[tid] = fmax(sh_m[tid], sh_m[tid + w]);
         }
         __syncthreads();
     }
-    if (threadIdx.x == 0) {
-        const int64_t b = (int64_t)blockIdx.y * gridDim.x + blockIdx.x;
-        part[b] = sh_s[0];
-        part[nblk + b] = sh_m[0];
+    if (tid == 0) {
+        part[blockIdx.x] = sh_s[0];
+        part[nblk + blockIdx.x] = sh_m[0];
     }
 }
 
@@ -653,7 +688,8 @@ int fq_launch_choose_group(const void* W, int64_t K, int64_t N, int g_top, int l
 }
 
 int64_t fq_quant_error_blocks(int64_t K, int64_t N) {
-    return ((N + 255) / 256) * ((K + FQ_QE_ROWS - 1) / FQ_QE_ROWS);
+    const int64_t panels = ((N + FQ_QE_PANEL - 1) / FQ_QE_PANEL) * ((K + FQ_QE_PANEL - 1) / FQ_QE_PANEL);
+    return panels < 2048 ? panels : 2048;
 }
 
 int fq_launch_quant_error(const void* W, int64_t K, int64_t N, int bits, int g, int sfmt, const void* codes,
@@ -662,7 +698,7 @@ int fq_launch_quant_error(const void* W, int64_t K, int64_t N, int bits, int g, 
     double* out = (double*)workspace;
     double* part = out + 2;
     const int64_t nblk = fq_quant_error_blocks(K, N);
-    dim3 grid((unsigned)((N + 255) / 256), (unsigned)((K + FQ_QE_ROWS - 1) / FQ_QE_ROWS));
+    dim3 grid((unsigned)nblk);
     if (bits == 3)
         hipLaunchKernelGGL(fq_quant_error_kernel<3>, grid, dim3(256), 0, stream, (const uint16_t*)W,
                            (const uint32_t*)codes, (const uint16_t*)scales, K, N, g, sfmt, part, nblk);

@@ -173,8 +173,8 @@ __global__ __launch_bounds__(256) void w8_act_quant_kernel(const uint16_t* __res
 // Block = 8 waves x 3 column tiles (384 columns), BM = 16 MT rows; k-block = 128 rows; two LDS buffers, one
 // barrier per k-block, the next k-block's weights and activations in flight during the multiply.
 // ZR = multiplier rows a k-block spans (1, 2 or 4: every 128, 64 or 32 rows).
-// With splits > 1 the blocks of a tile add their int32 sums into a zeroed buffer (integer addition: the
-// result does not depend on the order), and a second kernel scales it.
+// With splits > 1 every block writes its int32 sums to its split's slab of a partial buffer and a second
+// kernel adds the slabs (integers: exact whatever the order) and scales the sum.
 // ------------------------------------------------------------------------------------------------------
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef uint16_t u16x2v __attribute__((ext_vector_type(2)));
@@ -381,26 +381,22 @@ __global__ __launch_bounds__(W8_WAVES * 64) void fq_gemm_w4a8_kernel(
             if (splits == 1) {
                 w8_store4<OUT>(C + at, acc[mt][nt], am, tn[nt]);
             } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i) atomicAdd(partial + at + i, acc[mt][nt][i]);
+                *reinterpret_cast<v4i*>(partial + (int64_t)split * M * N + at) = acc[mt][nt];
             }
         }
     }
 }
 
-__global__ __launch_bounds__(256) void w8_zero_kernel(int32_t* __restrict__ p, int64_t n4) {
-    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i < n4) reinterpret_cast<v4i*>(p)[i] = v4i{0, 0, 0, 0};
-}
-
 template <int OUT>
-__global__ __launch_bounds__(256) void w8_finalize_kernel(const int32_t* __restrict__ S, const float* __restrict__ alpha,
+__global__ __launch_bounds__(256) void w8_finalize_kernel(const int32_t* __restrict__ S, int splits,
+                                                           const float* __restrict__ alpha,
                                                            const uint16_t* __restrict__ tstep, int64_t M, int64_t N,
                                                            uint16_t* __restrict__ C) {
     const int64_t i = ((int64_t)blockIdx.x * 256 + threadIdx.x) * 4;
     if (i >= M * N) return;
     const int64_t m = i / N, n = i - m * N;                  // N is a multiple of 16: the four share a row
-    const v4i s = *reinterpret_cast<const v4i*>(S + i);
+    v4i s = *reinterpret_cast<const v4i*>(S + i);
+    for (int k = 1; k < splits; ++k) s += *reinterpret_cast<const v4i*>(S + (int64_t)k * M * N + i);
     float tn[4];
 #pragma unroll
     for (int k = 0; k < 4; ++k) tn[k] = f16_bits_to_float(tstep[n + k]);
@@ -459,10 +455,6 @@ int w8_gemm(const int8_t* Aq, const float* alpha, int64_t M, int64_t N, int64_t 
             const void* tstep, int g, void* C, void* workspace, hipStream_t stream) {
     const w8_plan p = w8_plan_of(M, N, K);
     int32_t* partial = (int32_t*)workspace;
-    if (p.splits > 1) {
-        const int64_t n4 = M * N / 4;
-        hipLaunchKernelGGL(w8_zero_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, stream, partial, n4);
-    }
     switch (p.mt) {
         case 1: w8_launch<1, OUT>(p, g, Aq, alpha, codes, z, tstep, C, partial, M, N, K, stream); break;
         case 2: w8_launch<2, OUT>(p, g, Aq, alpha, codes, z, tstep, C, partial, M, N, K, stream); break;
@@ -472,7 +464,7 @@ int w8_gemm(const int8_t* Aq, const float* alpha, int64_t M, int64_t N, int64_t 
     if (p.splits > 1) {
         const int64_t n4 = M * N / 4;
         hipLaunchKernelGGL(w8_finalize_kernel<OUT>, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, stream,
-                           (const int32_t*)partial, alpha, (const uint16_t*)tstep, M, N, (uint16_t*)C);
+                           (const int32_t*)partial, p.splits, alpha, (const uint16_t*)tstep, M, N, (uint16_t*)C);
     }
     return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;
 }
@@ -526,7 +518,7 @@ size_t fq_gemm_w4a8_workspace_bytes(int64_t M, int64_t N, int64_t K, int group_s
     int g = 0;
     if (M <= 0 || w8_check(K, N, group_size, &g) != FQ_OK) return 0;
     const w8_plan p = w8_plan_of(M, N, K);
-    return p.splits > 1 ? (size_t)M * (size_t)N * sizeof(int32_t) : 0;
+    return p.splits > 1 ? (size_t)p.splits * (size_t)M * (size_t)N * sizeof(int32_t) : 0;
 }
 
 int fq_gemm_w4a8(const int8_t* Aq, const float* alpha, int64_t M, int64_t N, int64_t K, const void* codes,

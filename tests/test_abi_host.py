@@ -186,7 +186,8 @@ def test_plans_are_consistent_over_many_shapes():
         ws = fq.gemm_workspace_bytes_for(M, N, K, bits, g, fq.FQ_F16)
         ws_bf16 = fq.gemm_workspace_bytes_for(M, N, K, bits, g, fq.FQ_BF16)
         assert fq.gemm_workspace_bytes(M, N, K, bits, g) == max(ws, ws_bf16)
-        assert fq.gemm_workspace_bytes_for(M, N, K, bits, g, fq.FQ_BF16, fq.FQ_SCALE_BF16) == ws
+        # bfloat16 scales take the same path as binary16 ones (rows rewritten as binary16 for wide matrices)
+        assert fq.gemm_workspace_bytes_for(M, N, K, bits, g, fq.FQ_BF16, fq.FQ_SCALE_BF16) == ws_bf16
         KB = K // kblk
         if desc.startswith("small-m"):
             f = dict(re.findall(r"(\w+)=(\d+)", desc))
@@ -212,7 +213,8 @@ def test_plans_are_consistent_over_many_shapes():
                 seen.add("wide")
             assert splits >= 1 and kbs * splits >= KB and kbs * (splits - 1) < KB
             # bf16 rows are rewritten as binary16 for the 128-row shapes of wide matrices
-            extra = (-(-(M * K * 2) // 256) * 256 + M * 4) if (mt == 8 and N >= 8192) else 0
+            # (the rewritten rows, M row scales, the scale matrix's two powers of two and 256 words of their search)
+            extra = (-(-(M * K * 2) // 256) * 256 + (M + 2 + 256) * 4) if (mt == 8 and N >= 8192) else 0
             assert ws_bf16 == ws + extra
             tiles = -(-(N // 16) // (waves * 3)) * -(-M // (mt * 16))
             if tail_tiles:

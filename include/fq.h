@@ -252,8 +252,8 @@ int fq_gemm_grouped_sf(const void* A, int act_dtype, const int32_t* offsets_host
  *   product      S[m, n] = sum_k a[m, k] * q[k, n] * z[k / g, n] in exact int32 arithmetic (K <= 131072 keeps
  *                |S| < 2^31),  C[m, n] = alpha[m] * t[n] * S[m, n] evaluated in binary32, rounded to out_dtype.
  * Shape limits: N a multiple of 16, K a multiple of 128 and at most 131072, group_size 0 / K or a multiple of 32
- * that divides K.  The packed codes use the 4-bit layout of fq_quantize (fq_codes_bytes(K, N, 4) bytes;
- * fq_unpack(..., bits = 4, ...) reads them back).
+ * that divides K.  The packed codes take fq_codes_bytes(K, N, 4) bytes in a tiled layout of this path's own
+ * (ordered for the 64-deep int8 MFMA; fq_unpack does NOT read it, fq_unpack_w4a8 does).
  */
 
 /* Size in bytes of the multiplier matrix z[K/g, N] (one byte per group).  0 on invalid arguments. */
@@ -269,6 +269,9 @@ size_t fq_zscale_bytes(int64_t K, int64_t N, int group_size);
  */
 int fq_quantize_w4a8(const void* W_f16, int64_t K, int64_t N, int group_size, void* codes, uint8_t* zscale,
                      void* tstep_f16, void* stream);
+
+/* fq_unpack_w4a8 -- the logical signed codes q[K, N] (int8, row-major) of a buffer written by fq_quantize_w4a8. */
+int fq_unpack_w4a8(const void* codes, int64_t K, int64_t N, int8_t* q, void* stream);
 
 /*
  * fq_quantize_act_i8 -- the activation quantiser of the integer path (one scale per row).

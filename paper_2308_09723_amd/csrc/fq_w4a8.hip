@@ -7,6 +7,15 @@
 //   activations  Appendix A at 8 bits per row: alpha[m] binary32, a[m, k] in [-127, 127]
 //   product      S = sum_k a * (q * z) in int32 (v_mfma_i32_16x16x64_i8), C = alpha[m] * t[n] * S
 //
+// Packed layout of the codes of this path (its own: fq_unpack_w4a8 reads it back).  Tiles of 16 columns x 128
+// rows, k-block-major, 64 lane records of 16 bytes per tile exactly like the floating-point layout
+// (lane = 16 j + n % 16), but a record is ordered for v_mfma_i32_16x16x64_i8: MFMA step T (rows
+// 64 T .. 64 T + 63 of the k-block) takes from lane group j the 16 consecutive rows 64 T + 16 j + 0..15;
+// dword 2 T + h of the record holds rows 64 T + 16 j + 8 h + e (e = 0..7), byte b carrying element b in its
+// low and element b + 4 in its high nibble (stored value q + 8).  Masking the low / the high nibbles of a
+// dword then yields the operand's bytes in row order, and the activations need no reordering: lane (m, j)
+// supplies the 16 consecutive int8 of row m at k = 64 T + 16 j.
+//
 // The weights are brought to the activation's type before the multiply, as section 4.1 describes for the
 // floating-point kernels; here that type is int8 and the conversion is q * z, formed four at a time: the stored
 // nibbles u = q + 8 of a dword are spread over bytes, one packed 16-bit multiply-add gives u * z + (128 - 8 z)
@@ -85,7 +94,10 @@ __global__ __launch_bounds__(256) void w8_scales_kernel(const uint16_t* __restri
     }
 }
 
-// one thread per lane record (16 bytes: the 4 x 8 codes of one column in one k-block)
+// row of the k-block that element e of dword d of lane group j holds
+__host__ __device__ inline int w8_row(int d, int j, int e) { return 64 * (d >> 1) + 16 * j + 8 * (d & 1) + e; }
+
+// one thread per lane record (16 bytes: 32 codes of one column in one k-block)
 __global__ __launch_bounds__(256) void w8_encode_kernel(const uint16_t* __restrict__ W, int64_t K, int64_t N,
                                                          int g, const uint8_t* __restrict__ z,
                                                          const uint16_t* __restrict__ tstep,
@@ -101,19 +113,38 @@ __global__ __launch_bounds__(256) void w8_encode_kernel(const uint16_t* __restri
     uint32_t out[4];
 #pragma unroll
     for (int d = 0; d < 4; ++d) {
-        const int64_t k0 = kb * 128 + 32 * d + 8 * j;
-        const float s = (float)z[(k0 / g) * N + n] * t;                      // exact
+        const int64_t k0 = kb * 128 + w8_row(d, j, 0);
+        const float s = (float)z[(k0 / g) * N + n] * t;                      // exact; 8 rows inside one group
         uint32_t w = 0;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const float x = f16_bits_to_float(W[(k0 + e) * N + n]);
             int q = 0;
             if (s != 0.0f) q = (int)fminf(fmaxf(rintf(__fdiv_rn(x, s)), -7.0f), 7.0f);
-            w |= (uint32_t)(q + 8) << (4 * fq_nibble_slot(e));
+            w |= (uint32_t)(q + 8) << (8 * (e & 3) + 4 * (e >> 2));
         }
         out[d] = w;
     }
     *reinterpret_cast<uint4*>(codes + rec * 4) = make_uint4(out[0], out[1], out[2], out[3]);
+}
+
+// the logical codes q[K, N] (int8) of a packed buffer: one thread per lane record
+__global__ __launch_bounds__(256) void w8_unpack_kernel(const uint32_t* __restrict__ codes, int64_t K, int64_t N,
+                                                         int8_t* __restrict__ q) {
+    const int64_t rec = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t ntiles = N / FQ_NTILE;
+    if (rec >= (K / 128) * ntiles * 64) return;
+    const int lane = (int)(rec & 63);
+    const int64_t tile = (rec >> 6) % ntiles, kb = (rec >> 6) / ntiles;
+    const int64_t n = tile * FQ_NTILE + (lane & 15);
+    const int j = lane >> 4;
+    const uint4 v = *reinterpret_cast<const uint4*>(codes + rec * 4);
+    const uint32_t d4[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int d = 0; d < 4; ++d)
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            q[(kb * 128 + w8_row(d, j, e)) * N + n] = (int8_t)((int)((d4[d] >> (8 * (e & 3) + 4 * (e >> 2))) & 0xfu) - 8);
 }
 
 // ------------------------------------------------------------------------------------------------------
@@ -163,16 +194,22 @@ __global__ __launch_bounds__(256) void w8_act_quant_kernel(const uint16_t* __res
 
 // ------------------------------------------------------------------------------------------------------
 // Product.  Same orientation as the floating-point kernels: 16 x 16 tiles of C^T, the weights the first
-// MFMA operand (16 columns n), the activations the second (16 rows m); a lane's packed record holds, after the
-// conversion, its slice of the first operand, so weights never pass through LDS.  One v_mfma_i32_16x16x64_i8
-// contracts 64 rows of K: lane (n or m, j) supplies the 16 values of rows 64 T + 32 h + 8 j + e (h = 0, 1;
-// e = 0..7), i.e. dwords 2 T and 2 T + 1 of its record, in the byte order the nibble extraction leaves:
-// (e0, e4, e1, e5), (e2, e6, e3, e7) per dword.  The activation tile (BM rows x 128 int8) is staged through LDS
-// in that same order, 16 bytes per (row, T, j), the eight units of a row XOR-swizzled with the row so that a
-// fragment read of 16 rows spreads over all banks.
-// Block = 8 waves x 3 column tiles (384 columns), BM = 16 MT rows; k-block = 128 rows; two LDS buffers, one
-// barrier per k-block, the next k-block's weights and activations in flight during the multiply.
-// ZR = multiplier rows a k-block spans (1, 2 or 4: every 128, 64 or 32 rows).
+// MFMA operand (16 columns n), the activations the second (16 rows m); a lane's packed record is, after the
+// conversion, its slice of the first operand, so weights never pass through LDS.
+// Block = 8 waves x 3 column tiles (384 columns), BM = 16 MT rows, k-block = 128 rows = two MFMA steps.
+// The k loop is one software pipeline, two k-blocks deep:
+//   * activation tiles (BM rows x 128 int8, natural order) go global -> LDS directly (global_load_lds_dwordx4),
+//     three LDS tiles; the eight 16-byte units of a row are XOR-swizzled with the row (through the global
+//     address each lane reads), so a fragment read of 16 rows of one unit column spreads over all banks;
+//   * two weight register sets: the set of k-block kb is reloaded with k-block kb + 2 right after its last
+//     conversion; the loop is unrolled twice so that the sets keep their names;
+//   * one barrier per k-block, at its end: before it the wave waits until at most the loads issued after
+//     those of k-block kb + 1 are in flight (the counter retires in order and every loading wave issues the
+//     same loads), after it the tile read during kb is free.  Issue order inside k-block kb:
+//     fragments and conversion of step 0 | A(kb + 2) into the tile read during kb - 1 | fragments of step 1 |
+//     MFMAs of step 0 | conversion of step 1 | W(kb + 2) | MFMAs of step 1 | wait, barrier.
+// ZR = multiplier rows per k-block a lane needs: 1 when the group size is a multiple of 128, else one per
+// 64-row step (the lane's 16 rows of a step lie inside one 32-row block, hence inside one group).
 // With splits > 1 every block writes its int32 sums to its split's slab of a partial buffer and a second
 // kernel adds the slabs (integers: exact whatever the order) and scales the sum.
 // ------------------------------------------------------------------------------------------------------
@@ -197,14 +234,16 @@ template <int MT, int ZR, int OUT>
 __global__ __launch_bounds__(W8_WAVES * 64) void fq_gemm_w4a8_kernel(
     const int8_t* __restrict__ Aq, const float* __restrict__ alpha, const u32x4* __restrict__ codes,
     const uint8_t* __restrict__ z, const uint16_t* __restrict__ tstep, uint16_t* __restrict__ C,
-    int32_t* __restrict__ partial, int M, int N, int K, int g32, int kb_per_split, int splits, int nblocks_n,
+    int32_t* __restrict__ partial, int M, int N, int K, int g, int kb_per_split, int splits, int nblocks_n,
     int nblocks_m) {
     constexpr int NT = W8_NT;
     constexpr int BM = MT * 16;
-    constexpr int NTHR = W8_WAVES * 64;
     constexpr int UNITS = BM * 8;                       // 16-byte units of an activation tile
-    constexpr int UPT = (UNITS + NTHR - 1) / NTHR;
-    extern __shared__ u32x4 lds[];                       // [2][UNITS]
+    constexpr int NI = UNITS / 64;                      // wave-level direct loads per tile
+    constexpr int DPT = NI >= W8_WAVES ? NI / W8_WAVES : 1;   // of which this wave issues DPT (or none)
+    constexpr int NW = NT + ZR * NT;                    // vector loads of one weight set
+    static_assert(NI % W8_WAVES == 0 || NI < W8_WAVES, "every loading wave issues the same number of loads");
+    extern __shared__ u32x4 lds[];                       // [3][UNITS]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -240,17 +279,33 @@ __global__ __launch_bounds__(W8_WAVES * 64) void fq_gemm_w4a8_kernel(
         zbase[nt] = z + (int64_t)tc * FQ_NTILE + ml;
     }
 
-    // activation staging: unit u = tid + NTHR r -> (row = u / 8, slot = u % 8 = 4 T + jj)
-    int64_t a_off[UPT];
-    int a_dst[UPT];
+    // direct loads: LDS unit u = (wave DPT + r) 64 + lane of a tile = (row u / 8, position u % 8), which holds
+    // the row's 16-byte unit (position ^ (row & 7)); rows past the end repeat the last one (never stored)
+    const bool a_loader = NI >= W8_WAVES || wave < NI;   // wave-uniform
+    int64_t d_off[DPT];
 #pragma unroll
-    for (int r = 0; r < UPT; ++r) {
-        const int u = tid + NTHR * r;
-        const int row = u >> 3, slot = u & 7;
-        const int rowc = row < rows ? row : rows - 1;          // rows past the end repeat the last one; never stored
-        a_off[r] = (row0 + rowc) * (int64_t)K + 64 * (slot >> 2) + 8 * (slot & 3);
-        a_dst[r] = u < UNITS ? row * 8 + (slot ^ (row & 7)) : -1;
+    for (int r = 0; r < DPT; ++r) {
+        const int u = (wave * DPT + r) * 64 + lane;
+        const int row = u >> 3, pos = u & 7;
+        const int rowc = row < rows ? row : rows - 1;
+        d_off[r] = (row0 + rowc) * (int64_t)K + 16 * (pos ^ (row & 7));
     }
+    auto load_a_lds = [&](int kb, int tile_i) {
+        if (!a_loader) return;
+        const int8_t* base = Aq + (int64_t)kb * 128;
+        // (assembly on purpose: issued through the compiler's builtin these loads make its wait-count pass drain
+        // the whole memory queue at every later wait; the waits for them are written out below)
+        const uint32_t lds_base = __builtin_amdgcn_readfirstlane(
+            (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void*)(lds + tile_i * UNITS + wave * DPT * 64));
+#pragma unroll
+        for (int r = 0; r < DPT; ++r) {
+            const int8_t* src = base + d_off[r];
+            asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off"
+                         :
+                         : "s"(lds_base + r * 1024), "v"(src)
+                         : "memory", "m0");
+        }
+    };
     int a_rd[2];
 #pragma unroll
     for (int T = 0; T < 2; ++T) a_rd[T] = ml * 8 + ((4 * T + j) ^ (ml & 7));
@@ -261,80 +316,46 @@ __global__ __launch_bounds__(W8_WAVES * 64) void fq_gemm_w4a8_kernel(
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = v4i{0, 0, 0, 0};
 
-    u32x4 wq[NT], wq_n[NT];
-    uint32_t zq[ZR][NT], zq_n[ZR][NT];
-    u32x2 areg[UPT][2];
+    u32x4 wqs[2][NT];
+    uint32_t zqs[2][ZR][NT];
     auto load_w = [&](u32x4 (&q)[NT], uint32_t (&zr)[ZR][NT], int kb) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) q[nt] = wbase[nt][(int64_t)kb * kb_stride];
 #pragma unroll
         for (int r = 0; r < ZR; ++r) {
-            const int64_t zrow = (int64_t)((kb * 4 + r * (4 / ZR)) / g32) * N;
+            // ZR == 1: the k-block lies inside one group; else the group of this lane's rows of step r
+            const int krow = kb * 128 + (ZR == 1 ? 0 : 64 * r + 16 * j);
+            const int64_t zrow = (int64_t)(krow / g) * N;
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt) zr[r][nt] = zbase[nt][zrow];
         }
     };
-    auto load_a = [&](int kb) {
-#pragma unroll
-        for (int r = 0; r < UPT; ++r) {
-            const int8_t* p = Aq + a_off[r] + (int64_t)kb * 128;
-            areg[r][0] = *reinterpret_cast<const u32x2*>(p);
-            areg[r][1] = *reinterpret_cast<const u32x2*>(p + 32);
-        }
-    };
-    auto store_a = [&](u32x4* dst) {
-#pragma unroll
-        for (int r = 0; r < UPT; ++r) {
-            if (a_dst[r] < 0) continue;
-            u32x4 v;
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const uint32_t x = areg[r][h][0], y = areg[r][h][1];   // bytes a0..a3, a4..a7
-                v[2 * h] = __builtin_amdgcn_perm(y, x, 0x05010400u);     // (a0, a4, a1, a5)
-                v[2 * h + 1] = __builtin_amdgcn_perm(y, x, 0x07030602u); // (a2, a6, a3, a7)
-            }
-            dst[a_dst[r]] = v;
-        }
-    };
-
-    if (kb0 < kb1) {
-        load_a(kb0);
-        load_w(wq, zq, kb0);
-        store_a(lds);
-    }
-    __syncthreads();
-    int buf = 0;
-    auto convert = [&](u32x4 (&wop)[NT], int T) {
+    auto convert = [&](u32x4 (&wop)[NT], const u32x4 (&q)[NT], const uint32_t (&zr)[ZR][NT], int T) {
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {
+            const uint32_t zi = zr[ZR == 1 ? 0 : T][nt];
+            const uint16_t zz1 = (uint16_t)zi, cc1 = (uint16_t)((128u - 8u * zi) * 0x0101u);
+            const u16x2v zz = {zz1, zz1}, cc = {cc1, cc1};
 #pragma unroll
             for (int h = 0; h < 2; ++h) {
-                const int d = 2 * T + h;
-                const uint32_t zi = zq[d / (4 / ZR)][nt];
-                const uint16_t zz1 = (uint16_t)zi, cc1 = (uint16_t)((128u - 8u * zi) * 0x0101u);
-                const u16x2v zz = {zz1, zz1}, cc = {cc1, cc1};
-                const uint32_t w = wq[nt][d];
-                wop[nt][2 * h] = w8_scale_bytes(w & 0x0f0f0f0fu, zz, cc);
-                wop[nt][2 * h + 1] = w8_scale_bytes((w >> 4) & 0x0f0f0f0fu, zz, cc);
+                const uint32_t w = q[nt][2 * T + h];
+                wop[nt][2 * h] = w8_scale_bytes(w & 0x0f0f0f0fu, zz, cc);            // rows 8 h + 0..3
+                wop[nt][2 * h + 1] = w8_scale_bytes((w >> 4) & 0x0f0f0f0fu, zz, cc);   // rows 8 h + 4..7
             }
         }
     };
-    for (int kb = kb0; kb < kb1; ++kb) {
-        // Order of a k-block (kept by the scheduling barriers; left alone, the compiler sinks the global loads
-        // to the end of the iteration and waits for them at the top of the next one):
-        //   global loads of the next k-block | fragment reads of step 0 | conversion of step 0 |
-        //   fragment reads of step 1 | MFMAs of step 0 | conversion of step 1 | MFMAs of step 1 |
-        //   the next activation tile to LDS | barrier
-        const int kbn = kb + 1 < kb1 ? kb + 1 : kb;
-        load_w(wq_n, zq_n, kbn);
-        load_a(kbn);
-        __builtin_amdgcn_sched_barrier(0);
-        const u32x4* abuf = lds + buf * UNITS;
+    // one k-block: set (qa, za) holds its weights, tile `cur` its activations
+    auto kblock = [&](int kb, int cur, u32x4 (&qa)[NT], uint32_t (&za)[ZR][NT]) {
+        const int kb2 = kb + 2 < kb1 ? kb + 2 : kb1 - 1;
+        const u32x4* abuf = lds + cur * UNITS;
         u32x4 af0[MT], af1[MT], wop0[NT], wop1[NT];
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) af0[mt] = abuf[a_rd[0] + mt * 128];
-        convert(wop0, 0);
+        convert(wop0, qa, za, 0);
         __builtin_amdgcn_sched_barrier(0);
+        // (behind the first use of this k-block's weights: the compiler's wait for them, which does not know of
+        // the direct loads, then cannot reach the loads of k-block kb + 1 issued half a k-block ago)
+        load_a_lds(kb2, cur >= 1 ? cur - 1 : 2);                  // the tile read during kb - 1  (= (cur + 2) % 3)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) af1[mt] = abuf[a_rd[1] + mt * 128];
         __builtin_amdgcn_sched_barrier(0);
@@ -344,7 +365,10 @@ __global__ __launch_bounds__(W8_WAVES * 64) void fq_gemm_w4a8_kernel(
             for (int nt = 0; nt < NT; ++nt)
                 acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(bitcast<v4i>(wop0[nt]), bitcast<v4i>(af0[mt]),
                                                                     acc[mt][nt], 0, 0, 0);
-        convert(wop1, 1);
+        convert(wop1, qa, za, 1);
+        __builtin_amdgcn_sched_barrier(0);
+        load_w(qa, za, kb2);
+        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt)
 #pragma unroll
@@ -352,15 +376,30 @@ __global__ __launch_bounds__(W8_WAVES * 64) void fq_gemm_w4a8_kernel(
                 acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(bitcast<v4i>(wop1[nt]), bitcast<v4i>(af1[mt]),
                                                                     acc[mt][nt], 0, 0, 0);
         __builtin_amdgcn_sched_barrier(0);
-        store_a(lds + (buf ^ 1) * UNITS);
+        // tile kb + 1 (this wave's share) has landed once at most the loads issued after it are in flight
+        wait_vmcnt<DPT + NW>();
         __syncthreads();
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) wq[nt] = wq_n[nt];
-#pragma unroll
-        for (int r = 0; r < ZR; ++r)
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt) zq[r][nt] = zq_n[r][nt];
-        buf ^= 1;
+    };
+
+    if (kb0 < kb1) {
+        const int kbn = kb0 + 1 < kb1 ? kb0 + 1 : kb1 - 1;
+        // same issue order as inside the loop: A(kb), W(kb), A(kb + 1), W(kb + 1)
+        load_a_lds(kb0, 0);
+        load_w(wqs[0], zqs[0], kb0);
+        load_a_lds(kbn, 1);
+        load_w(wqs[1], zqs[1], kbn);
+        wait_vmcnt<DPT + NW>();
+        __syncthreads();
+        int kb = kb0, cur = 0;
+        for (; kb + 2 <= kb1; kb += 2) {
+            kblock(kb, cur, wqs[0], zqs[0]);
+            cur = cur == 2 ? 0 : cur + 1;
+            kblock(kb + 1, cur, wqs[1], zqs[1]);
+            cur = cur == 2 ? 0 : cur + 1;
+        }
+        if (kb < kb1) kblock(kb, cur, wqs[0], zqs[0]);
+        // the last (redundant) direct loads still target this block's LDS
+        wait_vmcnt<0>();
     }
 
     float tn[NT][4];
@@ -438,15 +477,14 @@ template <int MT, int OUT>
 void w8_launch(const w8_plan& p, int g, const int8_t* Aq, const float* alpha, const void* codes, const uint8_t* z,
                const void* tstep, void* C, int32_t* partial, int64_t M, int64_t N, int64_t K, hipStream_t stream) {
     const dim3 grid((unsigned)((int64_t)p.nblocks_n * p.nblocks_m * p.splits));
-    const size_t lds = (size_t)2 * MT * 16 * 8 * 16;
-    const int zr = g % 128 == 0 ? 1 : (g == 64 ? 2 : 4);
+    const size_t lds = (size_t)3 * MT * 16 * 8 * 16;
+    const int zr = g % 128 == 0 ? 1 : 2;
 #define W8_GO(ZR_)                                                                                              \
     hipLaunchKernelGGL((fq_gemm_w4a8_kernel<MT, ZR_, OUT>), grid, dim3(W8_WAVES * 64), lds, stream, Aq, alpha,   \
                        (const u32x4*)codes, z, (const uint16_t*)tstep, (uint16_t*)C, partial, (int)M, (int)N,    \
-                       (int)K, g / 32, p.kb_per_split, p.splits, p.nblocks_n, p.nblocks_m)
+                       (int)K, g, p.kb_per_split, p.splits, p.nblocks_n, p.nblocks_m)
     if (zr == 1) W8_GO(1);
-    else if (zr == 2) W8_GO(2);
-    else W8_GO(4);
+    else W8_GO(2);
 #undef W8_GO
 }
 
@@ -496,6 +534,17 @@ int fq_quantize_w4a8(const void* W_f16, int64_t K, int64_t N, int group_size, vo
     const int64_t recs = (K / 128) * (N / FQ_NTILE) * 64;
     hipLaunchKernelGGL(w8_encode_kernel, dim3((unsigned)((recs + 255) / 256)), dim3(256), 0, s, (const uint16_t*)W_f16, K,
                        N, g, (const uint8_t*)zscale, (const uint16_t*)tstep_f16, (uint32_t*)codes);
+    return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;
+}
+
+int fq_unpack_w4a8(const void* codes, int64_t K, int64_t N, int8_t* q, void* stream) {
+    if (!codes || !q) return FQ_ERR_INVALID_ARG;
+    int g = 0;
+    const int st = w8_check(K, N, 0, &g);
+    if (st != FQ_OK) return st;
+    const int64_t recs = (K / 128) * (N / FQ_NTILE) * 64;
+    hipLaunchKernelGGL(w8_unpack_kernel, dim3((unsigned)((recs + 255) / 256)), dim3(256), 0, (hipStream_t)stream,
+                       (const uint32_t*)codes, K, N, q);
     return hipGetLastError() == hipSuccess ? FQ_OK : FQ_ERR_HIP;
 }
 

@@ -71,6 +71,7 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "fq_zscale_bytes": (sz, [i64, i64, i32]),
         "fq_quantize_w4a8": (i32, [vp, i64, i64, i32, vp, vp, vp, vp]),
         "fq_quantize_act_i8": (i32, [vp, i32, i64, i64, vp, vp, vp]),
+        "fq_unpack_w4a8": (i32, [vp, i64, i64, vp, vp]),
         "fq_gemm_w4a8_workspace_bytes": (sz, [i64, i64, i64, i32]),
         "fq_gemm_w4a8": (i32, [vp, vp, i64, i64, i64, vp, vp, vp, i32, vp, i32, vp, sz, vp]),
         "fq_gemm_describe": (i32, [i64, i64, i64, i32, i32, ctypes.c_char_p, sz]),
@@ -93,7 +94,7 @@ EXPORTED = [
     "fq_quant_error_workspace_bytes", "fq_quant_error",
     "fq_quantize_sf", "fq_quant_error_sf", "fq_gemm_sf", "fq_gemm_grouped_sf", "fq_gemm_workspace_bytes_for",
     "fq_stream_read_probe", "fq_gemm_noalloc", "fq_gemm_noalloc_scratch_bytes",
-    "fq_zscale_bytes", "fq_quantize_w4a8", "fq_quantize_act_i8", "fq_gemm_w4a8_workspace_bytes", "fq_gemm_w4a8",
+    "fq_zscale_bytes", "fq_unpack_w4a8", "fq_quantize_w4a8", "fq_quantize_act_i8", "fq_gemm_w4a8_workspace_bytes", "fq_gemm_w4a8",
 ]
 
 
@@ -221,6 +222,10 @@ def zscale_bytes(K, N, group_size):
 
 def quantize_w4a8_raw(W_ptr, K, N, group_size, codes_ptr, z_ptr, t_ptr, stream=0):
     return int(load().fq_quantize_w4a8(W_ptr, K, N, group_size, codes_ptr, z_ptr, t_ptr, stream))
+
+
+def unpack_w4a8_raw(codes_ptr, K, N, q_ptr, stream=0):
+    return int(load().fq_unpack_w4a8(codes_ptr, K, N, q_ptr, stream))
 
 
 def quantize_act_i8_raw(A_ptr, act_dtype, M, K, Aq_ptr, alpha_ptr, stream=0):
@@ -370,6 +375,14 @@ def quantize_w4a8(W, group_size):
     _check(quantize_w4a8_raw(W.data_ptr(), K, N, group_size, codes.data_ptr(), z.data_ptr(), t.data_ptr(), _stream()),
            "fq_quantize_w4a8")
     return codes, z, t
+
+
+def unpack_w4a8(codes, K, N):
+    import torch
+
+    q = torch.empty((K, N), dtype=torch.int8, device=codes.device)
+    _check(unpack_w4a8_raw(codes.data_ptr(), K, N, q.data_ptr(), _stream()), "fq_unpack_w4a8")
+    return q
 
 
 def quantize_act_i8(A):

@@ -25,7 +25,7 @@ def _quantize_weights(W, g):
     q_ref, z_ref, t_ref = oracle.quantize_int_scales(W, g)
     assert np.array_equal(t.view(torch.int16).cpu().numpy().view(np.uint16), t_ref.view(np.uint16)), "column steps differ"
     assert np.array_equal(z.cpu().numpy(), z_ref), "multipliers differ"
-    assert np.array_equal(fq.unpack(codes, K, N, 4).cpu().numpy(), q_ref), "codes differ"
+    assert np.array_equal(fq.unpack_w4a8(codes, K, N).cpu().numpy(), q_ref), "codes differ"
     return codes, z, t, q_ref, z_ref, t_ref
 
 
@@ -153,7 +153,7 @@ def test_full_size_layer_on_sampled_columns():
     cols_d = torch.from_numpy(cols).cuda()
     codes, z, t = fq.quantize_w4a8(torch.from_numpy(W).cuda(), 128)
     q_ref, z_ref, t_ref = oracle.quantize_int_scales(np.ascontiguousarray(W[:, cols]), 128)
-    assert np.array_equal(fq.unpack(codes, K, N, 4).index_select(1, cols_d).cpu().numpy(), q_ref)
+    assert np.array_equal(fq.unpack_w4a8(codes, K, N).index_select(1, cols_d).cpu().numpy(), q_ref)
     assert np.array_equal(z.index_select(1, cols_d).cpu().numpy(), z_ref)
     assert np.array_equal(t.index_select(0, cols_d).view(torch.int16).cpu().numpy().view(np.uint16), t_ref.view(np.uint16))
     for M, dtype in ((8, "f16"), (2048, "bf16")):

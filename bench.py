@@ -88,7 +88,7 @@ def main():
                     help="also time the other BASELINE configurations (reported under 'extra'): prefill and mid-M "
                          "products (configs[2]), the grouped expert products (configs[3]) and the heavy-tailed "
                          "stress layer (configs[4])")
-    ap.add_argument("--profile", choices=["decode", "prefill", "prefill-int8", "copy", "moe", "midm", "quantize", "w4a8"], default=None,
+    ap.add_argument("--profile", choices=["decode", "prefill", "prefill-int8", "copy", "moe", "midm", "quantize", "w4a8", "w4a8-prefill"], default=None,
                     help="short untimed run of one case for rocprofv3 (no JSON line): 'decode' = the benchmark "
                          "step, 'prefill' = QKV-shaped product at M = 2048 (bf16, then fp16; 'prefill-int8': the same with "
                          "8-bit codes, one group per column), 'copy' = a 1 GiB device copy "
@@ -130,6 +130,9 @@ def main():
         return
     if args.profile == "w4a8":
         print(json.dumps(w4a8_section(torch, fq, workloads, layers=("qkv",))), file=sys.stderr)
+        return
+    if args.profile == "w4a8-prefill":
+        print(json.dumps(w4a8_section(torch, fq, workloads, layers=("qkv",), Ms=(2048,))), file=sys.stderr)
         return
     if args.profile == "midm":
         K, N = workloads.OPT175B_LAYERS["qkv"]
@@ -579,7 +582,7 @@ def int3_section(torch, fq, workloads):
 INT8_PEAK_TOPS = 5000.0        # dense int8 MFMA, published
 
 
-def w4a8_section(torch, fq, workloads, layers=("qkv", "out_proj", "fc1", "fc2")):
+def w4a8_section(torch, fq, workloads, layers=("qkv", "out_proj", "fc1", "fc2"), Ms=(1, 8, 32, 128, 512, 2048)):
     """The integer path (int8 activations x int4 weights with integer group scales, g = 128) on the OPT-175B
     shapes: the product alone (activations quantised beforehand) at M = 1, 8, 32, 128, 512, 2048, against the HBM
     peak (weight stream) and the dense int8 MFMA peak; plus the two quantisers' times."""
@@ -598,7 +601,7 @@ def w4a8_section(torch, fq, workloads, layers=("qkv", "out_proj", "fc1", "fc2"))
             res["quantize_w4a8_qkv_ms"] = round(_timed(torch, quant, settle=0.1, reps=5), 3)
         del W
         wbytes = codes.numel() + z.numel() + t.numel() * 2
-        for M in (1, 8, 32, 128, 512, 2048):
+        for M in Ms:
             A = torch.randn((M, K), device="cuda", dtype=torch.float32).to(torch.bfloat16)
             Aq, alpha = fq.quantize_act_i8(A)
             C = torch.empty((M, N), device="cuda", dtype=torch.bfloat16)

@@ -206,8 +206,9 @@ __global__ __launch_bounds__(256) void w8_act_quant_kernel(const uint16_t* __res
 //   * one barrier per k-block, at its end: before it the wave waits until at most the loads issued after
 //     those of k-block kb + 1 are in flight (the counter retires in order and every loading wave issues the
 //     same loads), after it the tile read during kb is free.  Issue order inside k-block kb:
-//     fragments and conversion of step 0 | A(kb + 2) into the tile read during kb - 1 | fragments of step 1 |
-//     MFMAs of step 0 | conversion of step 1 | W(kb + 2) | MFMAs of step 1 | wait, barrier.
+//     fragments of step 1 | MFMAs of step 0 with the conversion of step 1 between them | first MFMAs of step 1 |
+//     A(kb + 2) into the tile read during kb - 1, W(kb + 2) | MFMAs of step 1 with the conversion of step 0 of
+//     k-block kb + 1 between them; before the last of them: wait, barrier, fragments of step 0 of kb + 1.
 // ZR = multiplier rows per k-block a lane needs: 1 when the group size is a multiple of 128, else one per
 // 64-row step (the lane's 16 rows of a step lie inside one 32-row block, hence inside one group).
 // With splits > 1 every block writes its int32 sums to its split's slab of a partial buffer and a second
@@ -330,55 +331,97 @@ __global__ __launch_bounds__(W8_WAVES * 64) void fq_gemm_w4a8_kernel(
             for (int nt = 0; nt < NT; ++nt) zr[r][nt] = zbase[nt][zrow];
         }
     };
-    auto convert = [&](u32x4 (&wop)[NT], const u32x4 (&q)[NT], const uint32_t (&zr)[ZR][NT], int T) {
-#pragma unroll
-        for (int nt = 0; nt < NT; ++nt) {
-            const uint32_t zi = zr[ZR == 1 ? 0 : T][nt];
-            const uint16_t zz1 = (uint16_t)zi, cc1 = (uint16_t)((128u - 8u * zi) * 0x0101u);
-            const u16x2v zz = {zz1, zz1}, cc = {cc1, cc1};
-#pragma unroll
-            for (int h = 0; h < 2; ++h) {
-                const uint32_t w = q[nt][2 * T + h];
-                wop[nt][2 * h] = w8_scale_bytes(w & 0x0f0f0f0fu, zz, cc);            // rows 8 h + 0..3
-                wop[nt][2 * h + 1] = w8_scale_bytes((w >> 4) & 0x0f0f0f0fu, zz, cc);   // rows 8 h + 4..7
-            }
+    // piece p (0 .. 2 NT - 1) of the conversion of step T: dword h = p % 2 of column tile p / 2 (the pieces of a
+    // step are converted in this order; the first piece of a column tile prepares its multiplier)
+    uint32_t zcur[NT], ccur[NT];
+    auto conv_piece = [&](u32x4 (&wop)[NT], const u32x4 (&q)[NT], const uint32_t (&zr)[ZR][NT], int T, int p) {
+        const int nt = p >> 1, h = p & 1;
+        if (h == 0) {
+            // (the loaded multiplier stays opaque to the optimiser until here: otherwise its narrowing to 16 bits
+            // is moved up to the load, and with it a wait for loads that were only just issued)
+            uint32_t zi = zr[ZR == 1 ? 0 : T][nt];
+            asm volatile("" : "+v"(zi));
+            zcur[nt] = zi;
+            ccur[nt] = (uint32_t)(0x8080 - (int)zi * 0x0808);   // 128 - 8 z in both bytes (8 z <= 128: no borrow)
         }
+        const u16x2v zz = {(uint16_t)zcur[nt], (uint16_t)zcur[nt]};
+        const u16x2v cc = {(uint16_t)ccur[nt], (uint16_t)ccur[nt]};
+        const uint32_t w = q[nt][2 * T + h];
+        wop[nt][2 * h] = w8_scale_bytes(w & 0x0f0f0f0fu, zz, cc);            // rows 8 h + 0..3
+        wop[nt][2 * h + 1] = w8_scale_bytes((w >> 4) & 0x0f0f0f0fu, zz, cc);   // rows 8 h + 4..7
     };
-    // one k-block: set (qa, za) holds its weights, tile `cur` its activations
-    auto kblock = [&](int kb, int cur, u32x4 (&qa)[NT], uint32_t (&za)[ZR][NT]) {
+    constexpr int NP = 2 * NT;                     // conversion pieces per step
+    constexpr int BAR_MT = MT >= 4 ? MT - 2 : MT - 1;   // the barrier stands before this MFMA group of step 1
+    u32x4 wopA[NT], wopB[NT], af0[MT], af1[MT];
+    // One k-block.  (qa, za): its weights, (qb, zb): those of k-block kb + 1, tile `cur`: its activations.
+    // On entry wopA holds the converted operands of its step 0 and af0 that step's fragments (requested);
+    // on exit the same for k-block kb + 1.  The conversions run in pieces between the MFMA groups (three MFMAs
+    // of one row tile), where they issue while the matrix pipe works; with all conversions in front of the
+    // MFMAs the waves of a block, which the barrier keeps in step, convert at the same time and multiply at the
+    // same time, and the two units overlap for only a twentieth of the time.
+    auto kblock = [&](int kb, int cur, u32x4 (&qa)[NT], uint32_t (&za)[ZR][NT], u32x4 (&qb)[NT],
+                      uint32_t (&zb)[ZR][NT]) {
         const int kb2 = kb + 2 < kb1 ? kb + 2 : kb1 - 1;
+        const int nxt = cur == 2 ? 0 : cur + 1;
         const u32x4* abuf = lds + cur * UNITS;
-        u32x4 af0[MT], af1[MT], wop0[NT], wop1[NT];
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt) af0[mt] = abuf[a_rd[0] + mt * 128];
-        convert(wop0, qa, za, 0);
+        const u32x4* nbuf = lds + nxt * UNITS;
         __builtin_amdgcn_sched_barrier(0);
-        // (behind the first use of this k-block's weights: the compiler's wait for them, which does not know of
-        // the direct loads, then cannot reach the loads of k-block kb + 1 issued half a k-block ago)
-        load_a_lds(kb2, cur >= 1 ? cur - 1 : 2);                  // the tile read during kb - 1  (= (cur + 2) % 3)
 #pragma unroll
         for (int mt = 0; mt < MT; ++mt) af1[mt] = abuf[a_rd[1] + mt * 128];
         __builtin_amdgcn_sched_barrier(0);
+        // step 0: MFMAs with wopA, conversion of step 1 into wopB
 #pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
-#pragma unroll
-            for (int nt = 0; nt < NT; ++nt)
-                acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(bitcast<v4i>(wop0[nt]), bitcast<v4i>(af0[mt]),
-                                                                    acc[mt][nt], 0, 0, 0);
-        convert(wop1, qa, za, 1);
-        __builtin_amdgcn_sched_barrier(0);
-        load_w(qa, za, kb2);
-        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-        for (int mt = 0; mt < MT; ++mt)
+        for (int mt = 0; mt < MT; ++mt) {
 #pragma unroll
             for (int nt = 0; nt < NT; ++nt)
-                acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(bitcast<v4i>(wop1[nt]), bitcast<v4i>(af1[mt]),
+                acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(bitcast<v4i>(wopA[nt]), bitcast<v4i>(af0[mt]),
                                                                     acc[mt][nt], 0, 0, 0);
+            if (mt < NP) conv_piece(wopB, qa, za, 1, mt);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int p = MT; p < NP; ++p) conv_piece(wopB, qa, za, 1, p);
         __builtin_amdgcn_sched_barrier(0);
-        // tile kb + 1 (this wave's share) has landed once at most the loads issued after it are in flight
-        wait_vmcnt<DPT + NW>();
-        __syncthreads();
+        // step 1: MFMAs with wopB, conversion of the next k-block's step 0 into wopA
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) {
+            if (mt == BAR_MT) {
+                // every fragment of this tile has been read (own LDS reads returned), and this wave's share of
+                // tile kb + 1 has landed once at most the loads issued after it are in flight
+                // (with a single MFMA group per step the loads of k-block kb + 2 are issued behind this point:
+                // then only the weights of kb + 1 are younger than its tile)
+                __builtin_amdgcn_s_waitcnt(0xC07F);          // lgkmcnt(0) only
+                wait_vmcnt<(BAR_MT == 0 ? NW : DPT + NW)>();
+                __syncthreads();
+#pragma unroll
+                for (int m2 = 0; m2 < MT; ++m2) af0[m2] = nbuf[a_rd[0] + m2 * 128];
+                __builtin_amdgcn_sched_barrier(0);
+            }
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt)
+                acc[mt][nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(bitcast<v4i>(wopB[nt]), bitcast<v4i>(af1[mt]),
+                                                                    acc[mt][nt], 0, 0, 0);
+            if (mt < NP) conv_piece(wopA, qb, zb, 0, mt);
+            __builtin_amdgcn_sched_barrier(0);
+            if (mt == 0) {
+                // Every register of the next k-block's weights is named here, so that the compiler places all
+                // its waits for them in front of the loads issued now (they landed long ago); a wait placed
+                // later would, in the compiler's count, which does not know of the direct loads, reach into the
+                // loads just issued.  Set a is free.
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    asm volatile("" : : "v"(qb[nt][0]), "v"(qb[nt][1]), "v"(qb[nt][2]), "v"(qb[nt][3]));
+#pragma unroll
+                    for (int r = 0; r < ZR; ++r) asm volatile("" : : "v"(zb[r][nt]));
+                }
+                load_a_lds(kb2, cur >= 1 ? cur - 1 : 2);      // the tile read during kb - 1  (= (cur + 2) % 3)
+                load_w(qa, za, kb2);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+#pragma unroll
+        for (int p = MT; p < NP; ++p) conv_piece(wopA, qb, zb, 0, p);
+        __builtin_amdgcn_sched_barrier(0);
     };
 
     if (kb0 < kb1) {
@@ -390,14 +433,18 @@ __global__ __launch_bounds__(W8_WAVES * 64) void fq_gemm_w4a8_kernel(
         load_w(wqs[1], zqs[1], kbn);
         wait_vmcnt<DPT + NW>();
         __syncthreads();
+#pragma unroll
+        for (int mt = 0; mt < MT; ++mt) af0[mt] = lds[a_rd[0] + mt * 128];
+#pragma unroll
+        for (int p = 0; p < NP; ++p) conv_piece(wopA, wqs[0], zqs[0], 0, p);
         int kb = kb0, cur = 0;
         for (; kb + 2 <= kb1; kb += 2) {
-            kblock(kb, cur, wqs[0], zqs[0]);
+            kblock(kb, cur, wqs[0], zqs[0], wqs[1], zqs[1]);
             cur = cur == 2 ? 0 : cur + 1;
-            kblock(kb + 1, cur, wqs[1], zqs[1]);
+            kblock(kb + 1, cur, wqs[1], zqs[1], wqs[0], zqs[0]);
             cur = cur == 2 ? 0 : cur + 1;
         }
-        if (kb < kb1) kblock(kb, cur, wqs[0], zqs[0]);
+        if (kb < kb1) kblock(kb, cur, wqs[0], zqs[0], wqs[1], zqs[1]);
         // the last (redundant) direct loads still target this block's LDS
         wait_vmcnt<0>();
     }

@@ -267,7 +267,8 @@ __global__ __launch_bounds__(W8_WAVES * 64) void fq_gemm_w4a8_kernel(
     const int64_t row0 = (int64_t)bm_idx * BM;
     const int rows = (int)min((int64_t)BM, (int64_t)M - row0);
 
-    const u32x4* wbase[NT];
+    // wave-uniform bases (scalar registers); the lane's part is a 32-bit offset added by the load itself
+    const char* wbase[NT];
     const uint8_t* zbase[NT];
     bool tvalid[NT];
     const int tile0 = (bn * W8_WAVES + wave) * NT;
@@ -276,9 +277,10 @@ __global__ __launch_bounds__(W8_WAVES * 64) void fq_gemm_w4a8_kernel(
         const int tile = tile0 + nt;
         tvalid[nt] = tile < ntiles;
         const int tc = tvalid[nt] ? tile : 0;
-        wbase[nt] = codes + fq_rec(tc, 0, ntiles, lane);
-        zbase[nt] = z + (int64_t)tc * FQ_NTILE + ml;
+        wbase[nt] = reinterpret_cast<const char*>(codes + fq_rec(tc, 0, ntiles, 0));
+        zbase[nt] = z + (int64_t)tc * FQ_NTILE;
     }
+    const uint32_t lane_rec = (uint32_t)lane * 16u;
 
     // direct loads: LDS unit u = (wave DPT + r) 64 + lane of a tile = (row u / 8, position u % 8), which holds
     // the row's 16-byte unit (position ^ (row & 7)); rows past the end repeat the last one (never stored)
@@ -320,15 +322,22 @@ __global__ __launch_bounds__(W8_WAVES * 64) void fq_gemm_w4a8_kernel(
     u32x4 wqs[2][NT];
     uint32_t zqs[2][ZR][NT];
     auto load_w = [&](u32x4 (&q)[NT], uint32_t (&zr)[ZR][NT], int kb) {
+        const int64_t kb_bytes = (int64_t)kb * kb_stride * 16;
 #pragma unroll
-        for (int nt = 0; nt < NT; ++nt) q[nt] = wbase[nt][(int64_t)kb * kb_stride];
+        for (int nt = 0; nt < NT; ++nt) q[nt] = load_rec<4, false>(scalar_ptr(wbase[nt] + kb_bytes) + lane_rec);
 #pragma unroll
         for (int r = 0; r < ZR; ++r) {
-            // ZR == 1: the k-block lies inside one group; else the group of this lane's rows of step r
-            const int krow = kb * 128 + (ZR == 1 ? 0 : 64 * r + 16 * j);
-            const int64_t zrow = (int64_t)(krow / g) * N;
+            if constexpr (ZR == 1) {
+                // the k-block lies inside one group
+                const int64_t zrow = (int64_t)((kb * 128) / g) * N;
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) zr[r][nt] = zbase[nt][zrow];
+                for (int nt = 0; nt < NT; ++nt) zr[r][nt] = scalar_ptr(zbase[nt] + zrow)[(uint32_t)ml];
+            } else {
+                // the group of this lane's 16 rows of step r
+                const int64_t zrow = (int64_t)((kb * 128 + 64 * r + 16 * j) / g) * N;
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) zr[r][nt] = zbase[nt][zrow + ml];
+            }
         }
     };
     // piece p (0 .. 2 NT - 1) of the conversion of step T: dword h = p % 2 of column tile p / 2 (the pieces of a

@@ -273,6 +273,15 @@ def main():
     out["stream_ceiling"] = stream_ceiling(torch, fq)
     if not args.no_large_m:
         out.update(default_large_m(torch, fq, layers))
+        w8 = w4a8_section(torch, fq, workloads, layers=("qkv",), Ms=(8, 2048), time_quantizers=False)
+        out["roofline_w4a8"] = {
+            "bound": "mfma", "unit": "TOP/s", "peak": INT8_PEAK_TOPS, "achieved": w8["qkv_M2048"]["TOPs"],
+            "frac": w8["qkv_M2048"]["frac_of_int8_peak"],
+            "kernel": "fq_gemm_w4a8_kernel (v_mfma_i32_16x16x64_i8), the integer path: int8 activations x int4 weights "
+                      "with integer group scales; the product alone, activations quantised beforehand",
+            "workload": "QKV 12288 x 36864, g=128, M = 2048 (and M = 8 against the HBM peak)",
+            "cases": w8,
+        }
     if args.large_m or args.all_configs:
         out["extra"] = large_m_section(torch, fq, layers, (32, 128, 512, 2048) if args.all_configs else (256, 2048))
     if args.all_configs:
@@ -582,7 +591,8 @@ def int3_section(torch, fq, workloads):
 INT8_PEAK_TOPS = 5000.0        # dense int8 MFMA, published
 
 
-def w4a8_section(torch, fq, workloads, layers=("qkv", "out_proj", "fc1", "fc2"), Ms=(1, 8, 32, 128, 512, 2048)):
+def w4a8_section(torch, fq, workloads, layers=("qkv", "out_proj", "fc1", "fc2"), Ms=(1, 8, 32, 128, 512, 2048),
+                 time_quantizers=True):
     """The integer path (int8 activations x int4 weights with integer group scales, g = 128) on the OPT-175B
     shapes: the product alone (activations quantised beforehand) at M = 1, 8, 32, 128, 512, 2048, against the HBM
     peak (weight stream) and the dense int8 MFMA peak; plus the two quantisers' times."""
@@ -597,7 +607,7 @@ def w4a8_section(torch, fq, workloads, layers=("qkv", "out_proj", "fc1", "fc2"),
             st = fq.quantize_w4a8_raw(W.data_ptr(), K, N, GROUP, codes.data_ptr(), z.data_ptr(), t.data_ptr(), stream)
             if st != fq.FQ_OK:
                 raise fq.FqError(st, "fq_quantize_w4a8")
-        if name == "qkv":
+        if name == "qkv" and time_quantizers:
             res["quantize_w4a8_qkv_ms"] = round(_timed(torch, quant, settle=0.1, reps=5), 3)
         del W
         wbytes = codes.numel() + z.numel() + t.numel() * 2
@@ -624,7 +634,7 @@ def w4a8_section(torch, fq, workloads, layers=("qkv", "out_proj", "fc1", "fc2"),
             res[f"{name}_M{M}"] = {"us": round(ms * 1e3, 2), "weight_TBps": round(wbytes / ms / 1e9, 3),
                                    "frac_of_hbm_peak": round(wbytes / ms / 1e6 / HBM_PEAK_GBS, 4),
                                    "TOPs": round(tops, 1), "frac_of_int8_peak": round(tops / INT8_PEAK_TOPS, 4)}
-            if name == "qkv" and M == 2048:
+            if name == "qkv" and M == 2048 and time_quantizers:
                 def aq():
                     st = fq.quantize_act_i8_raw(A.data_ptr(), fq.FQ_BF16, M, K, Aq.data_ptr(), alpha.data_ptr(), stream)
                     if st != fq.FQ_OK:

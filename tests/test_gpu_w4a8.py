@@ -141,12 +141,13 @@ def test_product_extreme_sums_and_one_hot_rows():
     _check_product(C2, C2_ref, "f16", "one-hot rows")
 
 
-def test_full_size_layer_on_sampled_columns():
-    """The out-proj-shaped layer at the sizes bench.py times for this path (M = 8 and M = 2048), on a column
-    sample that covers every 384-column block."""
+@pytest.mark.parametrize("layer", ["out_proj", "qkv"])
+def test_full_size_layer_on_sampled_columns(layer):
+    """The out-proj- and QKV-shaped layers (the latter is the one bench.py times for this path) at M = 8 and
+    M = 2048, on a column sample that covers every 384-column block."""
     from paper_2308_09723_amd import fq
     torch = torch_mod()
-    W = workloads.opt175b_weight("out_proj", seed=9)
+    W = workloads.opt175b_weight(layer, seed=9)
     K, N = W.shape
     cols = np.unique(np.concatenate([np.arange(0, N, 384) + (np.arange(0, N, 384) // 384 * 37) % 384, [0, 15, N - 16, N - 1]]))
     cols = cols[cols < N]
@@ -164,8 +165,8 @@ def test_full_size_layer_on_sampled_columns():
         assert bool(torch.isfinite(Cd.float()).all())
         C = from_dev_act(Cd.index_select(1, cols_d), dtype)
         _, C_ref = oracle.gemm_ref_int(a_ref, alpha_ref, q_ref, z_ref, t_ref)
-        rel = _check_product(C, C_ref, dtype, f"out_proj M={M}")
-        print(f"  w4a8 out_proj M={M} {dtype}: rel err {rel:.2e}", flush=True)
+        rel = _check_product(C, C_ref, dtype, f"{layer} M={M}")
+        print(f"  w4a8 {layer} M={M} {dtype}: rel err {rel:.2e}", flush=True)
 
 
 def test_rejects_bad_arguments():

@@ -163,9 +163,8 @@ int fq_quant_error_sf(const void* W_f16, int64_t K, int64_t N, int bits, int gro
  * accumulated in binary32, written in the activation's data type.  (For bfloat16 activations and
  * wide matrices with many rows the product is evaluated on the fp16 matrix path after each
  * activation row has been divided by a power of two that fits it into binary16; the result is
- * rescaled exactly and rounded to bfloat16 once.  That power of two is limited to 2^+-100: a row whose
- * largest magnitude lies below 2^-100 is not brought up fully and loses relative precision, one whose
- * largest magnitude lies below 2^-124 contributes zeros.  With bfloat16 scales the scale matrix is likewise
+ * rescaled exactly and rounded to bfloat16 once; every bfloat16 magnitude has such a power of two, so rows
+ * of any size keep their relative precision.  With bfloat16 scales the scale matrix is likewise
  * divided by the power of two of its largest scale, and scales more than 2^14 times smaller than that one lose
  * low bits or vanish.)
  *

@@ -768,8 +768,10 @@ __global__ __launch_bounds__(256) void fq_reduce_tail_kernel(const float* __rest
 }
 
 // bfloat16 rows -> binary16 rows divided by a power of two per row (see FQ_BF16_VIA_F16): block r
-// rewrites row r.  e = (exponent of the row's largest element) - 14, kept within +-100;
-// A16[r, :] = A[r, :] * 2^-e rounded to binary16, rowscale[r] = 2^e.
+// rewrites row r.  e = (exponent of the row's largest element) - 14 (between -141 and 114: every bfloat16
+// magnitude is brought to 2^14 .. 2^15, an exact scaling);
+// A16[r, :] = A[r, :] * 2^-e rounded to binary16, rowscale[r] = e as a float (2^e itself need not be a
+// normal binary32 number; the product kernel applies it in two halves).
 template <int THREADS>   // (a template so that every translation unit may hold a copy)
 __global__ __launch_bounds__(THREADS) void fq_rows_to_f16_kernel(const uint16_t* __restrict__ A, int K,
                                                              uint16_t* __restrict__ A16,
@@ -800,9 +802,8 @@ __global__ __launch_bounds__(THREADS) void fq_rows_to_f16_kernel(const uint16_t*
     m = red[0];
 #pragma unroll
     for (int i = 1; i < 4; ++i) m = red[i] > m ? red[i] : m;
-    int e = (int)(m >> 7) - 127 - 14;
-    e = e < -100 ? -100 : (e > 100 ? 100 : e);
-    if (threadIdx.x == 0) rowscale[r] = ldexpf(1.0f, e);
+    const int e = (int)(m >> 7) - 127 - 14;
+    if (threadIdx.x == 0) rowscale[r] = (float)e;
     for (int u = threadIdx.x; u < units; u += 256) {
         const u32x4 v = src[u];
         u32x4 o;
@@ -997,10 +998,11 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
     const uint32_t magic = Dequant<ACT, BITS>::init();
     const u32x4 zero4 = {0u, 0u, 0u, 0u};
     // FQ_BF16S_VIA_F16: the two floats behind the M row scales are 2^-E and 2^E (E: exponent of the largest scale)
-    float sshift = 1.0f, sback = 1.0f;
+    float sshift = 1.0f;
+    int sback_exp = 0;       // E
     if constexpr (ACT == FQ_BF16S_VIA_F16) {
         sshift = rowscale[M];
-        sback = rowscale[M + 1];
+        sback_exp = (int)((bitcast<uint32_t>(rowscale[M + 1]) >> 23) & 255u) - 127;   // 2^E is a normal number
     }
     constexpr int NQ = KREC * NT;                // lane records of a k-block: [record][column tile]
     u32x4 wq[NQ], wq_n[NQ], areg[UPT];
@@ -1353,10 +1355,17 @@ __global__ __launch_bounds__(WAVES * 64, (POST && MT == 2 && WAVES == 4 && ACT =
         const int row = mt * 16 + ml;
         if (row >= rows) continue;
         if constexpr (ACT == FQ_BF16_VIA_F16 || ACT == FQ_BF16S_VIA_F16) {
-            // back from the row's normalised scale (and the scales' common one): powers of two, exact
-            const float rs = rowscale[row0 + row] * sback;
+            // Back from the row's power of two and the scales' common one: the result times 2^T, T = e + E.
+            // 2^T may lie outside the normal binary32 range while the scaled result does not, so it is
+            // applied as two normal factors 2^(T/2) (the value after the first one lies between the sum and
+            // the result, hence in range whenever both are; exact unless the result itself is subnormal).
+            int T = (int)rowscale[row0 + row] + sback_exp;
+            T = T < -252 ? -252 : (T > 252 ? 252 : T);
+            const int h1 = T >> 1, h2 = T - h1;
+            const float m1 = bitcast<float>((uint32_t)(h1 + 127) << 23);
+            const float m2 = bitcast<float>((uint32_t)(h2 + 127) << 23);
 #pragma unroll
-            for (int nt = 0; nt < NT; ++nt) acc[mt][nt] *= rs;
+            for (int nt = 0; nt < NT; ++nt) acc[mt][nt] = (acc[mt][nt] * m1) * m2;
         }
 #pragma unroll
         for (int nt = 0; nt < NT; ++nt) {

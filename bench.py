@@ -340,6 +340,7 @@ def default_large_m(torch, fq, layers):
                       "time of 10 back-to-back calls",
             "workload": "BASELINE configs[2] shape: QKV 12288 x 36864, int4 g=128, M = 2048",
             "cases": big,
+            "mfma_ceiling": mfma_ceiling(torch, fq),
         },
         "mid_m": {
             "workload": "BASELINE configs[2] shape: QKV 12288 x 36864, int4 g=128, bf16, weights cycled through "
@@ -368,6 +369,35 @@ def stream_ceiling(torch, fq):
     ms = _timed(torch, run, settle=0.2, reps=20)
     return {"kind": "read-only kernel over a 2 GiB buffer", "GBps": round(n / ms / 1e6, 1),
             "frac_of_hbm_peak": round(n / ms / 1e6 / HBM_PEAK_GBS, 4)}
+
+
+def mfma_ceiling(torch, fq):
+    """What this box's matrix pipes deliver to a loop of nothing but MFMAs on operands distributed like the
+    product's (fq_mfma_rate_probe: N(0,1) activations, N(0,0.02) weights, binary16), with and without the
+    product's LDS fragment reads, and on all-zero operands: the clock under load follows the switching activity of
+    the operands, so the vendor's peak is reached on zeros only."""
+    nb = fq.mfma_rate_probe_operand_bytes()
+    sb = fq.mfma_rate_probe_sink_bytes()
+    n16 = nb // 2
+    ops = torch.randn(n16, device="cuda", dtype=torch.float32).to(torch.float16)
+    ops[n16 - 512 * 3 * 8:] *= 0.02                      # the tail holds the weight-like operands
+    zeros = torch.zeros(n16, device="cuda", dtype=torch.float16)
+    sink = torch.empty(sb, dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    iters = 200
+    flops = fq.mfma_rate_probe_flops(iters)
+    out = {"kind": "fq_mfma_rate_probe: the 128-row shape's MFMA loop (v_mfma_f32_16x16x32_f16) without loads, "
+                   "conversions or barriers; TFLOP/s"}
+    for key, buf, lds in (("random_operands_with_lds_reads", ops, 1), ("random_operands_registers_only", ops, 0),
+                          ("zero_operands_registers_only", zeros, 0)):
+        def run():
+            st = fq.mfma_rate_probe_raw(buf.data_ptr(), nb, sink.data_ptr(), sb, iters, lds, stream)
+            if st != fq.FQ_OK:
+                raise fq.FqError(st, "fq_mfma_rate_probe")
+        ms = _timed(torch, run, settle=0.3, reps=10)
+        out[key] = round(flops / ms / 1e9, 1)
+    out["frac_of_mfma_peak"] = round(out["random_operands_with_lds_reads"] / MFMA_PEAK_TFLOPS, 4)
+    return out
 
 
 def profile_prefill(torch, fq, workloads, reps, settle, bits=BITS, group=GROUP):

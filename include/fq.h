@@ -321,6 +321,27 @@ int fq_gemm_describe(int64_t M, int64_t N, int64_t K, int bits, int group_size, 
  */
 int fq_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stream);
 
+/*
+ * fq_mfma_rate_probe -- measurement helper, not part of the method: one kernel (1024 blocks of 8 waves) that
+ * runs the MFMA loop of the 128-row shape of the large-M product (per wave and iteration 96
+ * v_mfma_f32_16x16x32_f16: 4 k-steps x 8 row tiles x 3 column tiles) on the caller's operand VALUES and nothing
+ * else: no global loads in the loop, no conversions, no barrier; with lds_reads != 0 one 16-byte fragment
+ * read from LDS per lane and three MFMAs, as in the product.  The clock this GPU holds under load follows the
+ * switching activity of the operands, so the rate of this loop on operands distributed like the product's
+ * (and not the vendor's peak, which it reaches on all-zero operands only) is what the matrix pipes can
+ * deliver to the product; the caller times it.
+ *   operands   in   device, >= fq_mfma_rate_probe_operand_bytes() bytes of binary16 values (read as they are)
+ *   sink       out  device, >= fq_mfma_rate_probe_sink_bytes() bytes (one checksum per thread)
+ * One launch performs fq_mfma_rate_probe_flops(iterations) floating-point operations.
+ * Errors: FQ_ERR_INVALID_ARG (NULL pointer, iterations outside 1 .. 2^20), FQ_ERR_WORKSPACE (a buffer is too
+ * small), FQ_ERR_HIP.
+ */
+size_t fq_mfma_rate_probe_operand_bytes(void);
+size_t fq_mfma_rate_probe_sink_bytes(void);
+double fq_mfma_rate_probe_flops(int iterations);
+int fq_mfma_rate_probe(const void* operands, size_t operand_bytes, void* sink, size_t sink_bytes, int iterations,
+                       int lds_reads, void* stream);
+
 /* Human-readable name of a status code (static string, never NULL). */
 const char* fq_status_string(int status);
 

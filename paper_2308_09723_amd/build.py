@@ -19,6 +19,7 @@ SOURCES = [
     "fq_quantize.hip",
     "fq_gemm.hip",
     "fq_w4a8.hip",
+    "fq_probe.hip",
     "fq_gemm_f16_4.hip",
     "fq_gemm_f16_8.hip",
     "fq_gemm_bf16_4.hip",

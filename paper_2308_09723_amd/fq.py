@@ -76,6 +76,10 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "fq_gemm_w4a8": (i32, [vp, vp, i64, i64, i64, vp, vp, vp, i32, vp, i32, vp, sz, vp]),
         "fq_gemm_describe": (i32, [i64, i64, i64, i32, i32, ctypes.c_char_p, sz]),
         "fq_stream_read_probe": (i32, [vp, sz, vp, vp]),
+        "fq_mfma_rate_probe_operand_bytes": (sz, []),
+        "fq_mfma_rate_probe_sink_bytes": (sz, []),
+        "fq_mfma_rate_probe_flops": (ctypes.c_double, [i32]),
+        "fq_mfma_rate_probe": (i32, [vp, sz, vp, sz, i32, i32, vp]),
         "fq_status_string": (ctypes.c_char_p, [i32]),
         "fq_version": (ctypes.c_char_p, []),
     }
@@ -94,12 +98,30 @@ EXPORTED = [
     "fq_quant_error_workspace_bytes", "fq_quant_error",
     "fq_quantize_sf", "fq_quant_error_sf", "fq_gemm_sf", "fq_gemm_grouped_sf", "fq_gemm_workspace_bytes_for",
     "fq_stream_read_probe", "fq_gemm_noalloc", "fq_gemm_noalloc_scratch_bytes",
+    "fq_mfma_rate_probe_operand_bytes", "fq_mfma_rate_probe_sink_bytes", "fq_mfma_rate_probe_flops", "fq_mfma_rate_probe",
     "fq_zscale_bytes", "fq_unpack_w4a8", "fq_quantize_w4a8", "fq_quantize_act_i8", "fq_gemm_w4a8_workspace_bytes", "fq_gemm_w4a8",
 ]
 
 
 def stream_read_probe_raw(buf_ptr, nbytes, sink_ptr, stream=0):
     return int(load().fq_stream_read_probe(buf_ptr, nbytes, sink_ptr, stream))
+
+
+def mfma_rate_probe_operand_bytes():
+    return int(load().fq_mfma_rate_probe_operand_bytes())
+
+
+def mfma_rate_probe_sink_bytes():
+    return int(load().fq_mfma_rate_probe_sink_bytes())
+
+
+def mfma_rate_probe_flops(iterations):
+    return float(load().fq_mfma_rate_probe_flops(int(iterations)))
+
+
+def mfma_rate_probe_raw(operands_ptr, operand_bytes, sink_ptr, sink_bytes, iterations, lds_reads, stream=0):
+    return int(load().fq_mfma_rate_probe(operands_ptr, operand_bytes, sink_ptr, sink_bytes, iterations, lds_reads,
+                                         stream))
 
 
 def status_string(status: int) -> str:

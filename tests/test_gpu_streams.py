@@ -145,3 +145,28 @@ def test_stream_read_probe_reads_every_word_once(nbytes):
     assert got == np.bitwise_xor.reduce(host)
     assert fq.stream_read_probe_raw(buf.data_ptr(), 24, sink.data_ptr(), 0) == fq.FQ_ERR_INVALID_ARG
     assert fq.stream_read_probe_raw(None, 16, sink.data_ptr(), 0) == fq.FQ_ERR_INVALID_ARG
+
+
+def test_mfma_rate_probe_counts_what_it_says():
+    """The measurement helper that bench.py times as the matrix pipes' ceiling: with all operands 1.0 every
+    accumulator element ends at 32 per MFMA folded into it (4 k-steps x iterations), so each thread's checksum is
+    known; buffers that are too small are refused."""
+    from paper_2308_09723_amd import fq
+    torch = torch_mod()
+    nb, sb = fq.mfma_rate_probe_operand_bytes(), fq.mfma_rate_probe_sink_bytes()
+    ones = torch.ones(nb // 2, dtype=torch.float16, device="cuda")
+    sink = torch.zeros(sb // 4, dtype=torch.float32, device="cuda")
+    stream = torch.cuda.current_stream().cuda_stream
+    iters = 3
+    for lds in (0, 1):
+        sink.zero_()
+        assert fq.mfma_rate_probe_raw(ones.data_ptr(), nb, sink.data_ptr(), sb, iters, lds, stream) == fq.FQ_OK
+        torch.cuda.synchronize()
+        # 8 x 3 accumulator tiles, four elements each, every element = 32 * 4 * iters
+        want = 8 * 3 * 4 * 32.0 * 4 * iters
+        assert bool((sink == want).all()), (float(sink.min()), float(sink.max()), want)
+    assert fq.mfma_rate_probe_flops(iters) == 1024 * 8 * iters * 96 * 2.0 * 16 * 16 * 32
+    assert fq.mfma_rate_probe_raw(ones.data_ptr(), nb - 16, sink.data_ptr(), sb, iters, 0, 0) == fq.FQ_ERR_WORKSPACE
+    assert fq.mfma_rate_probe_raw(ones.data_ptr(), nb, sink.data_ptr(), sb - 4, iters, 0, 0) == fq.FQ_ERR_WORKSPACE
+    assert fq.mfma_rate_probe_raw(None, nb, sink.data_ptr(), sb, iters, 0, 0) == fq.FQ_ERR_INVALID_ARG
+    assert fq.mfma_rate_probe_raw(ones.data_ptr(), nb, sink.data_ptr(), sb, 0, 0, 0) == fq.FQ_ERR_INVALID_ARG

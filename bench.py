@@ -281,6 +281,7 @@ def main():
                       "with integer group scales; the product alone, activations quantised beforehand",
             "workload": "QKV 12288 x 36864, g=128, M = 2048 (and M = 8 against the HBM peak)",
             "cases": w8,
+            "mfma_ceiling": mfma_ceiling(torch, fq, int8=True),
         }
     if args.large_m or args.all_configs:
         out["extra"] = large_m_section(torch, fq, layers, (32, 128, 512, 2048) if args.all_configs else (256, 2048))
@@ -371,32 +372,45 @@ def stream_ceiling(torch, fq):
             "frac_of_hbm_peak": round(n / ms / 1e6 / HBM_PEAK_GBS, 4)}
 
 
-def mfma_ceiling(torch, fq):
+def mfma_ceiling(torch, fq, int8=False):
     """What this box's matrix pipes deliver to a loop of nothing but MFMAs on operands distributed like the
-    product's (fq_mfma_rate_probe: N(0,1) activations, N(0,0.02) weights, binary16), with and without the
+    product's (fq_mfma_rate_probe: N(0,1) activations and N(0,0.02) weights in binary16, or, for the integer
+    path, int8 activations quantised from N(0,1) rows and codes times multipliers), with and without the
     product's LDS fragment reads, and on all-zero operands: the clock under load follows the switching activity of
     the operands, so the vendor's peak is reached on zeros only."""
     nb = fq.mfma_rate_probe_operand_bytes()
     sb = fq.mfma_rate_probe_sink_bytes()
-    n16 = nb // 2
-    ops = torch.randn(n16, device="cuda", dtype=torch.float32).to(torch.float16)
-    ops[n16 - 512 * 3 * 8:] *= 0.02                      # the tail holds the weight-like operands
-    zeros = torch.zeros(n16, device="cuda", dtype=torch.float16)
+    if int8:
+        # activations: rne(x * 127 / max|x|) of N(0,1) rows (max ~ 4.5 sigma over 12288 values); weights: code x multiplier
+        ops = torch.clamp(torch.round(torch.randn(nb, device="cuda") * (127.0 / 4.5)), -127, 127).to(torch.int8)
+        wq = torch.clamp(torch.round(torch.randn(512 * 3 * 16, device="cuda") * 2.3), -7, 7)
+        wz = torch.randint(8, 17, (512 * 3 * 16,), device="cuda").float()
+        ops[nb - 512 * 3 * 16:] = (wq * wz).to(torch.int8)
+        zeros = torch.zeros(nb, device="cuda", dtype=torch.int8)
+        kind = "v_mfma_i32_16x16x64_i8"
+        peak = INT8_PEAK_TOPS
+    else:
+        n16 = nb // 2
+        ops = torch.randn(n16, device="cuda", dtype=torch.float32).to(torch.float16)
+        ops[n16 - 512 * 3 * 8:] *= 0.02                      # the tail holds the weight-like operands
+        zeros = torch.zeros(n16, device="cuda", dtype=torch.float16)
+        kind = "v_mfma_f32_16x16x32_f16"
+        peak = MFMA_PEAK_TFLOPS
     sink = torch.empty(sb, dtype=torch.uint8, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
     iters = 200
-    flops = fq.mfma_rate_probe_flops(iters)
-    out = {"kind": "fq_mfma_rate_probe: the 128-row shape's MFMA loop (v_mfma_f32_16x16x32_f16) without loads, "
-                   "conversions or barriers; TFLOP/s"}
+    flops = fq.mfma_rate_probe_flops(iters, int(int8))
+    out = {"kind": f"fq_mfma_rate_probe: the 128-row shape's MFMA loop ({kind}) without loads, conversions or "
+                   f"barriers; {'TOP/s' if int8 else 'TFLOP/s'}"}
     for key, buf, lds in (("random_operands_with_lds_reads", ops, 1), ("random_operands_registers_only", ops, 0),
                           ("zero_operands_registers_only", zeros, 0)):
         def run():
-            st = fq.mfma_rate_probe_raw(buf.data_ptr(), nb, sink.data_ptr(), sb, iters, lds, stream)
+            st = fq.mfma_rate_probe_raw(buf.data_ptr(), nb, sink.data_ptr(), sb, iters, lds, int(int8), stream)
             if st != fq.FQ_OK:
                 raise fq.FqError(st, "fq_mfma_rate_probe")
         ms = _timed(torch, run, settle=0.3, reps=10)
         out[key] = round(flops / ms / 1e9, 1)
-    out["frac_of_mfma_peak"] = round(out["random_operands_with_lds_reads"] / MFMA_PEAK_TFLOPS, 4)
+    out["frac_of_peak"] = round(out["random_operands_with_lds_reads"] / peak, 4)
     return out
 
 

@@ -329,18 +329,20 @@ int fq_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stream
  * read from LDS per lane and three MFMAs, as in the product.  The clock this GPU holds under load follows the
  * switching activity of the operands, so the rate of this loop on operands distributed like the product's
  * (and not the vendor's peak, which it reaches on all-zero operands only) is what the matrix pipes can
- * deliver to the product; the caller times it.
- *   operands   in   device, >= fq_mfma_rate_probe_operand_bytes() bytes of binary16 values (read as they are)
- *   sink       out  device, >= fq_mfma_rate_probe_sink_bytes() bytes (one checksum per thread)
- * One launch performs fq_mfma_rate_probe_flops(iterations) floating-point operations.
+ * deliver to the product; the caller times it.  With int8 != 0 the loop uses the integer path's instruction
+ * (v_mfma_i32_16x16x64_i8) on the same bytes read as int8 values.
+ *   operands   in   device, >= fq_mfma_rate_probe_operand_bytes() bytes of binary16 (or int8) values, read as
+ *                   they are
+ *   sink       out  device, >= fq_mfma_rate_probe_sink_bytes() bytes (one binary32 checksum per thread)
+ * One launch performs fq_mfma_rate_probe_flops(iterations, int8) operations (2 per multiply-add).
  * Errors: FQ_ERR_INVALID_ARG (NULL pointer, iterations outside 1 .. 2^20), FQ_ERR_WORKSPACE (a buffer is too
  * small), FQ_ERR_HIP.
  */
 size_t fq_mfma_rate_probe_operand_bytes(void);
 size_t fq_mfma_rate_probe_sink_bytes(void);
-double fq_mfma_rate_probe_flops(int iterations);
+double fq_mfma_rate_probe_flops(int iterations, int int8);
 int fq_mfma_rate_probe(const void* operands, size_t operand_bytes, void* sink, size_t sink_bytes, int iterations,
-                       int lds_reads, void* stream);
+                       int lds_reads, int int8, void* stream);
 
 /* Human-readable name of a status code (static string, never NULL). */
 const char* fq_status_string(int status);

@@ -318,13 +318,15 @@ int fq_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stream
 
 size_t fq_mfma_rate_probe_operand_bytes(void) { return fq_mfma_probe_operand_bytes(); }
 size_t fq_mfma_rate_probe_sink_bytes(void) { return fq_mfma_probe_sink_bytes(); }
-double fq_mfma_rate_probe_flops(int iterations) { return iterations > 0 ? fq_mfma_probe_flops(iterations) : 0.0; }
+double fq_mfma_rate_probe_flops(int iterations, int int8) {
+    return iterations > 0 ? fq_mfma_probe_flops(iterations, int8 != 0) : 0.0;
+}
 
 int fq_mfma_rate_probe(const void* operands, size_t operand_bytes, void* sink, size_t sink_bytes, int iterations,
-                       int lds_reads, void* stream) {
+                       int lds_reads, int int8, void* stream) {
     if (!operands || !sink || iterations <= 0 || iterations > (1 << 20)) return FQ_ERR_INVALID_ARG;
     if (operand_bytes < fq_mfma_probe_operand_bytes() || sink_bytes < fq_mfma_probe_sink_bytes()) return FQ_ERR_WORKSPACE;
-    return fq_launch_mfma_rate_probe(operands, sink, iterations, lds_reads != 0, (hipStream_t)stream);
+    return fq_launch_mfma_rate_probe(operands, sink, iterations, lds_reads != 0, int8 != 0, (hipStream_t)stream);
 }
 
 const char* fq_status_string(int status) {

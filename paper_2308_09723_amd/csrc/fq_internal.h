@@ -22,8 +22,9 @@ int fq_launch_choose_group(const void* W, int64_t K, int64_t N, int g_top, int l
 int fq_launch_stream_read_probe(const void* buf, size_t bytes, void* sink, hipStream_t stream);
 size_t fq_mfma_probe_operand_bytes();
 size_t fq_mfma_probe_sink_bytes();
-double fq_mfma_probe_flops(int iterations);
-int fq_launch_mfma_rate_probe(const void* operands, void* sink, int iterations, int lds_reads, hipStream_t stream);
+double fq_mfma_probe_flops(int iterations, int int8);
+int fq_launch_mfma_rate_probe(const void* operands, void* sink, int iterations, int lds_reads, int int8,
+                              hipStream_t stream);
 
 // product side
 struct fq_gemm_plan {

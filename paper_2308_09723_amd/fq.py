@@ -78,8 +78,8 @@ def load(build_if_missing: bool = True) -> ctypes.CDLL:
         "fq_stream_read_probe": (i32, [vp, sz, vp, vp]),
         "fq_mfma_rate_probe_operand_bytes": (sz, []),
         "fq_mfma_rate_probe_sink_bytes": (sz, []),
-        "fq_mfma_rate_probe_flops": (ctypes.c_double, [i32]),
-        "fq_mfma_rate_probe": (i32, [vp, sz, vp, sz, i32, i32, vp]),
+        "fq_mfma_rate_probe_flops": (ctypes.c_double, [i32, i32]),
+        "fq_mfma_rate_probe": (i32, [vp, sz, vp, sz, i32, i32, i32, vp]),
         "fq_status_string": (ctypes.c_char_p, [i32]),
         "fq_version": (ctypes.c_char_p, []),
     }
@@ -115,13 +115,13 @@ def mfma_rate_probe_sink_bytes():
     return int(load().fq_mfma_rate_probe_sink_bytes())
 
 
-def mfma_rate_probe_flops(iterations):
-    return float(load().fq_mfma_rate_probe_flops(int(iterations)))
+def mfma_rate_probe_flops(iterations, int8=0):
+    return float(load().fq_mfma_rate_probe_flops(int(iterations), int(int8)))
 
 
-def mfma_rate_probe_raw(operands_ptr, operand_bytes, sink_ptr, sink_bytes, iterations, lds_reads, stream=0):
+def mfma_rate_probe_raw(operands_ptr, operand_bytes, sink_ptr, sink_bytes, iterations, lds_reads, int8=0, stream=0):
     return int(load().fq_mfma_rate_probe(operands_ptr, operand_bytes, sink_ptr, sink_bytes, iterations, lds_reads,
-                                         stream))
+                                         int8, stream))
 
 
 def status_string(status: int) -> str:

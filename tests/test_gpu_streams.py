@@ -148,25 +148,29 @@ def test_stream_read_probe_reads_every_word_once(nbytes):
 
 
 def test_mfma_rate_probe_counts_what_it_says():
-    """The measurement helper that bench.py times as the matrix pipes' ceiling: with all operands 1.0 every
-    accumulator element ends at 32 per MFMA folded into it (4 k-steps x iterations), so each thread's checksum is
-    known; buffers that are too small are refused."""
+    """The measurement helper that bench.py times as the matrix pipes' ceiling: with all operands 1 (binary16 1.0,
+    or int8 1 for the integer instruction) every accumulator element grows by the MFMA's depth (32 or 64) per
+    MFMA folded into it (4 k-steps x iterations), so each thread's checksum is known; buffers that are too small
+    are refused."""
     from paper_2308_09723_amd import fq
     torch = torch_mod()
     nb, sb = fq.mfma_rate_probe_operand_bytes(), fq.mfma_rate_probe_sink_bytes()
-    ones = torch.ones(nb // 2, dtype=torch.float16, device="cuda")
+    ones16 = torch.ones(nb // 2, dtype=torch.float16, device="cuda")
+    ones8 = torch.ones(nb, dtype=torch.int8, device="cuda")
     sink = torch.zeros(sb // 4, dtype=torch.float32, device="cuda")
     stream = torch.cuda.current_stream().cuda_stream
     iters = 3
-    for lds in (0, 1):
-        sink.zero_()
-        assert fq.mfma_rate_probe_raw(ones.data_ptr(), nb, sink.data_ptr(), sb, iters, lds, stream) == fq.FQ_OK
-        torch.cuda.synchronize()
-        # 8 x 3 accumulator tiles, four elements each, every element = 32 * 4 * iters
-        want = 8 * 3 * 4 * 32.0 * 4 * iters
-        assert bool((sink == want).all()), (float(sink.min()), float(sink.max()), want)
-    assert fq.mfma_rate_probe_flops(iters) == 1024 * 8 * iters * 96 * 2.0 * 16 * 16 * 32
-    assert fq.mfma_rate_probe_raw(ones.data_ptr(), nb - 16, sink.data_ptr(), sb, iters, 0, 0) == fq.FQ_ERR_WORKSPACE
-    assert fq.mfma_rate_probe_raw(ones.data_ptr(), nb, sink.data_ptr(), sb - 4, iters, 0, 0) == fq.FQ_ERR_WORKSPACE
-    assert fq.mfma_rate_probe_raw(None, nb, sink.data_ptr(), sb, iters, 0, 0) == fq.FQ_ERR_INVALID_ARG
-    assert fq.mfma_rate_probe_raw(ones.data_ptr(), nb, sink.data_ptr(), sb, 0, 0, 0) == fq.FQ_ERR_INVALID_ARG
+    for int8, ones, depth in ((0, ones16, 32), (1, ones8, 64)):
+        for lds in (0, 1):
+            sink.zero_()
+            assert fq.mfma_rate_probe_raw(ones.data_ptr(), nb, sink.data_ptr(), sb, iters, lds, int8, stream) == fq.FQ_OK
+            torch.cuda.synchronize()
+            # 8 x 3 accumulator tiles, four elements each, every element = depth * 4 * iters
+            want = 8 * 3 * 4 * float(depth) * 4 * iters
+            assert bool((sink == want).all()), (int8, lds, float(sink.min()), float(sink.max()), want)
+        assert fq.mfma_rate_probe_flops(iters, int8) == 1024 * 8 * iters * 96 * 2.0 * 16 * 16 * depth
+    ones = ones16
+    assert fq.mfma_rate_probe_raw(ones.data_ptr(), nb - 16, sink.data_ptr(), sb, iters, 0, 0, 0) == fq.FQ_ERR_WORKSPACE
+    assert fq.mfma_rate_probe_raw(ones.data_ptr(), nb, sink.data_ptr(), sb - 4, iters, 0, 0, 0) == fq.FQ_ERR_WORKSPACE
+    assert fq.mfma_rate_probe_raw(None, nb, sink.data_ptr(), sb, iters, 0, 0, 0) == fq.FQ_ERR_INVALID_ARG
+    assert fq.mfma_rate_probe_raw(ones.data_ptr(), nb, sink.data_ptr(), sb, 0, 0, 0, 0) == fq.FQ_ERR_INVALID_ARG

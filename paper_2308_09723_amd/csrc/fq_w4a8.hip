@@ -360,7 +360,10 @@ __global__ __launch_bounds__(W8_WAVES * 64) void fq_gemm_w4a8_kernel(
         wop[nt][2 * h + 1] = w8_scale_bytes((w >> 4) & 0x0f0f0f0fu, zz, cc);   // rows 8 h + 4..7
     };
     constexpr int NP = 2 * NT;                     // conversion pieces per step
-    constexpr int BAR_MT = MT >= 4 ? MT - 2 : MT - 1;   // the barrier stands before this MFMA group of step 1
+    // the barrier stands before this MFMA group of step 1: early in the 128-row shape, so that the reads of the next
+    // k-block's first fragments, which follow it, have six MFMA groups to return in (measured 1 - 4 % faster
+    // than ahead of the last two groups; the tile it waits for was requested a k-block earlier either way)
+    constexpr int BAR_MT = MT >= 8 ? 1 : (MT >= 4 ? MT - 2 : MT - 1);
     u32x4 wopA[NT], wopB[NT], af0[MT], af1[MT];
     // One k-block.  (qa, za): its weights, (qb, zb): those of k-block kb + 1, tile `cur`: its activations.
     // On entry wopA holds the converted operands of its step 0 and af0 that step's fragments (requested);

@@ -106,7 +106,7 @@ def _resource_report(rows, verbose):
         dem = names
     table = []
     for d, r in zip(dem, rows):
-        short = d.split("(")[0].replace("void ", "").replace("fqk::", "")
+        short = d.replace("(anonymous namespace)::", "").split("(")[0].replace("void ", "").replace("fqk::", "")
         table.append((short,) + r[1:])
     table.sort()
     with open(os.path.join(OBJ_DIR, "resources.txt"), "w") as f:

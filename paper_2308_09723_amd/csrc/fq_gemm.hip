@@ -32,7 +32,7 @@ FQ_DECLARE_GEMM(2, 3)
 
 // Compute units of the device, asked once per process (the current device at the first call); without a
 // device (host-only use of the size queries and fq_gemm_describe) the MI355X's 256.
-static int fq_cu_count() {
+int fq_cu_count() {
     static const int n = [] {
         int dev = 0, v = 0;
         if (hipGetDevice(&dev) == hipSuccess &&

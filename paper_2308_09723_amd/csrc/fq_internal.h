@@ -41,6 +41,8 @@ struct fq_gemm_plan {
     int tail_tiles, tail_splits, tail_kbs;
 };
 fq_gemm_plan fq_plan_gemm(int64_t M, int64_t N, int64_t K, int bits, int g);
+// compute units of the device (asked once per process; 256 without a device)
+int fq_cu_count();
 // Rows of K per k-block of the tiled kernel for a block shape (the unit of kb_per_split and tail_kbs):
 // the layout's k-block, except that the 128-row, 8-wave shape takes two 64-row blocks of 8-bit codes at a
 // time when K allows it and such a k-block lies inside one scale group (with two scale rows the wider

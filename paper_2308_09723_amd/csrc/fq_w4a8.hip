@@ -23,6 +23,7 @@
 // complement.
 #include <hip/hip_runtime.h>
 #include <hip/hip_fp16.h>
+#include <math.h>
 #include <stdint.h>
 
 #include "fq_gemm_kernels.h"
@@ -363,7 +364,8 @@ __global__ __launch_bounds__(W8_WAVES * 64) void fq_gemm_w4a8_kernel(
     // the barrier stands before this MFMA group of step 1: early in the 128-row shape, so that the reads of the next
     // k-block's first fragments, which follow it, have six MFMA groups to return in (measured 1 - 4 % faster
     // than ahead of the last two groups; the tile it waits for was requested a k-block earlier either way)
-    constexpr int BAR_MT = MT >= 8 ? 1 : (MT >= 4 ? MT - 2 : MT - 1);
+    // (with two multiplier rows per k-block the fragments held that much longer cost spilled registers)
+    constexpr int BAR_MT = MT >= 8 ? (ZR == 1 ? 1 : MT - 2) : (MT >= 4 ? MT - 2 : MT - 1);
     u32x4 wopA[NT], wopB[NT], af0[MT], af1[MT];
     // One k-block.  (qa, za): its weights, (qb, zb): those of k-block kb + 1, tile `cur`: its activations.
     // On entry wopA holds the converted operands of its step 0 and af0 that step's fragments (requested);
@@ -485,6 +487,224 @@ __global__ __launch_bounds__(W8_WAVES * 64) void fq_gemm_w4a8_kernel(
     }
 }
 
+
+// ------------------------------------------------------------------------------------------------------
+// Small-M kernel of the integer path (M <= 16), bound by the HBM read of the weights like its floating-point
+// counterpart (fq_gemm_skinny_kernel), whose structure it takes: one block per compute unit and all blocks
+// resident at once; a block is GP column groups x KW k-workers (run-time values), wave (gi, kw) owns NT
+// column tiles and, in iteration `it`, k-block (sb * KW + kw) of super-block sb; codes and multipliers stream
+// through a DEPTH-deep register ring per wave and never touch LDS; the int8 activation slice of a super-block
+// (M rows x KW k-blocks of 128 bytes) is fetched once per block, DEPTH iterations ahead, through the same ring
+// into one of two LDS buffers; one barrier per iteration; the k-workers' int32 sums are added through LDS
+// (integer sums: exact in any order) and scaled by alpha[m] * t[n], or written as int32 slabs when K is
+// also split over the grid (w8_finalize_kernel adds and scales those).
+// ------------------------------------------------------------------------------------------------------
+constexpr int W8S_PITCH = 17;      // LDS row pitch of the activation buffer in 16-byte units (16 rows + 1 pad)
+constexpr int W8S_KC = 8;          // 16-byte activation units per row and k-block
+
+template <int NT, int ZR, int AU>
+struct W8Stage {
+    u32x4 wq[NT];
+    uint32_t zq[ZR][NT];
+    u32x4 areg[AU];
+};
+
+template <int NT, int DEPTH, int ZR, int MAXW, int AU, int OUT>
+__global__ __launch_bounds__(MAXW * 64) void fq_w4a8_skinny_kernel(
+    const int8_t* __restrict__ Aq, const float* __restrict__ alpha, const u32x4* __restrict__ codes,
+    const uint8_t* __restrict__ z, const uint16_t* __restrict__ tstep, uint16_t* __restrict__ C,
+    int32_t* __restrict__ partial, int M, int N, int K, uint32_t g32, uint32_t g32_recip, int gp, int kw_n,
+    int grid_splits) {
+    constexpr int KC = W8S_KC, PITCH = W8S_PITCH;
+    typedef W8Stage<NT, ZR, AU> Stage;
+    extern __shared__ u32x4 lds[];   // two activation buffers [kw_n * KC][PITCH]; later the reduction
+
+    const int tid = threadIdx.x;
+    const int nthreads = blockDim.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int gi = wave / kw_n;
+    const int kw = wave - gi * kw_n;
+    const int ntiles = N / FQ_NTILE;
+    const int ngroups = (ntiles + NT - 1) / NT;
+    const int bgroups = (ngroups + gp - 1) / gp;      // blocks per grid split
+    const int bx = blockIdx.x % bgroups;
+    const int gsplit = blockIdx.x / bgroups;          // < grid_splits
+    const int ng = bx * gp + gi;
+    const bool gvalid = ng < ngroups;
+    const int KB = K / 128;
+    const int SB = (KB + kw_n - 1) / kw_n;            // super-blocks of kw_n k-blocks
+    const int n_it = gsplit < SB ? (SB - gsplit + grid_splits - 1) / grid_splits : 0;   // block-uniform
+    const int64_t kb_stride = (int64_t)ntiles * 64;   // records between consecutive k-blocks of a tile
+    const int ml = lane & 15, j = lane >> 4;
+    const int abuf_units = kw_n * KC * PITCH;
+
+    const char* wbase[NT];
+    const uint8_t* zbase[NT];
+    bool tvalid[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) {
+        const int tile = ng * NT + nt;
+        tvalid[nt] = gvalid && tile < ntiles;
+        const int tc = tvalid[nt] ? tile : 0;
+        wbase[nt] = reinterpret_cast<const char*>(codes + fq_rec(tc, 0, ntiles, 0));
+        zbase[nt] = z + (int64_t)tc * FQ_NTILE + ml;
+    }
+
+    // cooperative activation fetch: unit u = tid + r * nthreads covers row u / upr, unit column u % upr of the
+    // super-block (upr = kw_n * KC units of 16 int8 per row)
+    const int upr = kw_n * KC;
+    int a_row[AU], a_col[AU];
+#pragma unroll
+    for (int r = 0; r < AU; ++r) {
+        const int u = tid + r * nthreads;
+        a_row[r] = u / upr;
+        a_col[r] = u - a_row[r] * upr;
+    }
+
+    v4i acc[NT];
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) acc[nt] = v4i{0, 0, 0, 0};
+    const u32x4 zero4 = {0u, 0u, 0u, 0u};
+
+    auto load_act = [&](u32x4 (&areg)[AU], int it) {
+        const int64_t k0 = (int64_t)(gsplit + it * grid_splits) * kw_n * 128;
+#pragma unroll
+        for (int r = 0; r < AU; ++r) {
+            int64_t k = k0 + a_col[r] * 16;
+            k = k < K ? k : K - 16;                      // past the end (tail super-block): never multiplied
+            areg[r] = a_row[r] < M ? *reinterpret_cast<const u32x4*>(Aq + (int64_t)a_row[r] * K + k) : zero4;
+        }
+    };
+    auto store_act = [&](const u32x4 (&areg)[AU], int buf) {
+#pragma unroll
+        for (int r = 0; r < AU; ++r)
+            if (a_row[r] < 16) lds[buf * abuf_units + a_col[r] * PITCH + a_row[r]] = areg[r];
+    };
+    // stage `it`: this wave's codes and multipliers for iteration it, and the lane's share of the activations of
+    // iteration it + 1
+    auto load_stage = [&](Stage& sl, int it) {
+        int kb = (gsplit + it * grid_splits) * kw_n + kw;
+        kb = kb < KB ? kb : KB - 1;                      // tail super-block: idle workers re-read the last block
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) sl.wq[nt] = load_rec<4, true>(wbase[nt] + ((int64_t)kb * kb_stride + lane) * 16);
+#pragma unroll
+        for (int r = 0; r < ZR; ++r) {
+            // group of the 32-row step at hand (ZR == 1: the k-block lies inside one group; else the group of this
+            // lane's 16 rows of MFMA step r): an exact division by g / 32 as a multiplication by its rounded-up
+            // reciprocal (valid while step * (g / 32) < 2^32)
+            const uint32_t step = (uint32_t)kb * 4u + (ZR == 1 ? 0u : 2u * r + (uint32_t)(j >> 1));
+            const uint32_t grp = g32 == 1 ? step : __umulhi(step, g32_recip);
+            const int64_t zrow = (int64_t)grp * N;
+#pragma unroll
+            for (int nt = 0; nt < NT; ++nt) sl.zq[r][nt] = zbase[nt][zrow];
+        }
+        load_act(sl.areg, it + 1);
+    };
+    // one iteration: publish the next activations, read this iteration's fragments, convert and multiply
+    auto iterate = [&](const Stage& sl, int it) {
+        store_act(sl.areg, (it + 1) & 1);
+        const int kb = (gsplit + it * grid_splits) * kw_n + kw;
+        u32x4 af[2];
+        const u32x4* abuf = lds + (it & 1) * abuf_units + (kw * KC + j) * PITCH + ml;
+#pragma unroll
+        for (int T = 0; T < 2; ++T) af[T] = abuf[T * 4 * PITCH];
+        if (gvalid && kb < KB) {
+#pragma unroll
+            for (int T = 0; T < 2; ++T) {
+#pragma unroll
+                for (int nt = 0; nt < NT; ++nt) {
+                    const uint32_t zi = sl.zq[ZR == 1 ? 0 : T][nt];
+                    const uint32_t ci = (uint32_t)(0x8080 - (int)zi * 0x0808);   // 128 - 8 z in both bytes
+                    const u16x2v zz = {(uint16_t)zi, (uint16_t)zi};
+                    const u16x2v cc = {(uint16_t)ci, (uint16_t)ci};
+                    u32x4 wop;
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const uint32_t w = sl.wq[nt][2 * T + h];
+                        wop[2 * h] = w8_scale_bytes(w & 0x0f0f0f0fu, zz, cc);
+                        wop[2 * h + 1] = w8_scale_bytes((w >> 4) & 0x0f0f0f0fu, zz, cc);
+                    }
+                    acc[nt] = __builtin_amdgcn_mfma_i32_16x16x64_i8(bitcast<v4i>(wop), bitcast<v4i>(af[T]), acc[nt], 0, 0, 0);
+                }
+            }
+        }
+    };
+
+    if (n_it > 0) {
+        {   // activations of iteration 0
+            u32x4 a0[AU];
+            load_act(a0, 0);
+            store_act(a0, 0);
+        }
+        Stage ring[DEPTH];
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d)
+            if (d < n_it) load_stage(ring[d], d);
+        __syncthreads();
+        int it = 0;
+        for (; it + 2 * DEPTH <= n_it; it += DEPTH) {
+#pragma unroll
+            for (int d = 0; d < DEPTH; ++d) {
+                iterate(ring[d], it + d);
+                load_stage(ring[d], it + d + DEPTH);
+                __syncthreads();
+            }
+        }
+        // drain: at most 2 * DEPTH - 1 iterations are left, the first min(DEPTH, left) already loaded
+#pragma unroll
+        for (int d = 0; d < DEPTH; ++d) {
+            if (it + d < n_it) {
+                iterate(ring[d], it + d);
+                if (it + d + DEPTH < n_it) load_stage(ring[d], it + d + DEPTH);
+                __syncthreads();
+            }
+        }
+#pragma unroll
+        for (int d = 0; d < DEPTH - 1; ++d) {
+            if (it + d + DEPTH < n_it) {
+                iterate(ring[d], it + d + DEPTH);
+                __syncthreads();
+            }
+        }
+    }
+
+    // the k-workers' sums of each column group, added by all threads of the block (one result quad each)
+    auto store_quad = [&](const v4i& v, int group, int nt, int ln) {
+        const int mq = ln & 15, jq = ln >> 4;
+        const int tile = group * NT + nt;
+        if (mq >= M || group >= ngroups || tile >= ntiles) return;
+        const int64_t n = (int64_t)tile * FQ_NTILE + jq * 4;
+        if (grid_splits == 1) {
+            float tn[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) tn[i] = f16_bits_to_float(tstep[n + i]);
+            w8_store4<OUT>(C + (int64_t)mq * N + n, v, alpha[mq], tn);
+        } else {
+            *reinterpret_cast<v4i*>(partial + ((int64_t)gsplit * M + mq) * N + n) = v;
+        }
+    };
+    if (kw_n == 1) {
+#pragma unroll
+        for (int nt = 0; nt < NT; ++nt) store_quad(acc[nt], ng, nt, lane);
+        return;
+    }
+    v4i* red = reinterpret_cast<v4i*>(lds);
+#pragma unroll
+    for (int nt = 0; nt < NT; ++nt) red[(wave * NT + nt) * 64 + lane] = acc[nt];
+    __syncthreads();
+    const int nquads = gp * NT * 64;
+    for (int q = tid; q < nquads; q += nthreads) {
+        const int gq = q / (NT * 64);            // column group of the block
+        const int r = q - gq * (NT * 64);        // nt * 64 + lane inside the group
+        const v4i* src = red + (int64_t)gq * kw_n * NT * 64 + r;   // worker w: + w * NT * 64
+        v4i v = src[0];
+#pragma unroll 4
+        for (int w = 1; w < kw_n; ++w) v += src[w * NT * 64];
+        store_quad(v, bx * gp + gq, r >> 6, r & 63);
+    }
+}
+
 template <int OUT>
 __global__ __launch_bounds__(256) void w8_finalize_kernel(const int32_t* __restrict__ S, int splits,
                                                            const float* __restrict__ alpha,
@@ -503,11 +723,60 @@ __global__ __launch_bounds__(256) void w8_finalize_kernel(const int32_t* __restr
 
 struct w8_plan {
     int mt, splits, kb_per_split, nblocks_n, nblocks_m;
+    int small, gp, kw, au;      // small-M kernel (M <= 16): column groups x k-workers per block, activation units per lane
 };
 
+constexpr int W8S_NT = 3, W8S_DEPTH = 2, W8S_MAXW = 12;   // the small-M kernel that is compiled in
+
 w8_plan w8_plan_of(int64_t M, int64_t N, int64_t K) {
-    w8_plan p;
-    p.mt = M <= 16 ? 1 : (M <= 32 ? 2 : (M <= 64 ? 4 : 8));
+    w8_plan p = {};
+    if (M <= 16) {
+        // One block per compute unit, all resident at once; the block shape that fills the compute units most
+        // evenly, scored like the floating-point small-M plan (evenness of the fill squared, bytes in flight per
+        // compute unit up to 64 KiB, a second round of blocks, a split of K over the grid and lone k-workers cost).
+        const int ncu = fq_cu_count();
+        const int ntiles = (int)(N / FQ_NTILE);
+        const int KB = (int)(K / 128);
+        const int ngroups = (ntiles + W8S_NT - 1) / W8S_NT;
+        p.small = 1;
+        p.mt = 1;
+        double best = -1.0;
+        for (int gp = 1; gp <= W8S_MAXW; ++gp) {
+            int kw = W8S_MAXW / gp;
+            if (kw > KB) kw = KB;
+            const int need = (int)M * W8S_KC;
+            const int au = need <= 64 * gp ? 1 : (need <= 128 * gp ? 2 : 0);
+            if (au == 0 || kw < 1) continue;
+            const int64_t blocks = (ngroups + gp - 1) / gp;
+            const int SB = (KB + kw - 1) / kw;
+            int gs = 1;
+            if (blocks <= ncu / 2) gs = (int)(ncu / blocks);
+            if (gs > 8) gs = 8;
+            if (gs > SB) gs = SB;
+            const int64_t grid = blocks * gs;
+            const int64_t rounds = (grid + ncu - 1) / ncu;
+            const double eff = (double)ngroups * gs / (double)(rounds * ncu * gp);
+            const double inflight = (double)(gp * kw) * W8S_NT * W8S_DEPTH;   // KiB
+            double score = eff * eff * (inflight >= 64.0 ? 1.0 : sqrt(inflight / 64.0));
+            score /= 1.0 + 0.1 * (double)(rounds - 1);
+            if (au == 2) score *= 0.8;
+            if (gs > 1) score *= 0.8;
+            if (gp * kw < 6) score *= 0.85;
+            if (kw == 1) score *= 0.95;
+            if (score > best + 1e-9) {
+                best = score;
+                p.gp = gp;
+                p.kw = kw;
+                p.au = au;
+                p.splits = gs;
+            }
+        }
+        p.kb_per_split = 0;
+        p.nblocks_n = (ngroups + p.gp - 1) / p.gp;
+        p.nblocks_m = 1;
+        return p;
+    }
+    p.mt = M <= 32 ? 2 : (M <= 64 ? 4 : 8);
     const int ntiles = (int)(N / FQ_NTILE);
     p.nblocks_n = (ntiles + W8_WAVES * W8_NT - 1) / (W8_WAVES * W8_NT);
     p.nblocks_m = (int)((M + p.mt * 16 - 1) / (p.mt * 16));
@@ -547,13 +816,34 @@ void w8_launch(const w8_plan& p, int g, const int8_t* Aq, const float* alpha, co
 #undef W8_GO
 }
 
+template <int OUT, int ZR, int AU>
+int w8_launch_small(const w8_plan& p, int g, const int8_t* Aq, const float* alpha, const void* codes, const uint8_t* z,
+                    const void* tstep, void* C, int32_t* partial, int64_t M, int64_t N, int64_t K, hipStream_t stream) {
+    const size_t lds_act = (size_t)2 * p.kw * W8S_KC * W8S_PITCH * 16;
+    const size_t lds_red = (size_t)p.gp * p.kw * W8S_NT * 64 * 16;
+    const size_t lds = lds_act > lds_red ? lds_act : lds_red;       // at most 36 KiB
+    const uint32_t g32 = (uint32_t)(g / 32);
+    const uint32_t g32_recip = (uint32_t)((((uint64_t)1 << 32) + g32 - 1) / g32);   // unused when g32 == 1
+    hipLaunchKernelGGL((fq_w4a8_skinny_kernel<W8S_NT, W8S_DEPTH, ZR, W8S_MAXW, AU, OUT>),
+                       dim3((unsigned)(p.nblocks_n * p.splits)), dim3((unsigned)(p.gp * p.kw * 64)), lds, stream, Aq,
+                       alpha, (const u32x4*)codes, z, (const uint16_t*)tstep, (uint16_t*)C, partial, (int)M, (int)N,
+                       (int)K, g32, g32_recip, p.gp, p.kw, p.splits);
+    return FQ_OK;
+}
+
 template <int OUT>
 int w8_gemm(const int8_t* Aq, const float* alpha, int64_t M, int64_t N, int64_t K, const void* codes, const uint8_t* z,
             const void* tstep, int g, void* C, void* workspace, hipStream_t stream) {
     const w8_plan p = w8_plan_of(M, N, K);
     int32_t* partial = (int32_t*)workspace;
+    if (p.small) {
+        const bool zr1 = g % 128 == 0;
+        if (zr1 && p.au == 1) w8_launch_small<OUT, 1, 1>(p, g, Aq, alpha, codes, z, tstep, C, partial, M, N, K, stream);
+        else if (zr1) w8_launch_small<OUT, 1, 2>(p, g, Aq, alpha, codes, z, tstep, C, partial, M, N, K, stream);
+        else if (p.au == 1) w8_launch_small<OUT, 2, 1>(p, g, Aq, alpha, codes, z, tstep, C, partial, M, N, K, stream);
+        else w8_launch_small<OUT, 2, 2>(p, g, Aq, alpha, codes, z, tstep, C, partial, M, N, K, stream);
+    } else
     switch (p.mt) {
-        case 1: w8_launch<1, OUT>(p, g, Aq, alpha, codes, z, tstep, C, partial, M, N, K, stream); break;
         case 2: w8_launch<2, OUT>(p, g, Aq, alpha, codes, z, tstep, C, partial, M, N, K, stream); break;
         case 4: w8_launch<4, OUT>(p, g, Aq, alpha, codes, z, tstep, C, partial, M, N, K, stream); break;
         default: w8_launch<8, OUT>(p, g, Aq, alpha, codes, z, tstep, C, partial, M, N, K, stream); break;

@@ -110,6 +110,26 @@ def test_product_matches_oracle(M, dtype, g):
     print(f"  w4a8 M={M} {dtype} g={g or K}: rel err {rel:.2e}", flush=True)
 
 
+@pytest.mark.parametrize("M,K,N,g", [(7, 4096, 192, 64), (16, 8192, 48, 128), (3, 2048, 1040, 0), (1, 128, 16, 128),
+                                     (12, 1536, 6000, 96)])
+def test_small_m_block_shapes(M, K, N, g):
+    """The small-M kernel of the integer path on shapes that drive its plan to its corners: few column tiles
+    (K split over the grid, int32 slabs summed by the second kernel), a single tile and a single k-block, one group
+    per column, many column groups per block, two activation units per lane (M = 16 with one column group)."""
+    from paper_2308_09723_amd import fq
+    torch = torch_mod()
+    N -= N % 16
+    W = workloads.weights_gaussian(K, N, seed=300 + M, outlier_prob=2e-3)
+    codes, z, t, q_ref, z_ref, t_ref = _quantize_weights(W, g)
+    for dtype in ("f16", "bf16"):
+        A = workloads.activations(M, K, dtype, 310 + M)
+        Aq, alpha, a_ref, alpha_ref = _quantize_acts(A, dtype)
+        out_dt = torch.float16 if dtype == "f16" else torch.bfloat16
+        C = from_dev_act(fq.gemm_w4a8(Aq, alpha, codes, z, t, g, out_dt), dtype)
+        _, C_ref = oracle.gemm_ref_int(a_ref, alpha_ref, q_ref, z_ref, t_ref)
+        _check_product(C, C_ref, dtype, f"small-M M={M} K={K} N={N} g={g}")
+
+
 def test_product_extreme_sums_and_one_hot_rows():
     """All activations +-127 against all codes -7 with z = 16 (the largest sums), and one-hot activation rows
     that read back single rows of q * z (every row of two k-blocks)."""

@@ -277,8 +277,9 @@ def main():
         out["roofline_w4a8"] = {
             "bound": "mfma", "unit": "TOP/s", "peak": INT8_PEAK_TOPS, "achieved": w8["qkv_M2048"]["TOPs"],
             "frac": w8["qkv_M2048"]["frac_of_int8_peak"],
-            "kernel": "fq_gemm_w4a8_kernel (v_mfma_i32_16x16x64_i8), the integer path: int8 activations x int4 weights "
-                      "with integer group scales; the product alone, activations quantised beforehand",
+            "kernel": "fq_gemm_w4a8_kernel (v_mfma_i32_16x16x64_i8; M = 8: fq_w4a8_skinny_kernel), the integer path: int8 "
+                      "activations x int4 weights with integer group scales; the product alone, activations quantised "
+                      "beforehand",
             "workload": "QKV 12288 x 36864, g=128, M = 2048 (and M = 8 against the HBM peak)",
             "cases": w8,
             "mfma_ceiling": mfma_ceiling(torch, fq, int8=True),

@@ -446,7 +446,7 @@ __global__ void fq_zero_ints_kernel(int* p, int n) {
 // instead reads the packed buffer four bytes at a time and computes a record address per weight.)
 #define FQ_QE_PANEL 128
 #define FQ_QE_PITCH 130   // binary16 elements per LDS row: rows 8 apart fall 8 banks apart
-template <int BITS>
+template <int BITS, bool EXACT32>
 __global__ __launch_bounds__(256) void fq_quant_error_kernel(const uint16_t* __restrict__ W,
                                                              const uint32_t* __restrict__ codes,
                                                              const uint16_t* __restrict__ scales, int64_t K,
@@ -463,6 +463,12 @@ __global__ __launch_bounds__(256) void fq_quant_error_kernel(const uint16_t* __r
     const int64_t panels_n = (N + FQ_QE_PANEL - 1) / FQ_QE_PANEL;
     const int64_t panels = panels_n * ((K + FQ_QE_PANEL - 1) / FQ_QE_PANEL);
     double sse = 0.0, mx = 0.0;
+    float mxf = 0.0f;
+    // With binary16 scales the error w - q s of one weight is formed in binary32, where it is exact: q s has at
+    // most 19 significant bits, and when q != 0, |w| >= s / 2, so w, q s and their difference are multiples of
+    // 2^(exponent of s - 11) below 2^(exponent of s + 8): 19 bits.  (q = 0: the error is w itself.)  Only its
+    // square is accumulated in binary64; the largest magnitude is a binary32 maximum.  A third of the binary64
+    // instructions per weight that the all-binary64 form needs, with the same bits in both results.
     // a block walks panels blockIdx.x, blockIdx.x + gridDim.x, ... (one partial result per block)
     for (int64_t pnl = blockIdx.x; pnl < panels; pnl += gridDim.x) {
     const int64_t n0 = (pnl % panels_n) * FQ_QE_PANEL;
@@ -493,23 +499,31 @@ __global__ __launch_bounds__(256) void fq_quant_error_kernel(const uint16_t* __r
 #pragma unroll
         for (int t = 0; t < STEPS; ++t) {
             const int krel = kbl * KBLK + FQ_KSTEP * t + 8 * j;
-            const double sv = (double)scale_bits_to_float(scales[((k0 + krel) / g) * N + n], sfmt);
+            const float sf = scale_bits_to_float(scales[((k0 + krel) / g) * N + n], sfmt);
+            const double sv = (double)sf;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 int q;
                 if (BITS == 4) q = (int)((d[t] >> (4 * fq_nibble_slot(e))) & 0xfu) - 8;
                 else if (BITS == 3) q = (int)fq_get3(d, t, e) - 4;
                 else q = (int)((d[2 * t + (e >> 2)] >> (8 * (e & 3))) & 0xffu) - 128;
-                const double wv = (double)half_bits_to_float(wp16[(krel + e) * FQ_QE_PITCH + col]);
-                const double err = wv - (double)q * sv;
-                sse += err * err;
-                mx = fmax(mx, fabs(err));
+                const float wf = half_bits_to_float(wp16[(krel + e) * FQ_QE_PITCH + col]);
+                if constexpr (EXACT32) {
+                    const float ef = __builtin_fmaf(-(float)q, sf, wf);
+                    const double err = (double)ef;
+                    sse += err * err;
+                    mxf = fmaxf(mxf, fabsf(ef));
+                } else {
+                    const double err = (double)wf - (double)q * sv;
+                    sse += err * err;
+                    mx = fmax(mx, fabs(err));
+                }
             }
         }
     }
     }
     sh_s[tid] = sse;
-    sh_m[tid] = mx;
+    sh_m[tid] = fmax(mx, (double)mxf);
     __syncthreads();
     for (int w = 128; w > 0; w >>= 1) {
         if (tid < w) {
@@ -699,15 +713,14 @@ int fq_launch_quant_error(const void* W, int64_t K, int64_t N, int bits, int g, 
     double* part = out + 2;
     const int64_t nblk = fq_quant_error_blocks(K, N);
     dim3 grid((unsigned)nblk);
-    if (bits == 3)
-        hipLaunchKernelGGL(fq_quant_error_kernel<3>, grid, dim3(256), 0, stream, (const uint16_t*)W,
-                           (const uint32_t*)codes, (const uint16_t*)scales, K, N, g, sfmt, part, nblk);
-    else if (bits == 4)
-        hipLaunchKernelGGL(fq_quant_error_kernel<4>, grid, dim3(256), 0, stream, (const uint16_t*)W,
-                           (const uint32_t*)codes, (const uint16_t*)scales, K, N, g, sfmt, part, nblk);
-    else
-        hipLaunchKernelGGL(fq_quant_error_kernel<8>, grid, dim3(256), 0, stream, (const uint16_t*)W,
-                           (const uint32_t*)codes, (const uint16_t*)scales, K, N, g, sfmt, part, nblk);
+#define FQ_QE_GO(B_, X_)                                                                                    \
+    hipLaunchKernelGGL((fq_quant_error_kernel<B_, X_>), grid, dim3(256), 0, stream, (const uint16_t*)W,     \
+                       (const uint32_t*)codes, (const uint16_t*)scales, K, N, g, sfmt, part, nblk)
+    const bool x32 = sfmt == FQ_SCALE_F16;
+    if (bits == 3) { if (x32) FQ_QE_GO(3, true); else FQ_QE_GO(3, false); }
+    else if (bits == 4) { if (x32) FQ_QE_GO(4, true); else FQ_QE_GO(4, false); }
+    else { if (x32) FQ_QE_GO(8, true); else FQ_QE_GO(8, false); }
+#undef FQ_QE_GO
     hipLaunchKernelGGL(fq_quant_error_final_kernel, dim3(1), dim3(256), 0, stream, (const double*)part, nblk, out);
     if (hipGetLastError() != hipSuccess) return FQ_ERR_HIP;
     if (hipMemcpyAsync(out_host2, out, sizeof(double) * 2, hipMemcpyDeviceToHost, stream) != hipSuccess)

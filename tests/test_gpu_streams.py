@@ -128,6 +128,40 @@ def test_products_captured_in_a_graph_replay_to_the_same_bits():
         assert torch.equal(again, ref[0])
 
 
+def test_integer_path_captured_in_a_graph_replays_to_the_same_bits():
+    """fq_quantize_act_i8 and fq_gemm_w4a8 enqueue kernels only as well: the activation quantiser and the products
+    of the small-M kernel (with a split of K over the grid) and of the tiled kernel captured in one graph."""
+    from paper_2308_09723_amd import fq
+    torch = torch_mod()
+    K, N, g = 2048, 1536, 128
+    W = workloads.weights_gaussian(K, N, 4500, outlier_prob=1e-3)
+    codes, z, t = fq.quantize_w4a8(torch.from_numpy(W).cuda(), g)
+    cases = []
+    for M in (6, 200):
+        A = to_dev_act(workloads.activations(M, K, "f16", 4500 + M), "f16")
+        Aq, alpha = fq.quantize_act_i8(A)
+        ref = fq.gemm_w4a8(Aq, alpha, codes, z, t, g, torch.float16).clone()
+        ws = torch.empty(max(16, fq.gemm_w4a8_workspace_bytes(M, N, K, g)), dtype=torch.uint8, device="cuda")
+        cases.append((A, torch.empty_like(Aq), torch.empty_like(alpha), ws, ref, torch.empty_like(ref)))
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        stream = torch.cuda.current_stream().cuda_stream
+        for A, Aq, alpha, ws, ref, C in cases:
+            M = A.shape[0]
+            assert fq.quantize_act_i8_raw(A.data_ptr(), fq.FQ_F16, M, K, Aq.data_ptr(), alpha.data_ptr(), stream) == fq.FQ_OK
+            fq.gemm_w4a8(Aq, alpha, codes, z, t, g, torch.float16, out=C, workspace=ws)
+    for replay in range(3):
+        for _, Aq, _, _, _, C in cases:
+            C.fill_(7.0)
+            Aq.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for A, _, _, _, ref, C in cases:
+            assert torch.equal(ref, C), f"replay {replay}, M={A.shape[0]}"
+
+
 @pytest.mark.parametrize("nbytes", [16, 1 << 20, (1 << 22) + 4096 + 48, 256 * 768 * 16 * 4 + 16])
 def test_stream_read_probe_reads_every_word_once(nbytes):
     """The measurement helper that bench.py times as the streaming-read ceiling: the XOR of its per-block

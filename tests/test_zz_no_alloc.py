@@ -57,6 +57,51 @@ def test_noalloc_matches_gemm_twice_second_smaller(K, N, bits, g, dtype, Ms):
         _pair(fq, torch, codes, scales, K, N, bits, g, M, dtype, seed=100 + i)
 
 
+def test_noalloc_captured_in_a_graph_replays_to_the_same_bits():
+    """The callers the entry point is for: captured in a HIP graph (nothing is allocated and only kernels are
+    enqueued, so the capture succeeds), replayed three times with eager work and synchronisations between the
+    replays, each replay compared with fq_gemm's result."""
+    from paper_2308_09723_amd import fq
+    torch = torch_mod()
+    K, N, bits, g = 4096, 1024, 4, 128
+    W = workloads.weights_gaussian(K, N, seed=97, outlier_prob=1e-3)
+    codes, scales = fq.quantize(torch.from_numpy(W).cuda(), bits, g)
+    cases = []
+    for M, dtype in ((8, "f16"), (40, "bf16")):
+        A = workloads.activations(M, K, dtype, 120 + M)
+        if dtype == "f16":
+            Ad = torch.from_numpy(A).cuda()
+        else:
+            Ad = torch.from_numpy(workloads.bf16_bits(A).view(np.int16)).cuda().view(torch.bfloat16)
+        act = fq.FQ_F16 if dtype == "f16" else fq.FQ_BF16
+        assert 0 < fq.gemm_workspace_bytes_for(M, N, K, bits, g, act) <= fq.gemm_noalloc_scratch_bytes()
+        ref = fq.gemm(Ad, codes, scales, bits, g)
+        C = torch.empty_like(ref)
+        # one eager call first: the library looks its scratch up on the first call on a device
+        stream = torch.cuda.current_stream().cuda_stream
+        assert fq.gemm_noalloc_raw(Ad.data_ptr(), act, M, N, K, codes.data_ptr(), scales.data_ptr(), bits, g,
+                                   C.data_ptr(), stream) == fq.FQ_OK
+        cases.append((Ad, act, M, ref, C))
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        stream = torch.cuda.current_stream().cuda_stream
+        for Ad, act, M, ref, C in cases:
+            st = fq.gemm_noalloc_raw(Ad.data_ptr(), act, M, N, K, codes.data_ptr(), scales.data_ptr(), bits, g,
+                                     C.data_ptr(), stream)
+            assert st == fq.FQ_OK, fq.status_string(st)
+    for replay in range(3):
+        for _, _, _, _, C in cases:
+            C.fill_(7.0)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for _, _, M, ref, C in cases:
+            assert torch.equal(C.view(torch.int16), ref.view(torch.int16)), f"replay {replay}, M={M}"
+        again = fq.gemm(cases[0][0], codes, scales, bits, g)      # eager work between the replays
+        assert torch.equal(again, cases[0][3])
+
+
 def test_noalloc_rejects_what_does_not_fit_and_bad_arguments():
     from paper_2308_09723_amd import fq
     torch = torch_mod()

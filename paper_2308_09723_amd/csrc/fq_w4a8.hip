@@ -165,9 +165,22 @@ __global__ __launch_bounds__(256) void w8_act_quant_kernel(const uint16_t* __res
     __shared__ uint32_t red[4];
     const int64_t r = blockIdx.x;
     const uint16_t* src = A + r * K;
+    // rows of whole 16-byte units at 16-byte aligned addresses are read eight values and written eight bytes per
+    // lane (with one value per lane the kernel is bound by the number of its memory instructions)
+    const bool wide = (K & 7) == 0 && ((uintptr_t)A & 15) == 0 && ((uintptr_t)Aq & 7) == 0;
+    const int64_t units = wide ? K >> 3 : 0;
     uint32_t m = 0;
-    for (int64_t k = threadIdx.x; k < K; k += 256) {
-        const uint32_t v = src[k] & 0x7fffu;      // magnitudes of one format order like their bit patterns
+    for (int64_t u = threadIdx.x; u < units; u += 256) {
+        const u32x4 v = reinterpret_cast<const u32x4*>(src)[u];
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const uint32_t a0 = v[i] & 0x7fffu, a1 = (v[i] >> 16) & 0x7fffu;   // magnitudes of one format order
+            m = a0 > m ? a0 : m;                                                // like their bit patterns
+            m = a1 > m ? a1 : m;
+        }
+    }
+    for (int64_t k = units * 8 + threadIdx.x; k < K; k += 256) {
+        const uint32_t v = src[k] & 0x7fffu;
         m = v > m ? v : m;
     }
 #pragma unroll
@@ -186,11 +199,21 @@ __global__ __launch_bounds__(256) void w8_act_quant_kernel(const uint16_t* __res
     if (__builtin_fmaf(0.5f * ALEVELS, al, -amax) < 0.0f) al = __uint_as_float(__float_as_uint(al) + 1u);   // next value up
     if (threadIdx.x == 0) alpha[r] = al;
     int8_t* dst = Aq + r * K;
-    for (int64_t k = threadIdx.x; k < K; k += 256) {
+    auto code = [&](uint16_t bits) -> uint32_t {
         int q = 0;
-        if (al != 0.0f) q = (int)fminf(fmaxf(rintf(__fdiv_rn(act_to_float<ACT>(src[k]), al)), -127.0f), 127.0f);
-        dst[k] = (int8_t)q;
+        if (al != 0.0f) q = (int)fminf(fmaxf(rintf(__fdiv_rn(act_to_float<ACT>(bits), al)), -127.0f), 127.0f);
+        return (uint32_t)q & 0xffu;
+    };
+    for (int64_t u = threadIdx.x; u < units; u += 256) {
+        const u32x4 v = reinterpret_cast<const u32x4*>(src)[u];
+        u32x2 o;
+#pragma unroll
+        for (int h = 0; h < 2; ++h)
+            o[h] = code((uint16_t)v[2 * h]) | (code((uint16_t)(v[2 * h] >> 16)) << 8) |
+                   (code((uint16_t)v[2 * h + 1]) << 16) | (code((uint16_t)(v[2 * h + 1] >> 16)) << 24);
+        reinterpret_cast<u32x2*>(dst)[u] = o;
     }
+    for (int64_t k = units * 8 + threadIdx.x; k < K; k += 256) dst[k] = (int8_t)code(src[k]);
 }
 
 // ------------------------------------------------------------------------------------------------------

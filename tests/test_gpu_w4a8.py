@@ -90,6 +90,14 @@ def test_activation_quantiser(dtype):
     _quantize_acts(A, dtype)
 
 
+@pytest.mark.parametrize("K", [8, 1000, 1003, 12288 + 40, 7])
+def test_activation_quantiser_row_lengths(K):
+    """Rows of whole 16-byte units (eight values per lane), rows that are not (one value per lane), rows shorter
+    than a block."""
+    for dtype in ("f16", "bf16"):
+        _quantize_acts(workloads.activations(9, K, dtype, 700 + K), dtype)
+
+
 @pytest.mark.parametrize("g", [32, 64, 96, 128, 0])
 @pytest.mark.parametrize("M,dtype", [(1, "f16"), (5, "bf16"), (16, "f16"), (24, "bf16"), (50, "f16"), (130, "bf16"),
                                      (300, "f16")])

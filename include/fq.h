@@ -335,7 +335,7 @@ int fq_stream_read_probe(const void* buf, size_t bytes, void* sink, void* stream
  *                   they are
  *   sink       out  device, >= fq_mfma_rate_probe_sink_bytes() bytes (one binary32 checksum per thread)
  * One launch performs fq_mfma_rate_probe_flops(iterations, int8) operations (2 per multiply-add).
- * Errors: FQ_ERR_INVALID_ARG (NULL pointer, iterations outside 1 .. 2^20), FQ_ERR_WORKSPACE (a buffer is too
+ * Errors: FQ_ERR_INVALID_ARG (NULL pointer, iterations outside 1 .. 2^16: a launch stays below a second), FQ_ERR_WORKSPACE (a buffer is too
  * small), FQ_ERR_HIP.
  */
 size_t fq_mfma_rate_probe_operand_bytes(void);

@@ -324,7 +324,7 @@ double fq_mfma_rate_probe_flops(int iterations, int int8) {
 
 int fq_mfma_rate_probe(const void* operands, size_t operand_bytes, void* sink, size_t sink_bytes, int iterations,
                        int lds_reads, int int8, void* stream) {
-    if (!operands || !sink || iterations <= 0 || iterations > (1 << 20)) return FQ_ERR_INVALID_ARG;
+    if (!operands || !sink || iterations <= 0 || iterations > (1 << 16)) return FQ_ERR_INVALID_ARG;
     if (operand_bytes < fq_mfma_probe_operand_bytes() || sink_bytes < fq_mfma_probe_sink_bytes()) return FQ_ERR_WORKSPACE;
     return fq_launch_mfma_rate_probe(operands, sink, iterations, lds_reads != 0, int8 != 0, (hipStream_t)stream);
 }
